@@ -1,0 +1,349 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests re-types an oracle formula or re-calls an oracle routine as its own
+reference: the expected values are closed forms, invariants, brute force, numpy's LAPACK
+routines on tiny inputs, or numbers printed in the paper.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import tsr_oracle as orc
+
+RNG = np.random.default_rng(1234)
+
+
+def orthonormal(rows, cols, key):
+    return si.orthonormal(rows, cols, key).numpy()
+
+
+def rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+# ------------------------------------------------------------------ products
+@pytest.mark.parametrize("M,N,K", [(3, 5, 7), (8, 2, 11), (1, 1, 1), (13, 17, 4)])
+def test_matmul_variants_match_numpy(M, N, K):
+    A = RNG.standard_normal((M, K)); B = RNG.standard_normal((K, N))
+    assert np.allclose(orc.matmul(A, B), A @ B, rtol=0, atol=1e-13)
+    At = np.ascontiguousarray(A.T); Bt = np.ascontiguousarray(B.T)
+    assert np.allclose(orc.matmul(At, B, ta=True), A @ B, rtol=0, atol=1e-13)
+    assert np.allclose(orc.matmul(A, Bt, tb=True), A @ B, rtol=0, atol=1e-13)
+
+
+def test_matmul_by_hand():
+    A = np.array([[1., 2.], [3., 4.], [5., 6.]])
+    B = np.array([[1., 0., -1.], [2., 1., 0.]])
+    expect = np.array([[5., 2., -1.], [11., 4., -3.], [17., 6., -5.]])
+    assert np.array_equal(orc.matmul(A, B), expect)
+
+
+# ------------------------------------------------------------------ project / lift
+@pytest.mark.parametrize("m,n,r", [(24, 40, 5), (40, 24, 7), (9, 9, 9)])
+def test_project_of_lift_is_identity(m, n, r):
+    # U^T (U C0 V^T) V = C0 for orthonormal U, V
+    U = orthonormal(m, r, 11); V = orthonormal(n, r, 12)
+    C0 = RNG.standard_normal((r, r))
+    G = U @ C0 @ V.T
+    assert rel(orc.project_core(G, U, V), C0) < 1e-13
+
+
+def test_project_matches_definition_elementwise():
+    # C[a,b] = sum_ij U[i,a] G[i,j] V[j,b], brute force with Python loops
+    m, n, r = 6, 5, 3
+    G = RNG.standard_normal((m, n)); U = RNG.standard_normal((m, r)); V = RNG.standard_normal((n, r))
+    C = np.zeros((r, r))
+    for a in range(r):
+        for b in range(r):
+            for i in range(m):
+                for j in range(n):
+                    C[a, b] += U[i, a] * G[i, j] * V[j, b]
+    assert np.allclose(orc.project_core(G, U, V), C, rtol=0, atol=1e-13)
+
+
+def test_project_idempotent_and_linear():
+    m, n, r, K = 30, 22, 6, 5
+    U = orthonormal(m, r, 21); V = orthonormal(n, r, 22)
+    Gs = [RNG.standard_normal((m, n)) for _ in range(K)]
+    C = orc.project_core(Gs[0], U, V)
+    again = orc.project_core(U @ C @ V.T, U, V)
+    assert rel(again, C) < 1e-13
+    mean_of_cores = orc.core_average([orc.project_core(G, U, V) for G in Gs])
+    core_of_mean = orc.project_core(sum(Gs) / K, U, V)
+    assert rel(mean_of_cores, core_of_mean) < 1e-13
+
+
+def test_core_average_is_arithmetic_mean():
+    cores = [np.full((3, 3), float(i)) for i in (1, 2, 6)]
+    assert np.allclose(orc.core_average(cores), np.full((3, 3), 3.0))
+    one = RNG.standard_normal((4, 4))
+    assert np.array_equal(orc.core_average([one]), one)
+
+
+# ------------------------------------------------------------------ Adam on the core
+def test_adam_first_step_closed_form():
+    # m0 = v0 = 0  =>  D = g / (|g| + eps) elementwise; values around eps make the
+    # placement of eps (outside the root, after bias correction) matter
+    g = np.array([[1.0, -2.5, 3e-8], [-1e-8, 0.0, 7e-9], [1e-3, -4e-12, 5.0]])
+    M = np.zeros_like(g); Vm = np.zeros_like(g)
+    D = orc.adam_core(g, M, Vm, t=1, beta1=0.9, beta2=0.999, eps=1e-8)
+    assert np.allclose(D, g / (np.abs(g) + 1e-8), rtol=1e-12, atol=0)
+    assert np.allclose(M, 0.1 * g, rtol=1e-12) and np.allclose(Vm, 0.001 * g * g, rtol=1e-9)
+
+
+def test_adam_constant_core_every_step():
+    # constant core g: m_t = (1-b1^t) g, v_t = (1-b2^t) g^2, so D_t = g/(|g|+eps) for all t
+    g = RNG.standard_normal((5, 5)) * np.logspace(-9, 1, 25).reshape(5, 5)
+    M = np.zeros_like(g); Vm = np.zeros_like(g)
+    for t in range(1, 40):
+        D = orc.adam_core(g, M, Vm, t=t, beta1=0.9, beta2=0.999, eps=1e-8)
+        assert np.allclose(D, g / (np.abs(g) + 1e-8), rtol=1e-10, atol=0), t
+        assert np.allclose(M, (1 - 0.9 ** t) * g, rtol=1e-10)
+        assert np.allclose(Vm, (1 - 0.999 ** t) * g * g, rtol=1e-9)
+
+
+def test_adam_two_steps_by_hand():
+    # scalar case worked by hand: g1 = 1, g2 = -1, b1 = 0.5, b2 = 0.5, eps = 0
+    M = np.zeros((1, 1)); Vm = np.zeros((1, 1))
+    D1 = orc.adam_core(np.array([[1.0]]), M, Vm, t=1, beta1=0.5, beta2=0.5, eps=0.0)
+    assert D1[0, 0] == pytest.approx(1.0)
+    D2 = orc.adam_core(np.array([[-1.0]]), M, Vm, t=2, beta1=0.5, beta2=0.5, eps=0.0)
+    # m2 = .5*.5 - .5 = -.25 ; v2 = .5*.5 + .5 = .75 ; mhat = -.25/.75 ; vhat = .75/.75 = 1
+    assert M[0, 0] == pytest.approx(-0.25) and Vm[0, 0] == pytest.approx(0.75)
+    assert D2[0, 0] == pytest.approx(-1.0 / 3.0)
+
+
+def dense_adamw(W, grads, lr, wd, b1, b2, eps):
+    """Dense AdamW exactly as the background section writes it (moment recursions, bias
+    correction, decoupled decay)."""
+    m = np.zeros_like(W); v = np.zeros_like(W)
+    for t, g in enumerate(grads, start=1):
+        m = b1 * m + (1 - b1) * g
+        v = b2 * v + (1 - b2) * g * g
+        W = W - lr * ((m / (1 - b1 ** t)) / (np.sqrt(v / (1 - b2 ** t)) + eps) + wd * W)
+    return W
+
+
+def test_identity_bases_reduce_to_dense_adamw():
+    n = 7
+    I = np.eye(n)
+    W = RNG.standard_normal((n, n)); grads = [RNG.standard_normal((n, n)) for _ in range(6)]
+    expect = dense_adamw(W.copy(), grads, 1e-2, 0.1, 0.9, 0.999, 1e-8)
+    M = np.zeros((n, n)); Vm = np.zeros((n, n)); Wo = W.copy()
+    for t, g in enumerate(grads, start=1):
+        orc.tsr_adam_step(Wo, [g], I, I, M, Vm, t, lr=1e-2, wd=0.1)
+    assert rel(Wo, expect) < 1e-13
+
+
+# ------------------------------------------------------------------ lift + apply
+def test_first_step_weight_closed_form():
+    m, n, r = 20, 31, 4
+    U = orthonormal(m, r, 31); V = orthonormal(n, r, 32)
+    G = RNG.standard_normal((m, n)); W0 = RNG.standard_normal((m, n)) * 0.02
+    g = U.T @ G @ V
+    expect = W0 - 1e-3 * U @ (g / (np.abs(g) + 1e-8)) @ V.T
+    W = W0.copy(); M = np.zeros((r, r)); Vm = np.zeros((r, r))
+    orc.tsr_adam_step(W, [G], U, V, M, Vm, 1, lr=1e-3)
+    assert rel(W, expect) < 1e-13
+
+
+def test_constant_gradient_T_steps_closed_form():
+    m, n, r, T = 12, 9, 3, 25
+    U = orthonormal(m, r, 41); V = orthonormal(n, r, 42)
+    G = RNG.standard_normal((m, n)); W0 = RNG.standard_normal((m, n))
+    g = U.T @ G @ V
+    expect = W0 - T * 1e-3 * U @ (g / (np.abs(g) + 1e-8)) @ V.T
+    W = W0.copy(); M = np.zeros((r, r)); Vm = np.zeros((r, r))
+    for t in range(1, T + 1):
+        orc.tsr_adam_step(W, [G], U, V, M, Vm, t, lr=1e-3)
+    assert rel(W, expect) < 1e-12
+
+
+def test_weight_decay_only():
+    # zero gradient => D = 0 => W_T = (1 - lr*wd)^T W0
+    m, n, r, T = 8, 10, 2, 7
+    U = orthonormal(m, r, 51); V = orthonormal(n, r, 52)
+    W0 = RNG.standard_normal((m, n)); W = W0.copy()
+    M = np.zeros((r, r)); Vm = np.zeros((r, r))
+    for t in range(1, T + 1):
+        orc.tsr_adam_step(W, [np.zeros((m, n))], U, V, M, Vm, t, lr=0.1, wd=0.3)
+    assert rel(W, (1 - 0.03) ** T * W0) < 1e-13
+
+
+def test_apply_uses_pre_update_weights_and_scale():
+    m, n, r = 6, 4, 2
+    U = RNG.standard_normal((m, r)); V = RNG.standard_normal((n, r)); D = RNG.standard_normal((r, r))
+    W0 = RNG.standard_normal((m, n))
+    expect = W0 - 0.5 * (0.75 * (U @ D @ V.T) + 0.2 * W0)
+    W = orc.backproject_apply(W0.copy(), U, V, D, lr=0.5, wd=0.2, scale=0.75)
+    assert rel(W, expect) < 1e-14
+
+
+def test_sign_flips_of_bases_leave_weights_unchanged():
+    m, n, r, T = 16, 12, 4, 5
+    U = orthonormal(m, r, 61); V = orthonormal(n, r, 62)
+    su = np.array([1, -1, -1, 1.0]); sv = np.array([-1, 1, -1, 1.0])
+    grads = [RNG.standard_normal((m, n)) for _ in range(T)]
+    W0 = RNG.standard_normal((m, n))
+    outs = []
+    for (Uu, Vv) in ((U, V), (U * su, V * sv)):
+        W = W0.copy(); M = np.zeros((r, r)); Vm = np.zeros((r, r))
+        for t, g in enumerate(grads, start=1):
+            orc.tsr_adam_step(W, [g], Uu, Vv, M, Vm, t, lr=1e-2)
+        outs.append(W)
+    assert rel(outs[1], outs[0]) < 1e-13
+
+
+def test_sgd_core_recursion():
+    # Algorithm 2: m_t = (1-beta) sum_s beta^(t-s) C_s ; D = m
+    cores = [RNG.standard_normal((3, 3)) for _ in range(5)]
+    M = np.zeros((3, 3))
+    for t, c in enumerate(cores, start=1):
+        D = orc.sgd_core(c, M, beta=0.8)
+        expect = sum(0.2 * 0.8 ** (t - s) * cores[s - 1] for s in range(1, t + 1))
+        assert np.allclose(D, expect, rtol=1e-12, atol=1e-15)
+        assert np.array_equal(D, M)
+
+
+# ------------------------------------------------------------------ thin QR
+@pytest.mark.parametrize("rows,k", [(30, 30), (50, 7), (9, 1), (64, 20)])
+def test_householder_qr_invariants(rows, k):
+    Y = RNG.standard_normal((rows, k))
+    Q, R = orc.householder_qr(Y)
+    assert np.abs(Q.T @ Q - np.eye(k)).max() < 1e-12
+    assert rel(Q @ (Q.T @ Y), Y) < 1e-12
+    assert rel(Q @ R, Y) < 1e-12
+    assert np.abs(np.tril(R, -1)).max() == 0.0
+    # against LAPACK: R is unique up to row signs
+    Rl = np.linalg.qr(Y)[1]
+    assert np.allclose(np.abs(R), np.abs(Rl), rtol=1e-9, atol=1e-12)
+
+
+def test_householder_qr_rank_deficient_still_orthonormal():
+    rows, k, rank = 40, 10, 4
+    Y = RNG.standard_normal((rows, rank)) @ RNG.standard_normal((rank, k))
+    Y[:, 3] = 0.0
+    Q, _ = orc.householder_qr(Y)
+    assert np.abs(Q.T @ Q - np.eye(k)).max() < 1e-12
+    assert rel(Q @ (Q.T @ Y), Y) < 1e-12
+    Qz, _ = orc.householder_qr(np.zeros((12, 5)))
+    assert np.abs(Qz.T @ Qz - np.eye(5)).max() < 1e-12
+
+
+# ------------------------------------------------------------------ small SVD
+@pytest.mark.parametrize("k,n", [(5, 5), (6, 19), (1, 8), (12, 40)])
+def test_jacobi_svd_against_lapack_and_invariants(k, n):
+    B = RNG.standard_normal((k, n))
+    Ut, S, Vt, sweeps = orc.jacobi_svd(B)
+    assert sweeps < 30
+    assert rel(Ut @ np.diag(S) @ Vt.T, B) < 1e-13
+    assert np.abs(Ut.T @ Ut - np.eye(k)).max() < 1e-13
+    assert np.abs(Vt.T @ Vt - np.eye(k)).max() < 1e-13
+    assert np.all(np.diff(S) <= 0)
+    assert np.allclose(S, np.linalg.svd(B, compute_uv=False), rtol=1e-12, atol=1e-14)
+
+
+def test_jacobi_svd_known_singular_values():
+    k, n = 4, 9
+    X = orthonormal(k, k, 71); Z = orthonormal(n, k, 72)
+    s = np.array([3.0, 2.0, 0.5, 0.0])
+    Ut, S, Vt, _ = orc.jacobi_svd(X @ np.diag(s) @ Z.T)
+    assert np.allclose(S, s, atol=1e-14)
+    for j in range(3):  # singular vectors up to sign
+        assert abs(abs(Ut[:, j] @ X[:, j]) - 1) < 1e-12
+        assert abs(abs(Vt[:, j] @ Z[:, j]) - 1) < 1e-12
+
+
+def test_full_svd_both_orientations():
+    for shape in ((7, 11), (11, 7)):
+        G = RNG.standard_normal(shape)
+        U, S, V = orc.full_svd(G)
+        assert rel(U @ np.diag(S) @ V.T, G) < 1e-13
+        assert np.allclose(S, np.linalg.svd(G, compute_uv=False), rtol=1e-12)
+
+
+# ------------------------------------------------------------------ rSVD refresh
+def projector(X):
+    return X @ X.T
+
+
+@pytest.mark.parametrize("m,n,r,p,q", [(60, 45, 6, 4, 1), (45, 60, 6, 4, 0), (80, 80, 10, 5, 2)])
+def test_rsvd_recovers_exact_rank_r_subspace(m, n, r, p, q):
+    G, A, B = si.exact_lowrank(m, n, r, 81)
+    G, A, B = G.numpy(), A.numpy(), B.numpy()
+    Om = si.omega(n, r + p, 82).numpy()
+    U, V, S = orc.refresh_rsvd(G, Om, r, p, q)
+    assert np.linalg.norm(projector(U) - projector(A)) < 1e-10
+    assert np.linalg.norm(projector(V) - projector(B)) < 1e-10
+    assert np.abs(U.T @ U - np.eye(r)).max() < 1e-12
+    assert np.abs(V.T @ V - np.eye(r)).max() < 1e-12
+    assert np.allclose(S[:r], np.linspace(2.0, 1.0, r), rtol=1e-11)
+    assert np.abs(S[r:]).max() < 1e-12
+
+
+@pytest.mark.parametrize("m,n,r,q", [(12, 20, 4, 0), (12, 20, 4, 1), (20, 12, 5, 2)])
+def test_rsvd_with_full_sketch_is_truncated_svd(m, n, r, q):
+    # k = min(m, n): range(Q) is everything, so the refresh is the exact truncated SVD
+    G = RNG.standard_normal((m, n))
+    k = min(m, n)
+    Om = si.omega(n, k, 91).numpy()
+    U, V, S = orc.refresh_rsvd(G, Om, r, k - r, q)
+    Ub, Sb, Vb = orc.full_svd(G)                     # brute force: Jacobi on G itself
+    Ul, Sl, Vlt = np.linalg.svd(G, full_matrices=False)  # LAPACK
+    assert np.allclose(S, Sl, rtol=1e-11)
+    assert np.allclose(Sb, Sl, rtol=1e-11)
+    for ref_u, ref_v in ((Ub[:, :r], Vb[:, :r]), (Ul[:, :r], Vlt.T[:, :r])):
+        assert np.linalg.norm(projector(U) - projector(ref_u)) < 1e-9
+        assert np.linalg.norm(projector(V) - projector(ref_v)) < 1e-9
+    # U S V^T is the best rank-r approximation: its error is the tail of the spectrum
+    err = np.linalg.norm(G - U @ np.diag(S[:r]) @ V.T)
+    assert err == pytest.approx(np.sqrt((Sl[r:] ** 2).sum()), rel=1e-9)
+
+
+def test_rsvd_power_iterations_do_not_change_full_rank_capture_but_help_decay():
+    # slowly decaying spectrum: more power iterations can only tighten the captured energy
+    m, n, r, p = 70, 90, 8, 4
+    X = orthonormal(m, 40, 101); Z = orthonormal(n, 40, 102)
+    s = 1.0 / np.sqrt(np.arange(1, 41))
+    G = X @ np.diag(s) @ Z.T
+    Om = si.omega(n, r + p, 103).numpy()
+    best = np.sqrt((s[r:] ** 2).sum())
+    errs = []
+    for q in (0, 1, 3):
+        U, V, S = orc.refresh_rsvd(G, Om, r, p, q)
+        errs.append(np.linalg.norm(G - U @ (U.T @ G @ V) @ V.T))
+        assert errs[-1] >= best * (1 - 1e-9)
+    assert errs[2] <= errs[1] <= errs[0]
+    assert errs[2] < 1.05 * best
+
+
+def test_rsvd_independent_of_orth_basis():
+    # post-multiplying Q by a rotation (another valid output of orth) leaves U U^T and
+    # V V^T unchanged: composed here from the oracle's pieces with q = 0
+    m, n, r, p = 40, 33, 5, 3
+    k = r + p
+    G = RNG.standard_normal((m, n)); Om = si.omega(n, k, 111).numpy()
+    U0, V0, _ = orc.refresh_rsvd(G, Om, r, p, 0)
+    Q, _ = orc.householder_qr(G @ Om)
+    Rot = orthonormal(k, k, 112)
+    Q2 = Q @ Rot
+    Ut, S, Vt, _ = orc.jacobi_svd(Q2.T @ G)
+    U1 = Q2 @ Ut[:, :r]; V1 = Vt[:, :r]
+    assert np.linalg.norm(projector(U1) - projector(U0)) < 1e-9
+    assert np.linalg.norm(projector(V1) - projector(V0)) < 1e-9
+
+
+def test_rsvd_rejects_oversized_sketch():
+    G = RNG.standard_normal((10, 8))
+    with pytest.raises(ValueError):
+        orc.refresh_rsvd(G, np.zeros((8, 9)), 6, 3, 1)
+
+
+def test_rsvd_returns_final_q():
+    m, n, r, p = 30, 26, 4, 3
+    G = RNG.standard_normal((m, n)); Om = si.omega(n, r + p, 121).numpy()
+    U, V, S, Q = orc.refresh_rsvd(G, Om, r, p, 1, return_q=True)
+    assert np.abs(Q.T @ Q - np.eye(r + p)).max() < 1e-12
+    # U lies in range(Q); S are the singular values of Q^T G
+    assert rel(Q @ (Q.T @ U), U) < 1e-12
+    assert np.allclose(S, np.linalg.svd(Q.T @ G, compute_uv=False), rtol=1e-11)
