@@ -1,0 +1,174 @@
+/*
+ * tsr.h - C ABI of the MI355X (gfx950) TSR-Adam per-matrix optimizer library.
+ *
+ * The calls follow the paper's statement of the update for one matrix block
+ * W (m x n) with orthonormal bases U (m x r), V (n x r) and r x r core moments
+ * (Algorithm 1, Sections 3.3-3.6):
+ *
+ *   refresh   (every K steps)  (U, V) <- randomized SVD of the gradient      tsr_refresh_rsvd
+ *   project                    C = U^T G V                                    tsr_project_core
+ *   average   (all-reduce stand-in on one GPU)  Cbar = mean_i C_i             tsr_core_average
+ *   Adam on the core           m, v, D = mhat / (sqrt(vhat) + eps)            tsr_adam_core
+ *   lift + apply               W <- W - lr (scale U D V^T + wd W)             tsr_backproject_apply
+ *   all blocks of a model in grouped launches                                 tsr_plan_* / tsr_step_batched /
+ *                                                                             tsr_refresh_batched
+ *
+ * Conventions
+ *   - Every matrix is dense row-major.  G and W take an explicit leading dimension
+ *     (elements between consecutive rows); U, V, Omega, C, M, Vm, D are contiguous
+ *     (leading dimension = number of columns).
+ *   - Every data pointer is a DEVICE pointer unless the comment says "host".  The caller
+ *     owns every buffer, including the workspace; the library allocates no device memory
+ *     and keeps no hidden device state.  Workspaces must be 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on that stream and return; results are ready once the stream has
+ *     drained.  Calls on one stream are ordered.
+ *   - Arguments are validated on the host before anything is launched; on error nothing
+ *     is enqueued and a negative tsr_status is returned.  Non-finite inputs are not
+ *     detected: they propagate into the outputs.
+ *   - Fast paths need 16-byte aligned G / W base pointers and leading dimensions that
+ *     are multiples of 8 elements; anything else is still computed correctly, slower.
+ */
+#ifndef TSR_H
+#define TSR_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tsr_status {
+    TSR_OK = 0,
+    TSR_INVALID_ARG = -1,         /* null pointer, misaligned workspace, t < 1 ...          */
+    TSR_BAD_SHAPE = -2,           /* m, n, r <= 0, r > min(m, n), r + p > min(m, n), ld < n */
+    TSR_BAD_DTYPE = -3,
+    TSR_WORKSPACE_TOO_SMALL = -4,
+    TSR_HIP_ERROR = -5            /* a HIP runtime call failed (see tsr_last_hip_error)     */
+} tsr_status;
+
+/* Storage type of the gradient G (everything else is fp32). */
+typedef enum tsr_dtype { TSR_F32 = 0, TSR_BF16 = 1 } tsr_dtype;
+
+/* Arithmetic of the dense contractions.  Both accumulate in fp32 on the matrix cores.
+ *   TSR_PREC_SPLIT  fp32 operands are split into two bf16 pieces (hi + lo) and the three
+ *                   leading cross products are summed: about 2^-17 relative per product,
+ *                   for the "fp32 path" (cores / weights within 1e-4 of an fp64 result).
+ *   TSR_PREC_BF16   operands that stream from the big matrices (G, V in G V; T, V in
+ *                   T V^T) are rounded once to bf16: for bf16 gradients (within 1e-2).
+ * The refresh always uses split arithmetic (three pieces where orthogonality depends on it). */
+typedef enum tsr_precision { TSR_PREC_SPLIT = 0, TSR_PREC_BF16 = 1 } tsr_precision;
+
+/* One matrix block of a model, for the batched calls.  All pointers are device pointers. */
+typedef struct tsr_matrix_desc {
+    const void* G;          /* gradients: n_workers consecutive m x n matrices             */
+    int g_dtype;            /* tsr_dtype of G                                               */
+    int m, n, r;
+    long long ldg;          /* leading dimension of each G, elements                        */
+    long long g_stride;     /* elements between consecutive workers' G (unused if 1 worker) */
+    float* W;               /* m x n weights, updated in place                              */
+    long long ldw;
+    float* U;               /* m x r basis                                                  */
+    float* V;               /* n x r basis                                                  */
+    float* M;               /* r x r first moment, in place                                 */
+    float* Vm;              /* r x r second moment, in place                                */
+    float* C;               /* r x r averaged core (output)                                 */
+    float* D;               /* r x r normalized core update (output)                        */
+} tsr_matrix_desc;
+
+typedef struct tsr_hyper {
+    float lr, wd, beta1, beta2, eps;
+    float scale;            /* multiplies U D V^T before lr (1 = Algorithm 1)               */
+} tsr_hyper;
+
+const char* tsr_status_string(int status);
+/* hipError_t value of the last failing HIP call on this host thread (0 if none). */
+int tsr_last_hip_error(void);
+/* Number of GPUs HIP reports (0 without a GPU or driver); touches no device. */
+int tsr_device_count(void);
+
+/* ---------------------------------------------------------------- project (Section 3.3)
+ * C <- alpha * U^T G V  (+ C if accumulate != 0).   Algorithm 1, projection line.
+ * G m x n (dtype g, leading dimension ldg), U m x r, V n x r, C r x r.
+ * alpha = 1/K with accumulate over K calls forms the K-worker average with no extra pass.
+ * Workspace: tsr_project_workspace_bytes(m, n, r) bytes. */
+size_t tsr_project_workspace_bytes(int m, int n, int r);
+int tsr_project_core(const void* G, int g_dtype, int m, int n, long long ldg,
+                     const float* U, const float* V, int r,
+                     float alpha, int accumulate, float* C, int precision,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------- average (all-reduce stand-in)
+ * Cbar = (1/K) sum_i Cs[i], Cs = K consecutive r x r cores, summed in worker order.
+ * Stands in, on one GPU, for the all-reduce-average of Algorithm 1.  Cbar may alias Cs. */
+int tsr_core_average(const float* Cs, int K, int r, float* Cbar, void* stream);
+
+/* ---------------------------------------------------------------- Adam on the core (Section 3.4)
+ * m <- beta1 m + (1-beta1) C ; v <- beta2 v + (1-beta2) C.C ;
+ * D = (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps).   t >= 1 is the global step count.
+ * C, M, Vm, D hold `count` floats each (count = r*r for one block; any count works, so a
+ * caller may pass all cores of a model laid out back to back).  D may alias C. */
+int tsr_adam_core(const float* C, float* M, float* Vm, float* D, long long count, int t,
+                  float beta1, float beta2, float eps, void* stream);
+
+/* Momentum variant (Algorithm 2): m <- beta m + (1-beta) C ; D = m. */
+int tsr_sgd_core(const float* C, float* M, float* D, long long count, float beta, void* stream);
+
+/* ---------------------------------------------------------------- lift + apply (Section 3.4)
+ * W <- W - lr * (scale * U D V^T + wd * W), in place.  Last two update lines of Algorithm 1.
+ * Workspace: tsr_backproject_workspace_bytes(m, n, r). */
+size_t tsr_backproject_workspace_bytes(int m, int n, int r);
+int tsr_backproject_apply(float* W, int m, int n, long long ldw,
+                          const float* U, const float* V, const float* D, int r,
+                          float lr, float wd, float scale, int precision,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------- refresh (Section 3.5)
+ * Randomized-SVD refresh of the bases for one worker (refresh branch of Algorithm 1):
+ *   Y = G Omega ; Q = orth(Y) ; q times { Yrow = G^T Q ; Qrow = orth(Yrow) ; Y = G Qrow ;
+ *   Q = orth(Y) } ; B = Q^T G ; B = Ut S Vt^T ; U = Q Ut[:, :r] ; V = Vt[:, :r].
+ * Omega is n x (r+p), N(0,1), supplied by the caller (the paper shares it by RNG seed).
+ * Requires r + p <= min(m, n).  Writes U (m x r), V (n x r) and, if sigma != NULL, the
+ * r + p singular values of B in descending order.
+ * orth is a Cholesky-based thin QR repeated twice with fp64 factorization of the Gram
+ * matrix; a Gram matrix that is singular to working precision (a gradient of rank below
+ * r + p, e.g. all zeros) gives zero columns in place of the undetermined directions.
+ * Workspace: tsr_refresh_workspace_bytes(m, n, r, p). */
+size_t tsr_refresh_workspace_bytes(int m, int n, int r, int p);
+int tsr_refresh_rsvd(const void* G, int g_dtype, int m, int n, long long ldg,
+                     const float* Omega, int r, int p, int q,
+                     float* U, float* V, float* sigma,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------- batched all-layers calls
+ * A plan holds, in caller-provided device workspace, the grouped-launch tables for a fixed
+ * list of blocks, so that every phase of the step (and of the refresh) is a handful of
+ * launches over all blocks.  `descs` is a HOST array; it is copied.  n_workers >= 1
+ * gradients per block are projected and their cores averaged (the data-parallel stand-in).
+ * p is the refresh oversampling (the plan reserves refresh scratch only if with_refresh).
+ * tsr_plan_create synchronizes the stream once (table upload); the other calls do not. */
+typedef struct tsr_plan tsr_plan;
+size_t tsr_plan_workspace_bytes(const tsr_matrix_desc* descs, int count, int n_workers,
+                                int with_refresh, int p);
+int tsr_plan_create(const tsr_matrix_desc* descs, int count, int n_workers, int precision,
+                    int with_refresh, int p,
+                    void* ws, size_t ws_bytes, void* stream, tsr_plan** plan_out);
+void tsr_plan_destroy(tsr_plan* plan);
+
+/* One TSR-Adam step (no refresh) for every block of the plan:
+ * project all workers -> average -> Adam on the cores -> lift + apply.  t >= 1. */
+int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream);
+
+/* Refresh (U, V) of every block from worker 0's gradient.  Omegas is a HOST array of
+ * `count` device pointers (block i: n_i x (r_i + p)). */
+int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void* stream);
+
+/* Bytes a worker would put on the wire per step for the plan's blocks: the r x r cores
+ * (4 bytes each) and the dense gradients they replace (at bytes_per_dense_element). */
+void tsr_plan_payload_bytes(const tsr_plan* plan, int bytes_per_dense_element,
+                            long long* core_bytes, long long* dense_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSR_H */

@@ -1,0 +1,707 @@
+// C ABI of the TSR-Adam library: argument validation, workspace carving, and the launch
+// sequences that compose the per-step path and the randomized-SVD refresh out of the grouped
+// GEMM family and the small kernels.  No device memory is allocated here: everything lives in
+// the caller's buffers and workspace.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/tsr.h"
+#include "gemm.h"
+#include "small.h"
+
+using namespace tsr;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+inline int hip_fail(hipError_t e) {
+    g_last_hip = (int)e;
+    return TSR_HIP_ERROR;
+}
+#define TSR_HIP(call)                                  \
+    do {                                               \
+        hipError_t e__ = (call);                       \
+        if (e__ != hipSuccess) return hip_fail(e__);   \
+    } while (0)
+#define TSR_TRY(call)                    \
+    do {                                 \
+        int s__ = (call);                \
+        if (s__ != TSR_OK) return s__;   \
+    } while (0)
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Bump allocator over the caller's workspace.  With base == nullptr it only measures.
+struct Arena {
+    char* base;
+    size_t off = 0;
+    explicit Arena(void* b) : base((char*)b) {}
+    template <typename T> T* take(size_t count) {
+        off = align_up(off);
+        T* p = base ? (T*)(base + off) : (T*)nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+    size_t used() const { return align_up(off); }
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ------------------------------------------------------------------ GEMM stages
+struct LogicalGemm {
+    const void* A; const float* B;
+    long long lda, ldb;
+    int M, N, K;
+    float* out; long long ldc;
+    int group = -1;                // consecutive entries with the same group >= 0 are summed into `out`
+};
+
+struct GemmStage {
+    GemmVariant var{};
+    std::vector<GemmProblem> probs;
+    std::vector<GemmTile> tiles;
+    std::vector<ReduceProblem> reduces;
+    int max_reduce_elems = 0;
+    bool direct = true;
+    int tiles_m = 0, tiles_n = 0, ksplit = 1;      // single-problem decode
+    const GemmProblem* d_probs = nullptr;
+    const GemmTile* d_tiles = nullptr;
+    const ReduceProblem* d_reduces = nullptr;
+    bool empty() const { return probs.empty(); }
+};
+
+// Decide k-splits, carve partial buffers from `ar`, and list the tiles.
+// want_tiles: keep splitting k while the launch has fewer tiles than this.
+void build_stage(GemmStage& st, const GemmVariant& var, const std::vector<LogicalGemm>& gemms, Arena& ar,
+                 int want_tiles = 512) {
+    st = GemmStage{};
+    st.var = var;
+    if (gemms.empty()) return;
+    long long base_tiles = 0;
+    bool shared_out = false;
+    for (size_t i = 0; i < gemms.size(); ++i) {
+        base_tiles += (long long)ceil_div(gemms[i].M, GEMM_BM) * ceil_div(gemms[i].N, GEMM_BN);
+        if (i > 0 && gemms[i].group >= 0 && gemms[i].group == gemms[i - 1].group) shared_out = true;
+    }
+    int want_split = (int)std::max<long long>(1, want_tiles / std::max<long long>(1, base_tiles));
+    std::vector<int> ksplit(gemms.size()), kchunk(gemms.size());
+    bool any_split = false;
+    for (size_t i = 0; i < gemms.size(); ++i) {
+        const int K = gemms[i].K;
+        int s = std::min(want_split, std::max(1, K / 256));
+        int chunk = ceil_div(ceil_div(K, s), 32) * 32;
+        s = ceil_div(K, chunk);
+        ksplit[i] = s; kchunk[i] = chunk;
+        if (s > 1) any_split = true;
+    }
+    st.direct = !(any_split || shared_out);
+    st.probs.resize(gemms.size());
+    size_t i = 0;
+    while (i < gemms.size()) {
+        // [i, e) = consecutive gemms summed into one output; their partials are one buffer
+        size_t e = i + 1;
+        while (e < gemms.size() && gemms[i].group >= 0 && gemms[e].group == gemms[i].group) ++e;
+        const size_t mn = (size_t)gemms[i].M * gemms[i].N;
+        float* part = nullptr;
+        int group_splits = 0;
+        if (!st.direct) {
+            for (size_t j = i; j < e; ++j) group_splits += ksplit[j];
+            part = ar.take<float>(mn * group_splits);
+            ReduceProblem r{};
+            r.part = part; r.out = gemms[i].out; r.stride = (long long)mn; r.ldc = gemms[i].ldc;
+            r.M = gemms[i].M; r.N = gemms[i].N; r.splits = group_splits;
+            st.reduces.push_back(r);
+            st.max_reduce_elems = std::max(st.max_reduce_elems, (int)std::min<size_t>(mn, 1u << 30));
+        }
+        int prefix = 0;
+        for (size_t j = i; j < e; ++j) {
+            const LogicalGemm& g = gemms[j];
+            GemmProblem& p = st.probs[j];
+            p.A = g.A; p.B = g.B; p.lda = g.lda; p.ldb = g.ldb;
+            p.M = g.M; p.N = g.N; p.K = g.K;
+            if (st.direct) {
+                p.C = g.out; p.ldc = g.ldc; p.c_split_stride = 0;
+                p.kchunk = std::max(32, ceil_div(g.K, 32) * 32);
+                ksplit[j] = 1;
+            } else {
+                p.C = part ? part + mn * prefix : nullptr;
+                p.ldc = g.N; p.c_split_stride = (long long)mn; p.kchunk = kchunk[j];
+                prefix += ksplit[j];
+            }
+            const int tmn = ceil_div(g.M, GEMM_BM), tnn = ceil_div(g.N, GEMM_BN);
+            for (int ks = 0; ks < ksplit[j]; ++ks)
+                for (int tm = 0; tm < tmn; ++tm)
+                    for (int tn = 0; tn < tnn; ++tn) st.tiles.push_back(GemmTile{(int)j, tm, tn, ks});
+            st.tiles_m = tmn; st.tiles_n = tnn; st.ksplit = ksplit[j];
+        }
+        i = e;
+    }
+}
+
+int run_stage(const GemmStage& st, bool grouped, float alpha, float beta, hipStream_t stream) {
+    if (st.empty()) return TSR_OK;
+    GemmLaunch L{};
+    L.n_tiles = (int)st.tiles.size();
+    if (grouped) {
+        L.probs = st.d_probs; L.tiles = st.d_tiles;
+    } else {
+        L.single = st.probs[0];
+        L.tiles_m = st.tiles_m; L.tiles_n = st.tiles_n; L.ksplit = st.ksplit;
+    }
+    if (st.direct) {
+        L.alpha = alpha; L.beta = beta;
+        TSR_HIP(launch_gemm(L, st.var, stream));
+    } else {
+        L.alpha = 1.0f; L.beta = 0.0f;
+        TSR_HIP(launch_gemm(L, st.var, stream));
+        TSR_HIP(launch_splitk_reduce(grouped ? st.d_reduces : nullptr, grouped ? nullptr : &st.reduces[0],
+                                     (int)st.reduces.size(), st.max_reduce_elems, alpha, beta, stream));
+    }
+    return TSR_OK;
+}
+
+// Device tables, carved from the arena after every data buffer and mirrored in `host`
+// (host[0] corresponds to arena offset `first`) so that one copy uploads them all.
+struct Uploader {
+    std::vector<char> host;
+    size_t first = (size_t)-1;
+    template <typename T> const T* put(const std::vector<T>& v, Arena& ar) {
+        T* d = ar.take<T>(v.size());
+        if (ar.base) {
+            const size_t o = (size_t)((char*)d - ar.base);
+            if (first == (size_t)-1) first = o;
+            const size_t rel = o - first;
+            if (host.size() < rel + v.size() * sizeof(T)) host.resize(rel + v.size() * sizeof(T));
+            if (!v.empty()) memcpy(host.data() + rel, v.data(), v.size() * sizeof(T));
+        }
+        return d;
+    }
+};
+
+void upload_stage(GemmStage& st, Arena& ar, Uploader& up) {
+    if (st.empty()) return;
+    st.d_probs = up.put(st.probs, ar);
+    st.d_tiles = up.put(st.tiles, ar);
+    if (!st.direct) st.d_reduces = up.put(st.reduces, ar);
+}
+
+inline GemmVariant variant(int aks, int bks, int abf, int pa, int pb) {
+    GemmVariant v; v.a_kstrided = aks; v.b_kstrided = bks; v.a_bf16 = abf; v.a_pieces = abf ? 1 : pa; v.b_pieces = pb;
+    return v;
+}
+
+// ------------------------------------------------------------------ validation helpers
+bool aligned256(const void* p) { return ((uintptr_t)p % ALIGN) == 0; }
+
+int check_block(int m, int n, int r) {
+    if (m <= 0 || n <= 0 || r <= 0) return TSR_BAD_SHAPE;
+    if (r > m || r > n) return TSR_BAD_SHAPE;
+    return TSR_OK;
+}
+int check_dtype(int d) { return (d == TSR_F32 || d == TSR_BF16) ? TSR_OK : TSR_BAD_DTYPE; }
+int check_prec(int p) { return (p == TSR_PREC_SPLIT || p == TSR_PREC_BF16) ? TSR_OK : TSR_INVALID_ARG; }
+
+// ------------------------------------------------------------------ per-step programs
+struct BlockView {          // what the step needs to know about one block
+    const void* G; int g_dtype; int m, n, r; long long ldg, g_stride;
+    float* W; long long ldw; float* U; float* V; float* M; float* Vm; float* C; float* D;
+};
+
+struct ProjectProgram {
+    GemmStage gv[2];        // P = G V, index = dtype of G
+    GemmStage utp;          // C = U^T P (summed over workers and k-splits)
+};
+
+// P buffers: one m x r fp32 per (block, worker), carved from `ar`.
+void build_project(ProjectProgram& pg, const std::vector<BlockView>& blocks, int n_workers, int prec, Arena& ar) {
+    std::vector<LogicalGemm> gv[2], utp;
+    int group = 0;
+    for (const BlockView& b : blocks) {
+        const int esz = (b.g_dtype == TSR_BF16) ? 2 : 4;
+        ++group;
+        for (int w = 0; w < n_workers; ++w) {
+            float* P = ar.take<float>((size_t)b.m * b.r);
+            const char* Gw = b.G ? (const char*)b.G + (size_t)w * b.g_stride * esz : nullptr;
+            gv[b.g_dtype].push_back(LogicalGemm{Gw, b.V, b.ldg, b.r, b.m, b.r, b.n, P, b.r});
+            utp.push_back(LogicalGemm{b.U, P, b.r, b.r, b.r, b.r, b.m, b.C, b.r, group});
+        }
+    }
+    const int pv = (prec == TSR_PREC_BF16) ? 1 : 2;
+    build_stage(pg.gv[TSR_F32], variant(0, 1, 0, pv, pv), gv[TSR_F32], ar);
+    build_stage(pg.gv[TSR_BF16], variant(0, 1, 1, 1, pv), gv[TSR_BF16], ar);
+    build_stage(pg.utp, variant(1, 1, 0, pv, pv), utp, ar);
+}
+
+int run_project(const ProjectProgram& pg, bool grouped, float alpha, float beta, hipStream_t s) {
+    TSR_TRY(run_stage(pg.gv[TSR_F32], grouped, 1.0f, 0.0f, s));
+    TSR_TRY(run_stage(pg.gv[TSR_BF16], grouped, 1.0f, 0.0f, s));
+    return run_stage(pg.utp, grouped, alpha, beta, s);
+}
+
+struct LiftProgram {
+    GemmStage ud;           // T = U D
+    GemmStage tvt;          // W = beta W + alpha T V^T
+};
+
+void build_lift(LiftProgram& lp, const std::vector<BlockView>& blocks, int prec, Arena& ar) {
+    std::vector<LogicalGemm> ud, tvt;
+    for (const BlockView& b : blocks) {
+        float* T = ar.take<float>((size_t)b.m * b.r);
+        ud.push_back(LogicalGemm{b.U, b.D, b.r, b.r, b.m, b.r, b.r, T, b.r});
+        tvt.push_back(LogicalGemm{T, b.V, b.r, b.r, b.m, b.n, b.r, b.W, b.ldw});
+    }
+    const int pv = (prec == TSR_PREC_BF16) ? 1 : 2;
+    build_stage(lp.ud, variant(0, 1, 0, pv, pv), ud, ar, /*want_tiles=*/1);
+    build_stage(lp.tvt, variant(0, 0, 0, pv, pv), tvt, ar, /*want_tiles=*/1);
+}
+
+int run_lift(const LiftProgram& lp, bool grouped, float lr, float wd, float scale, hipStream_t s) {
+    TSR_TRY(run_stage(lp.ud, grouped, 1.0f, 0.0f, s));
+    // W - lr (scale dW + wd W) = (1 - lr wd) W + (-lr scale) dW
+    return run_stage(lp.tvt, grouped, -lr * scale, 1.0f - lr * wd, s);
+}
+
+// ------------------------------------------------------------------ refresh program
+struct RefreshBlock {
+    const void* G; int g_dtype; int m, n, r, k; long long ldg;
+    float* U; float* V; float* sigma;
+    // workspace
+    float *Y, *Yalt, *Z, *Zalt, *S, *Rinv, *XrT, *GrT;
+    double *work, *R1, *Rtot, *Gacc;
+};
+
+struct OrthProgram {        // X (rows x k) -> orthonormal basis, in place, Xalt as scratch
+    GemmStage gram1, q1, gram2, q2;
+    std::vector<CholBlock> chol1, chol2;
+    const CholBlock* d_chol1 = nullptr; const CholBlock* d_chol2 = nullptr;
+};
+
+struct RefreshProgram {
+    std::vector<RefreshBlock> blocks;
+    GemmStage sketch[2];    // Y = G Omega
+    GemmStage gtq[2];       // Z = G^T Y'   (Y' = current Q held in Y)
+    GemmStage gq[2];        // Y = G Z'
+    OrthProgram orthY, orthZ;
+    std::vector<JacobiBlock> jac; const JacobiBlock* d_jac = nullptr;
+    GemmStage uout, vout;
+};
+
+void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool on_rows_m, Arena& ar) {
+    std::vector<LogicalGemm> g1, q1, g2, q2;
+    op.chol1.clear(); op.chol2.clear();
+    for (const RefreshBlock& b : blocks) {
+        const int rows = on_rows_m ? b.m : b.n;
+        float* X = on_rows_m ? b.Y : b.Z;
+        float* Xalt = on_rows_m ? b.Yalt : b.Zalt;
+        const int k = b.k;
+        g1.push_back(LogicalGemm{X, X, k, k, k, k, rows, b.S, k});
+        q1.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
+        g2.push_back(LogicalGemm{Xalt, Xalt, k, k, k, k, rows, b.S, k});
+        q2.push_back(LogicalGemm{Xalt, b.Rinv, k, k, rows, k, k, X, k});
+        op.chol1.push_back(CholBlock{b.S, b.Rinv, nullptr, b.R1, b.work, k});
+        op.chol2.push_back(CholBlock{b.S, b.Rinv, b.R1, b.Rtot, b.work, k});
+    }
+    build_stage(op.gram1, variant(1, 1, 0, 2, 2), g1, ar);
+    build_stage(op.q1, variant(0, 1, 0, 2, 2), q1, ar, 1);
+    build_stage(op.gram2, variant(1, 1, 0, 3, 3), g2, ar);
+    build_stage(op.q2, variant(0, 1, 0, 3, 3), q2, ar, 1);
+}
+
+int run_orth(const OrthProgram& op, bool grouped, hipStream_t s) {
+    const int nb = (int)op.chol1.size();
+    TSR_TRY(run_stage(op.gram1, grouped, 1.0f, 0.0f, s));
+    TSR_HIP(launch_chol_inv(grouped ? op.d_chol1 : nullptr, grouped ? nullptr : &op.chol1[0], nb, 1e-6, s));
+    TSR_TRY(run_stage(op.q1, grouped, 1.0f, 0.0f, s));
+    TSR_TRY(run_stage(op.gram2, grouped, 1.0f, 0.0f, s));
+    TSR_HIP(launch_chol_inv(grouped ? op.d_chol2 : nullptr, grouped ? nullptr : &op.chol2[0], nb, 1e-6, s));
+    return run_stage(op.q2, grouped, 1.0f, 0.0f, s);
+}
+
+// Carves every refresh buffer from `ar` and builds all stages.  Omega pointers may be null
+// at build time (they are patched in before the launch).
+void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, const float* const* omegas, int p,
+                   float* const* sigmas, Arena& ar) {
+    rp.blocks.clear();
+    for (size_t i = 0; i < views.size(); ++i) {
+        const BlockView& v = views[i];
+        RefreshBlock b{};
+        b.G = v.G; b.g_dtype = v.g_dtype; b.m = v.m; b.n = v.n; b.r = v.r; b.k = v.r + p; b.ldg = v.ldg;
+        b.U = v.U; b.V = v.V; b.sigma = sigmas ? sigmas[i] : nullptr;
+        const size_t k = (size_t)b.k;
+        b.Y = ar.take<float>((size_t)b.m * k); b.Yalt = ar.take<float>((size_t)b.m * k);
+        b.Z = ar.take<float>((size_t)b.n * k); b.Zalt = ar.take<float>((size_t)b.n * k);
+        b.S = ar.take<float>(k * k); b.Rinv = ar.take<float>(k * k);
+        b.XrT = ar.take<float>((size_t)b.r * k); b.GrT = ar.take<float>((size_t)b.r * k);
+        b.work = ar.take<double>(2 * k * k); b.R1 = ar.take<double>(k * k);
+        b.Rtot = ar.take<double>(k * k); b.Gacc = ar.take<double>(k * k);
+        rp.blocks.push_back(b);
+    }
+    std::vector<LogicalGemm> sk[2], gtq[2], gq[2], uo, vo;
+    rp.jac.clear();
+    for (size_t i = 0; i < rp.blocks.size(); ++i) {
+        const RefreshBlock& b = rp.blocks[i];
+        const float* om = omegas ? omegas[i] : nullptr;
+        sk[b.g_dtype].push_back(LogicalGemm{b.G, om, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
+        gtq[b.g_dtype].push_back(LogicalGemm{b.G, b.Y, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
+        gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Z, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
+        uo.push_back(LogicalGemm{b.Y, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
+        vo.push_back(LogicalGemm{b.Z, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
+        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.XrT, b.GrT, b.sigma, b.k, b.r});
+    }
+    for (int d = 0; d < 2; ++d) {
+        build_stage(rp.sketch[d], variant(0, 1, d, 2, 2), sk[d], ar);
+        build_stage(rp.gtq[d], variant(1, 1, d, 2, 2), gtq[d], ar);
+        build_stage(rp.gq[d], variant(0, 1, d, 2, 2), gq[d], ar);
+    }
+    build_orth(rp.orthY, rp.blocks, true, ar);
+    build_orth(rp.orthZ, rp.blocks, false, ar);
+    build_stage(rp.uout, variant(0, 0, 0, 3, 3), uo, ar, 1);
+    build_stage(rp.vout, variant(0, 0, 0, 3, 3), vo, ar, 1);
+}
+
+int run_refresh(const RefreshProgram& rp, bool grouped, int q, hipStream_t s) {
+    for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.sketch[d], grouped, 1.0f, 0.0f, s));
+    TSR_TRY(run_orth(rp.orthY, grouped, s));
+    for (int it = 0; it < q; ++it) {
+        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, s));
+        TSR_TRY(run_orth(rp.orthZ, grouped, s));
+        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gq[d], grouped, 1.0f, 0.0f, s));
+        TSR_TRY(run_orth(rp.orthY, grouped, s));
+    }
+    // B^T = G^T Q = Q_B R ; SVD of R ; U = Q X_r ; V = Q_B Gacc_r^T
+    for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, s));
+    TSR_TRY(run_orth(rp.orthZ, grouped, s));
+    TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), s));
+    TSR_TRY(run_stage(rp.uout, grouped, 1.0f, 0.0f, s));
+    return run_stage(rp.vout, grouped, 1.0f, 0.0f, s);
+}
+
+int check_refresh_shape(int m, int n, int r, int p) {
+    TSR_TRY(check_block(m, n, r));
+    if (p < 0) return TSR_BAD_SHAPE;
+    if ((long long)r + p > m || (long long)r + p > n) return TSR_BAD_SHAPE;
+    if (r + p > 1024) return TSR_BAD_SHAPE;     // limit of the one-workgroup factorization kernels
+    return TSR_OK;
+}
+
+}  // namespace
+
+// ====================================================================== C ABI
+struct tsr_plan {
+    std::vector<BlockView> blocks;
+    int n_workers = 1, precision = 0, p = 0;
+    bool with_refresh = false;
+    ProjectProgram project;
+    LiftProgram lift;
+    std::vector<CoreBlock> cores; const CoreBlock* d_cores = nullptr; long long max_core = 0;
+    RefreshProgram refresh;
+    char* ws = nullptr;
+    Uploader up;
+};
+
+extern "C" {
+
+const char* tsr_status_string(int status) {
+    switch (status) {
+        case TSR_OK: return "ok";
+        case TSR_INVALID_ARG: return "invalid argument";
+        case TSR_BAD_SHAPE: return "bad shape";
+        case TSR_BAD_DTYPE: return "bad dtype";
+        case TSR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case TSR_HIP_ERROR: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int tsr_last_hip_error(void) { return g_last_hip; }
+
+int tsr_device_count(void) {
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess) return 0;
+    return n;
+}
+
+// ---------------------------------------------------------------- project
+static void one_block_view(std::vector<BlockView>& v, const void* G, int g_dtype, int m, int n, int r,
+                           long long ldg, float* W, long long ldw, float* U, float* V, float* C, float* D) {
+    BlockView b{};
+    b.G = G; b.g_dtype = g_dtype; b.m = m; b.n = n; b.r = r; b.ldg = ldg; b.g_stride = 0;
+    b.W = W; b.ldw = ldw; b.U = U; b.V = V; b.C = C; b.D = D;
+    v.assign(1, b);
+}
+
+size_t tsr_project_workspace_bytes(int m, int n, int r) {
+    if (check_block(m, n, r) != TSR_OK) return 0;
+    std::vector<BlockView> v;
+    one_block_view(v, nullptr, TSR_F32, m, n, r, n, nullptr, n, nullptr, nullptr, nullptr, nullptr);
+    Arena ar(nullptr);
+    ProjectProgram pg;
+    build_project(pg, v, 1, TSR_PREC_SPLIT, ar);
+    return ar.used();
+}
+
+int tsr_project_core(const void* G, int g_dtype, int m, int n, long long ldg, const float* U, const float* V,
+                     int r, float alpha, int accumulate, float* C, int precision, void* ws, size_t ws_bytes,
+                     void* stream) {
+    TSR_TRY(check_block(m, n, r));
+    TSR_TRY(check_dtype(g_dtype));
+    TSR_TRY(check_prec(precision));
+    if (!G || !U || !V || !C || !ws) return TSR_INVALID_ARG;
+    if (ldg < n) return TSR_BAD_SHAPE;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_project_workspace_bytes(m, n, r)) return TSR_WORKSPACE_TOO_SMALL;
+    std::vector<BlockView> v;
+    one_block_view(v, G, g_dtype, m, n, r, ldg, nullptr, n, (float*)U, (float*)V, C, nullptr);
+    Arena ar(ws);
+    ProjectProgram pg;
+    build_project(pg, v, 1, precision, ar);
+    return run_project(pg, false, alpha, accumulate ? 1.0f : 0.0f, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- average
+int tsr_core_average(const float* Cs, int K, int r, float* Cbar, void* stream) {
+    if (!Cs || !Cbar) return TSR_INVALID_ARG;
+    if (K <= 0 || r <= 0) return TSR_BAD_SHAPE;
+    TSR_HIP(launch_average(Cs, K, (long long)r * r, Cbar, (hipStream_t)stream));
+    return TSR_OK;
+}
+
+// ---------------------------------------------------------------- Adam / SGD on the core
+static int adam_scalars(AdamScalars& s, int t, float beta1, float beta2, float eps) {
+    if (t < 1) return TSR_INVALID_ARG;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) || !(eps >= 0.0f)) return TSR_INVALID_ARG;
+    s.beta1 = beta1; s.beta2 = beta2; s.eps = eps;
+    s.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)t)));
+    s.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)t)));
+    return TSR_OK;
+}
+
+int tsr_adam_core(const float* C, float* M, float* Vm, float* D, long long count, int t, float beta1, float beta2,
+                  float eps, void* stream) {
+    if (!C || !M || !Vm || !D) return TSR_INVALID_ARG;
+    if (count <= 0) return TSR_BAD_SHAPE;
+    AdamScalars s;
+    TSR_TRY(adam_scalars(s, t, beta1, beta2, eps));
+    CoreBlock b{C, M, Vm, D, count};
+    TSR_HIP(launch_adam(nullptr, &b, 1, count, s, (hipStream_t)stream));
+    return TSR_OK;
+}
+
+int tsr_sgd_core(const float* C, float* M, float* D, long long count, float beta, void* stream) {
+    if (!C || !M || !D) return TSR_INVALID_ARG;
+    if (count <= 0) return TSR_BAD_SHAPE;
+    if (!(beta >= 0.0f && beta < 1.0f)) return TSR_INVALID_ARG;
+    TSR_HIP(launch_sgd(C, M, D, count, beta, (hipStream_t)stream));
+    return TSR_OK;
+}
+
+// ---------------------------------------------------------------- lift + apply
+size_t tsr_backproject_workspace_bytes(int m, int n, int r) {
+    if (check_block(m, n, r) != TSR_OK) return 0;
+    std::vector<BlockView> v;
+    one_block_view(v, nullptr, TSR_F32, m, n, r, n, nullptr, n, nullptr, nullptr, nullptr, nullptr);
+    Arena ar(nullptr);
+    LiftProgram lp;
+    build_lift(lp, v, TSR_PREC_SPLIT, ar);
+    return ar.used();
+}
+
+int tsr_backproject_apply(float* W, int m, int n, long long ldw, const float* U, const float* V, const float* D,
+                          int r, float lr, float wd, float scale, int precision, void* ws, size_t ws_bytes,
+                          void* stream) {
+    TSR_TRY(check_block(m, n, r));
+    TSR_TRY(check_prec(precision));
+    if (!W || !U || !V || !D || !ws) return TSR_INVALID_ARG;
+    if (ldw < n) return TSR_BAD_SHAPE;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_backproject_workspace_bytes(m, n, r)) return TSR_WORKSPACE_TOO_SMALL;
+    std::vector<BlockView> v;
+    one_block_view(v, nullptr, TSR_F32, m, n, r, n, W, ldw, (float*)U, (float*)V, nullptr, (float*)D);
+    Arena ar(ws);
+    LiftProgram lp;
+    build_lift(lp, v, precision, ar);
+    return run_lift(lp, false, lr, wd, scale, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- refresh
+size_t tsr_refresh_workspace_bytes(int m, int n, int r, int p) {
+    if (check_refresh_shape(m, n, r, p) != TSR_OK) return 0;
+    std::vector<BlockView> v;
+    one_block_view(v, nullptr, TSR_F32, m, n, r, n, nullptr, n, nullptr, nullptr, nullptr, nullptr);
+    Arena ar(nullptr);
+    RefreshProgram rp;
+    build_refresh(rp, v, nullptr, p, nullptr, ar);
+    return ar.used();
+}
+
+int tsr_refresh_rsvd(const void* G, int g_dtype, int m, int n, long long ldg, const float* Omega, int r, int p,
+                     int q, float* U, float* V, float* sigma, void* ws, size_t ws_bytes, void* stream) {
+    TSR_TRY(check_refresh_shape(m, n, r, p));
+    TSR_TRY(check_dtype(g_dtype));
+    if (q < 0) return TSR_INVALID_ARG;
+    if (!G || !Omega || !U || !V || !ws) return TSR_INVALID_ARG;
+    if (ldg < n) return TSR_BAD_SHAPE;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_refresh_workspace_bytes(m, n, r, p)) return TSR_WORKSPACE_TOO_SMALL;
+    std::vector<BlockView> v;
+    one_block_view(v, G, g_dtype, m, n, r, ldg, nullptr, n, U, V, nullptr, nullptr);
+    Arena ar(ws);
+    RefreshProgram rp;
+    const float* oms[1] = {Omega};
+    float* sigs[1] = {sigma};
+    build_refresh(rp, v, oms, p, sigs, ar);
+    return run_refresh(rp, false, q, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- plan
+static int check_descs(const tsr_matrix_desc* descs, int count, int n_workers, int with_refresh, int p,
+                       bool need_ptrs) {
+    if (!descs || count <= 0 || n_workers <= 0) return TSR_INVALID_ARG;
+    for (int i = 0; i < count; ++i) {
+        const tsr_matrix_desc& d = descs[i];
+        TSR_TRY(check_block(d.m, d.n, d.r));
+        TSR_TRY(check_dtype(d.g_dtype));
+        if (d.ldg < d.n || d.ldw < d.n) return TSR_BAD_SHAPE;
+        if (n_workers > 1 && d.g_stride < (long long)(d.m - 1) * d.ldg + d.n) return TSR_BAD_SHAPE;
+        if (with_refresh) TSR_TRY(check_refresh_shape(d.m, d.n, d.r, p));
+        if (need_ptrs && (!d.G || !d.W || !d.U || !d.V || !d.M || !d.Vm || !d.C || !d.D)) return TSR_INVALID_ARG;
+    }
+    return TSR_OK;
+}
+
+static void views_from_descs(std::vector<BlockView>& v, const tsr_matrix_desc* descs, int count) {
+    v.resize(count);
+    for (int i = 0; i < count; ++i) {
+        const tsr_matrix_desc& d = descs[i];
+        BlockView b{};
+        b.G = d.G; b.g_dtype = d.g_dtype; b.m = d.m; b.n = d.n; b.r = d.r; b.ldg = d.ldg; b.g_stride = d.g_stride;
+        b.W = d.W; b.ldw = d.ldw; b.U = d.U; b.V = d.V; b.M = d.M; b.Vm = d.Vm; b.C = d.C; b.D = d.D;
+        v[i] = b;
+    }
+}
+
+// Builds every program of the plan into `ar`; with plan == nullptr only measures.
+static void build_plan(tsr_plan& pl, Arena& ar) {
+    build_project(pl.project, pl.blocks, pl.n_workers, pl.precision, ar);
+    build_lift(pl.lift, pl.blocks, pl.precision, ar);
+    pl.cores.clear();
+    pl.max_core = 0;
+    for (const BlockView& b : pl.blocks) {
+        const long long cnt = (long long)b.r * b.r;
+        pl.cores.push_back(CoreBlock{b.C, b.M, b.Vm, b.D, cnt});
+        pl.max_core = std::max(pl.max_core, cnt);
+    }
+    if (pl.with_refresh) build_refresh(pl.refresh, pl.blocks, nullptr, pl.p, nullptr, ar);
+    // device tables
+    Uploader& up = pl.up;
+    for (int d = 0; d < 2; ++d) upload_stage(pl.project.gv[d], ar, up);
+    upload_stage(pl.project.utp, ar, up);
+    upload_stage(pl.lift.ud, ar, up);
+    upload_stage(pl.lift.tvt, ar, up);
+    pl.d_cores = up.put(pl.cores, ar);
+    if (pl.with_refresh) {
+        RefreshProgram& rp = pl.refresh;
+        for (int d = 0; d < 2; ++d) {
+            upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gq[d], ar, up);
+        }
+        for (OrthProgram* op : {&rp.orthY, &rp.orthZ}) {
+            upload_stage(op->gram1, ar, up); upload_stage(op->q1, ar, up);
+            upload_stage(op->gram2, ar, up); upload_stage(op->q2, ar, up);
+            op->d_chol1 = up.put(op->chol1, ar); op->d_chol2 = up.put(op->chol2, ar);
+        }
+        rp.d_jac = up.put(rp.jac, ar);
+        upload_stage(rp.uout, ar, up); upload_stage(rp.vout, ar, up);
+    }
+}
+
+size_t tsr_plan_workspace_bytes(const tsr_matrix_desc* descs, int count, int n_workers, int with_refresh, int p) {
+    if (check_descs(descs, count, n_workers, with_refresh, p, false) != TSR_OK) return 0;
+    tsr_plan pl;
+    views_from_descs(pl.blocks, descs, count);
+    pl.n_workers = n_workers; pl.precision = TSR_PREC_SPLIT; pl.with_refresh = with_refresh != 0; pl.p = p;
+    Arena ar(nullptr);
+    build_plan(pl, ar);
+    return ar.used();
+}
+
+int tsr_plan_create(const tsr_matrix_desc* descs, int count, int n_workers, int precision, int with_refresh, int p,
+                    void* ws, size_t ws_bytes, void* stream, tsr_plan** plan_out) {
+    if (!plan_out) return TSR_INVALID_ARG;
+    *plan_out = nullptr;
+    TSR_TRY(check_descs(descs, count, n_workers, with_refresh, p, true));
+    TSR_TRY(check_prec(precision));
+    if (!ws || !aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_plan_workspace_bytes(descs, count, n_workers, with_refresh, p)) return TSR_WORKSPACE_TOO_SMALL;
+    tsr_plan* pl = new (std::nothrow) tsr_plan;
+    if (!pl) return TSR_INVALID_ARG;
+    views_from_descs(pl->blocks, descs, count);
+    pl->n_workers = n_workers; pl->precision = precision; pl->with_refresh = with_refresh != 0; pl->p = p;
+    pl->ws = (char*)ws;
+    Arena ar(ws);
+    build_plan(*pl, ar);
+    if (!pl->up.host.empty()) {
+        hipError_t e = hipMemcpyAsync((char*)ws + pl->up.first, pl->up.host.data(), pl->up.host.size(),
+                                      hipMemcpyHostToDevice, (hipStream_t)stream);
+        if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) { delete pl; return hip_fail(e); }
+    }
+    *plan_out = pl;
+    return TSR_OK;
+}
+
+void tsr_plan_destroy(tsr_plan* plan) { delete plan; }
+
+int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream) {
+    if (!plan || !h) return TSR_INVALID_ARG;
+    AdamScalars s;
+    TSR_TRY(adam_scalars(s, t, h->beta1, h->beta2, h->eps));
+    hipStream_t st = (hipStream_t)stream;
+    TSR_TRY(run_project(plan->project, true, 1.0f / (float)plan->n_workers, 0.0f, st));
+    TSR_HIP(launch_adam(plan->d_cores, nullptr, (int)plan->cores.size(), plan->max_core, s, st));
+    return run_lift(plan->lift, true, h->lr, h->wd, h->scale, st);
+}
+
+int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void* stream) {
+    if (!plan || !Omegas || q < 0) return TSR_INVALID_ARG;
+    if (!plan->with_refresh) return TSR_INVALID_ARG;
+    RefreshProgram& rp = plan->refresh;
+    hipStream_t st = (hipStream_t)stream;
+    // patch the sketch stage's B pointers with this call's Omegas and re-upload those tables
+    size_t cursor[2] = {0, 0};
+    for (size_t i = 0; i < rp.blocks.size(); ++i) {
+        if (!Omegas[i]) return TSR_INVALID_ARG;
+        const int d = rp.blocks[i].g_dtype;
+        rp.sketch[d].probs[cursor[d]++].B = Omegas[i];
+    }
+    for (int d = 0; d < 2; ++d) {
+        GemmStage& sgm = rp.sketch[d];
+        if (sgm.empty()) continue;
+        TSR_HIP(hipMemcpyAsync((void*)sgm.d_probs, sgm.probs.data(), sgm.probs.size() * sizeof(GemmProblem),
+                               hipMemcpyHostToDevice, st));
+    }
+    TSR_HIP(hipStreamSynchronize(st));
+    return run_refresh(rp, true, q, st);
+}
+
+void tsr_plan_payload_bytes(const tsr_plan* plan, int bytes_per_dense_element, long long* core_bytes,
+                            long long* dense_bytes) {
+    long long c = 0, d = 0;
+    if (plan) {
+        for (const BlockView& b : plan->blocks) {
+            c += 4LL * b.r * b.r;
+            d += (long long)bytes_per_dense_element * b.m * b.n;
+        }
+    }
+    if (core_bytes) *core_bytes = c;
+    if (dense_bytes) *dense_bytes = d;
+}
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Element-wise core kernels and the small dense factorizations of the refresh
+// (internal interface).  "Batched" launches take a device table of per-block
+// descriptors; with a null table the single descriptor passed by value is used.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace tsr {
+
+// ---- Adam / momentum on the cores, core averaging
+struct CoreBlock {          // one block's core arrays, `count` floats each
+    const float* C; float* M; float* Vm; float* D;
+    long long count;
+};
+struct AdamScalars { float beta1, beta2, eps, inv_c1, inv_c2; };
+
+hipError_t launch_adam(const CoreBlock* table_dev, const CoreBlock* single, int blocks,
+                       long long max_count, const AdamScalars& s, hipStream_t stream);
+hipError_t launch_sgd(const float* C, float* M, float* D, long long count, float beta, hipStream_t stream);
+hipError_t launch_average(const float* Cs, int K, long long count, float* out, hipStream_t stream);
+
+// ---- Cholesky-based orth helper: from the k x k Gram matrix S (fp32, symmetric) of a
+// tall matrix Y compute, in fp64, S = R^T R and write
+//   Rinv (fp32, k x k upper) = R^-1, so that Y Rinv has orthonormal columns,
+//   Rtot (fp64, k x k upper, optional) = R * Rprev (Rprev optional = identity).
+// A pivot at or below tol * S[j][j] marks column j as dependent: row/column j of Rinv and
+// row j of Rtot become zero.  work = 2 k x k doubles per matrix.
+struct CholBlock {
+    const float* S; float* Rinv;
+    const double* Rprev; double* Rtot;
+    double* work;
+    int k;
+};
+hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, int blocks,
+                           double tol, hipStream_t stream);
+
+// ---- one-sided Jacobi SVD of the k x k upper-triangular factor R (fp64, destroyed):
+// rows of R are rotated until mutually orthogonal: Gacc R = diag(sigma) X^T.  Outputs, for the
+// r largest sigma in descending order: XrT (r x k fp32) rows x_j^T, GrT (r x k fp32) rows
+// of Gacc, and sigma (k fp32, optional, all k values descending).  Gacc = k x k doubles of work.
+struct JacobiBlock {
+    double* R; double* Gacc;
+    float* XrT; float* GrT; float* sigma;
+    int k, r;
+};
+hipError_t launch_jacobi(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks,
+                         hipStream_t stream);
+
+}  // namespace tsr
