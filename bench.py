@@ -1,0 +1,214 @@
+"""Benchmark of the TSR-Adam per-matrix optimizer hot path on one MI355X.
+
+A "step" is one pass of the whole per-step path (project all blocks -> Adam on the cores ->
+lift + apply) over one batch of synthetic LLaMA-shaped gradients already resident in HBM,
+issued through the batched C-ABI call.  The workload at N=1 is the LLaMA-130M-shaped optimizer
+step (84 blocks, r = 256, bf16 gradients, fp32 weights and core moments).  The subspace
+refresh (rSVD, p = 8, q = 1) is timed separately in the same run.
+
+Prints ONE JSON line (see the keys below).  `value` is the algorithmic bytes of one step
+(G once, W read + written, U and V once for project and once for lift, the core arrays)
+divided by the step time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak, published
+
+
+def step_bytes(m, n, r, g_bytes):
+    """Algorithmic HBM bytes of one step for one block."""
+    return m * n * g_bytes + 8 * m * n + 8 * r * (m + n) + 24 * r * r
+
+
+def step_flops(m, n, r):
+    return 4 * m * n * r + 4 * r * r * min(m, n)
+
+
+def tvt_bytes(m, n, r):
+    """Algorithmic bytes of the fused lift-and-apply kernel W <- bW + a T V^T for one block:
+    W read and written once, T (m x r) and V (n x r) read once."""
+    return 8 * m * n + 4 * r * (m + n)
+
+
+def gv_bytes(m, n, r, g_bytes):
+    """G once, V once, P = G V written once."""
+    return m * n * g_bytes + 4 * n * r + 4 * m * r
+
+
+def build_blocks(w: si.Workload, device):
+    blocks = []
+    for i, (m, n) in enumerate(w.shapes):
+        key = si.stream_key(si.BASE_SEED, 2, i)
+        sig = si.make_signal(m, n, w.signal_rank, w.spectrum, key, device=device)
+        if w.workers > 1:
+            G = torch.stack([si.gradient(sig, w.noise, si.stream_key(key, 100 + k), dtype=w.g_dtype)
+                             for k in range(w.workers)])
+        else:
+            G = si.gradient(sig, w.noise, si.stream_key(key, 100), dtype=w.g_dtype)
+        r = w.r
+        blocks.append(dict(
+            G=G, W=si.weights(m, n, si.stream_key(key, 7), device=device),
+            U=torch.empty(m, r, device=device), V=torch.empty(n, r, device=device),
+            M=torch.zeros(r, r, device=device), Vm=torch.zeros(r, r, device=device),
+            C=torch.empty(r, r, device=device), D=torch.empty(r, r, device=device)))
+    return blocks
+
+
+def cpu_baseline(w: si.Workload, blocks, n_sample):
+    """The fp64 oracle, as it stands, on the first n_sample blocks: one full step each."""
+    from oracle import tsr_oracle as orc
+    sample = []
+    for b in blocks[:n_sample]:
+        G = b["G"][0] if b["G"].dim() == 3 else b["G"]
+        sample.append((orc.f64(G), orc.f64(b["U"]), orc.f64(b["V"]), orc.f64(b["W"])))
+    r = w.r
+    t0 = time.perf_counter()
+    for G, U, V, W in sample:
+        M = np.zeros((r, r)); Vm = np.zeros((r, r))
+        orc.tsr_adam_step(W, [G], U, V, M, Vm, 1, lr=1e-3)
+    dt = time.perf_counter() - t0
+    g_bytes = 2 if w.g_dtype == torch.bfloat16 else 4
+    nbytes = sum(step_bytes(m, n, r, g_bytes) for m, n in w.shapes[:n_sample])
+    return dict(value=nbytes / dt / 1e9, unit="GB/s", cores=orc.num_threads(), kind="oracle",
+                sample="one full step (project, Adam, lift+apply) of the first %d of %d blocks, %.2f s"
+                       % (n_sample, len(w.shapes), dt),
+                seconds_per_full_step_extrapolated=dt * sum(step_flops(m, n, r) for m, n in w.shapes)
+                / sum(step_flops(m, n, r) for m, n in w.shapes[:n_sample]))
+
+
+def read_traffic(path):
+    """Optional rocprofv3 --pmc summary: lines `key: value`."""
+    if not os.path.exists(path):
+        return None
+    out = {}
+    for ln in open(path):
+        if ":" in ln and not ln.startswith("#"):
+            k, v = ln.split(":", 1)
+            try:
+                out[k.strip()] = float(v.strip())
+            except ValueError:
+                pass
+    return out.get("tvt_traffic_bytes_per_launch")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama-130m")
+    ap.add_argument("--layers", type=int, default=None, help="use fewer layers (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-refresh", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are built); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import paper_2602_08007_amd as tsr
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = si.workload(args.workload, args.layers)
+    g_bytes = 2 if w.g_dtype == torch.bfloat16 else 4
+    blocks = build_blocks(w, dev)
+    precision = tsr.TSR_PREC_BF16 if w.g_dtype == torch.bfloat16 else tsr.TSR_PREC_SPLIT
+    plan = tsr.Plan(blocks, n_workers=w.workers, precision=precision, with_refresh=True, p=w.p)
+    stream = torch.cuda.current_stream()
+
+    # ---- refresh (initialises U, V from the gradients; timed on its second run)
+    omegas = [si.omega(n, w.r + w.p, si.stream_key(si.BASE_SEED, 3, i), device=dev) for i, (m, n) in enumerate(w.shapes)]
+    plan.tsr_refresh_batched(omegas, w.q)
+    torch.cuda.synchronize()
+    refresh = None
+    if not args.no_refresh:
+        plan.tsr_plan_profile_begin()
+        t0 = time.perf_counter()
+        plan.tsr_refresh_batched(omegas, w.q)
+        torch.cuda.synchronize()
+        refresh_ms = (time.perf_counter() - t0) * 1e3
+        prof = plan.tsr_plan_profile_end()
+        k = w.r + w.p
+        gemm_flops = sum((2 * w.q + 2) * 2 * m * n * k for m, n in w.shapes)
+        gemm_ms = prof["sketch_gemm"][0]
+        refresh = dict(ms_total=refresh_ms, ms_per_matrix=refresh_ms / len(w.shapes),
+                       gemm_ms=gemm_ms, gemm_tflops=gemm_flops / gemm_ms / 1e9,
+                       gemm_mfma_frac=gemm_flops / gemm_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                       stages_ms={kk: round(v[0], 3) for kk, v in prof.items() if v[1]},
+                       p=w.p, q=w.q)
+
+    # ---- the timed step loop
+    hyper = dict(lr=1e-3, wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0)
+    t = 1
+    for _ in range(args.warmup):
+        plan.tsr_step_batched(t, **hyper); t += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan.tsr_step_batched(t, **hyper); t += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # ---- same steps again with HIP events around every stage (per-kernel durations)
+    plan.tsr_plan_profile_begin()
+    for _ in range(args.steps):
+        plan.tsr_step_batched(t, **hyper); t += 1
+    prof = plan.tsr_plan_profile_end()
+    stage_ms = {kk: v[0] / max(v[1], 1) for kk, v in prof.items() if v[1]}
+
+    total_bytes = sum(step_bytes(m, n, w.r, g_bytes) for m, n in w.shapes) + \
+        (w.workers - 1) * sum(m * n * g_bytes for m, n in w.shapes)
+    total_flops = sum(step_flops(m, n, w.r) for m, n in w.shapes)
+    value = total_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel = the longest stage of the step
+    dom = max(("gv", "tvt"), key=lambda kk: stage_ms.get(kk, 0.0))
+    if dom == "tvt":
+        dom_bytes = sum(tvt_bytes(m, n, w.r) for m, n in w.shapes)
+    else:
+        dom_bytes = w.workers * sum(gv_bytes(m, n, w.r, g_bytes) for m, n in w.shapes)
+    achieved = dom_bytes / (stage_ms[dom] * 1e-3) / 1e9
+    roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBPS, ms_per_launch=stage_ms[dom],
+                    traffic=read_traffic(os.path.join(ROOT, "profiles", "step_%s_traffic.txt" % w.name)))
+
+    core_b, dense_b = plan.payload_bytes(4)
+    out = {
+        "metric": "Projected-Adam step GB/s + % HBM roofline; rSVD refresh ms/matrix + MFMA %",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 operands, f32 accumulate" if precision == tsr.TSR_PREC_BF16 else "f32 (split bf16x2), f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": w.name, "blocks": len(w.shapes), "r": w.r, "g_dtype": str(w.g_dtype).replace("torch.", ""),
+                   "workers": w.workers},
+        "hbm_frac": value / HBM_PEAK_GBPS,
+        "step_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "stage_ms": {kk: round(v, 4) for kk, v in stage_ms.items()},
+        "roofline": roofline,
+        "refresh": refresh,
+        "payload": {"core_bytes": core_b, "dense_bytes_fp32": dense_b, "ratio": dense_b / core_b},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, blocks, min(7, len(w.shapes)))
+    plan.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,6 +163,22 @@ int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream);
  * `count` device pointers (block i: n_i x (r_i + p)). */
 int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void* stream);
 
+/* Per-stage timing of the batched calls, for benchmarks.  Between begin and end every stage
+ * the plan enqueues is bracketed by HIP events on the work stream.  tsr_plan_profile_end
+ * synchronizes the stream and adds up, per stage kind, the elapsed milliseconds (ms[kind])
+ * and the number of bracketed stages (launches[kind], may be NULL); both are HOST arrays of
+ * TSR_PROF_KINDS entries.  Stage kinds of the step: G V, U^T P (with its split-k reduction),
+ * Adam on the cores, U D, the fused T V^T weight update.  Of the refresh: the GEMMs that
+ * read G (sketch and power iterations and B), the GEMMs of the thin QR, its Cholesky
+ * kernels, the Jacobi SVD, the two basis-update GEMMs. */
+enum {
+    TSR_PROF_GV = 0, TSR_PROF_UTP = 1, TSR_PROF_ADAM = 2, TSR_PROF_UD = 3, TSR_PROF_TVT = 4,
+    TSR_PROF_SKETCH_GEMM = 5, TSR_PROF_ORTH_GEMM = 6, TSR_PROF_CHOL = 7, TSR_PROF_JACOBI = 8,
+    TSR_PROF_BASIS_GEMM = 9, TSR_PROF_KINDS = 10
+};
+int tsr_plan_profile_begin(tsr_plan* plan);
+int tsr_plan_profile_end(tsr_plan* plan, void* stream, float* ms, int* launches);
+
 /* Bytes a worker would put on the wire per step for the plan's blocks: the r x r cores
  * (4 bytes each) and the dense gradients they replace (at bytes_per_dense_element). */
 void tsr_plan_payload_bytes(const tsr_plan* plan, int bytes_per_dense_element,

@@ -68,6 +68,8 @@ _plan_create = _sig("tsr_plan_create", _i, ctypes.POINTER(tsr_matrix_desc), _i, 
 _plan_destroy = _sig("tsr_plan_destroy", None, _vp)
 _step_batched = _sig("tsr_step_batched", _i, _vp, _i, ctypes.POINTER(tsr_hyper), _vp)
 _refresh_batched = _sig("tsr_refresh_batched", _i, _vp, ctypes.POINTER(_vp), _i, _vp)
+_prof_begin = _sig("tsr_plan_profile_begin", _i, _vp)
+_prof_end = _sig("tsr_plan_profile_end", _i, _vp, _vp, ctypes.POINTER(_f), ctypes.POINTER(_i))
 _payload = _sig("tsr_plan_payload_bytes", None, _vp, _i, ctypes.POINTER(_ll), ctypes.POINTER(_ll))
 
 
@@ -235,6 +237,19 @@ class Plan:
         _f32c(*omegas)
         arr = (_vp * self.count)(*[_ptr(o) for o in omegas])
         _check(_refresh_batched(self._handle, arr, q, _stream(stream)))
+
+    PROF_KINDS = ("gv", "utp", "adam", "ud", "tvt", "sketch_gemm", "orth_gemm", "chol", "jacobi", "basis_gemm")
+
+    def tsr_plan_profile_begin(self):
+        _check(_prof_begin(self._handle))
+
+    def tsr_plan_profile_end(self, stream=None):
+        """{kind: (milliseconds, stages)} summed since tsr_plan_profile_begin; synchronizes."""
+        n = len(self.PROF_KINDS)
+        ms = (_f * n)()
+        cnt = (_i * n)()
+        _check(_prof_end(self._handle, _stream(stream), ms, cnt))
+        return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(self.PROF_KINDS)}
 
     def payload_bytes(self, bytes_per_dense_element=4):
         c, d = _ll(), _ll()

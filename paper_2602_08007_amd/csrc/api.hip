@@ -55,6 +55,37 @@ struct Arena {
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// Optional per-stage timing: HIP events recorded on the work stream around every stage.
+struct Prof {
+    struct Span { int kind; hipEvent_t a, b; };
+    std::vector<Span> spans;
+    bool on = false;
+    void clear() {
+        for (Span& s : spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+        spans.clear();
+    }
+};
+
+struct Ctx {                  // where to enqueue, and whether to time it
+    hipStream_t s;
+    Prof* prof;
+};
+
+struct Timed {                // RAII bracket of one stage
+    Ctx& c; int idx = -1;
+    Timed(Ctx& ctx, int kind) : c(ctx) {
+        if (c.prof && c.prof->on) {
+            Prof::Span sp{kind, nullptr, nullptr};
+            if (hipEventCreate(&sp.a) == hipSuccess && hipEventCreate(&sp.b) == hipSuccess) {
+                (void)hipEventRecord(sp.a, c.s);
+                c.prof->spans.push_back(sp);
+                idx = (int)c.prof->spans.size() - 1;
+            }
+        }
+    }
+    ~Timed() { if (idx >= 0) (void)hipEventRecord(c.prof->spans[idx].b, c.s); }
+};
+
 // ------------------------------------------------------------------ GEMM stages
 struct LogicalGemm {
     const void* A; const float* B;
@@ -146,8 +177,10 @@ void build_stage(GemmStage& st, const GemmVariant& var, const std::vector<Logica
     }
 }
 
-int run_stage(const GemmStage& st, bool grouped, float alpha, float beta, hipStream_t stream) {
+int run_stage(const GemmStage& st, bool grouped, float alpha, float beta, Ctx& cx, int kind) {
     if (st.empty()) return TSR_OK;
+    Timed timed(cx, kind);
+    hipStream_t stream = cx.s;
     GemmLaunch L{};
     L.n_tiles = (int)st.tiles.size();
     if (grouped) {
@@ -240,10 +273,10 @@ void build_project(ProjectProgram& pg, const std::vector<BlockView>& blocks, int
     build_stage(pg.utp, variant(1, 1, 0, pv, pv), utp, ar);
 }
 
-int run_project(const ProjectProgram& pg, bool grouped, float alpha, float beta, hipStream_t s) {
-    TSR_TRY(run_stage(pg.gv[TSR_F32], grouped, 1.0f, 0.0f, s));
-    TSR_TRY(run_stage(pg.gv[TSR_BF16], grouped, 1.0f, 0.0f, s));
-    return run_stage(pg.utp, grouped, alpha, beta, s);
+int run_project(const ProjectProgram& pg, bool grouped, float alpha, float beta, Ctx& cx) {
+    TSR_TRY(run_stage(pg.gv[TSR_F32], grouped, 1.0f, 0.0f, cx, TSR_PROF_GV));
+    TSR_TRY(run_stage(pg.gv[TSR_BF16], grouped, 1.0f, 0.0f, cx, TSR_PROF_GV));
+    return run_stage(pg.utp, grouped, alpha, beta, cx, TSR_PROF_UTP);
 }
 
 struct LiftProgram {
@@ -263,10 +296,10 @@ void build_lift(LiftProgram& lp, const std::vector<BlockView>& blocks, int prec,
     build_stage(lp.tvt, variant(0, 0, 0, pv, pv), tvt, ar, /*want_tiles=*/1);
 }
 
-int run_lift(const LiftProgram& lp, bool grouped, float lr, float wd, float scale, hipStream_t s) {
-    TSR_TRY(run_stage(lp.ud, grouped, 1.0f, 0.0f, s));
+int run_lift(const LiftProgram& lp, bool grouped, float lr, float wd, float scale, Ctx& cx) {
+    TSR_TRY(run_stage(lp.ud, grouped, 1.0f, 0.0f, cx, TSR_PROF_UD));
     // W - lr (scale dW + wd W) = (1 - lr wd) W + (-lr scale) dW
-    return run_stage(lp.tvt, grouped, -lr * scale, 1.0f - lr * wd, s);
+    return run_stage(lp.tvt, grouped, -lr * scale, 1.0f - lr * wd, cx, TSR_PROF_TVT);
 }
 
 // ------------------------------------------------------------------ refresh program
@@ -315,14 +348,20 @@ void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool o
     build_stage(op.q2, variant(0, 1, 0, 3, 3), q2, ar, 1);
 }
 
-int run_orth(const OrthProgram& op, bool grouped, hipStream_t s) {
+int run_orth(const OrthProgram& op, bool grouped, Ctx& cx) {
     const int nb = (int)op.chol1.size();
-    TSR_TRY(run_stage(op.gram1, grouped, 1.0f, 0.0f, s));
-    TSR_HIP(launch_chol_inv(grouped ? op.d_chol1 : nullptr, grouped ? nullptr : &op.chol1[0], nb, 1e-6, s));
-    TSR_TRY(run_stage(op.q1, grouped, 1.0f, 0.0f, s));
-    TSR_TRY(run_stage(op.gram2, grouped, 1.0f, 0.0f, s));
-    TSR_HIP(launch_chol_inv(grouped ? op.d_chol2 : nullptr, grouped ? nullptr : &op.chol2[0], nb, 1e-6, s));
-    return run_stage(op.q2, grouped, 1.0f, 0.0f, s);
+    TSR_TRY(run_stage(op.gram1, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    {
+        Timed timed(cx, TSR_PROF_CHOL);
+        TSR_HIP(launch_chol_inv(grouped ? op.d_chol1 : nullptr, grouped ? nullptr : &op.chol1[0], nb, 1e-6, cx.s));
+    }
+    TSR_TRY(run_stage(op.q1, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    TSR_TRY(run_stage(op.gram2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    {
+        Timed timed(cx, TSR_PROF_CHOL);
+        TSR_HIP(launch_chol_inv(grouped ? op.d_chol2 : nullptr, grouped ? nullptr : &op.chol2[0], nb, 1e-6, cx.s));
+    }
+    return run_stage(op.q2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM);
 }
 
 // Carves every refresh buffer from `ar` and builds all stages.  Omega pointers may be null
@@ -367,21 +406,24 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
     build_stage(rp.vout, variant(0, 0, 0, 3, 3), vo, ar, 1);
 }
 
-int run_refresh(const RefreshProgram& rp, bool grouped, int q, hipStream_t s) {
-    for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.sketch[d], grouped, 1.0f, 0.0f, s));
-    TSR_TRY(run_orth(rp.orthY, grouped, s));
+int run_refresh(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
+    for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.sketch[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
+    TSR_TRY(run_orth(rp.orthY, grouped, cx));
     for (int it = 0; it < q; ++it) {
-        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, s));
-        TSR_TRY(run_orth(rp.orthZ, grouped, s));
-        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gq[d], grouped, 1.0f, 0.0f, s));
-        TSR_TRY(run_orth(rp.orthY, grouped, s));
+        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
+        TSR_TRY(run_orth(rp.orthZ, grouped, cx));
+        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
+        TSR_TRY(run_orth(rp.orthY, grouped, cx));
     }
     // B^T = G^T Q = Q_B R ; SVD of R ; U = Q X_r ; V = Q_B Gacc_r^T
-    for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, s));
-    TSR_TRY(run_orth(rp.orthZ, grouped, s));
-    TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), s));
-    TSR_TRY(run_stage(rp.uout, grouped, 1.0f, 0.0f, s));
-    return run_stage(rp.vout, grouped, 1.0f, 0.0f, s);
+    for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
+    TSR_TRY(run_orth(rp.orthZ, grouped, cx));
+    {
+        Timed timed(cx, TSR_PROF_JACOBI);
+        TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), cx.s));
+    }
+    TSR_TRY(run_stage(rp.uout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
+    return run_stage(rp.vout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM);
 }
 
 int check_refresh_shape(int m, int n, int r, int p) {
@@ -405,6 +447,8 @@ struct tsr_plan {
     RefreshProgram refresh;
     char* ws = nullptr;
     Uploader up;
+    Prof prof;
+    ~tsr_plan() { prof.clear(); }
 };
 
 extern "C" {
@@ -463,7 +507,8 @@ int tsr_project_core(const void* G, int g_dtype, int m, int n, long long ldg, co
     Arena ar(ws);
     ProjectProgram pg;
     build_project(pg, v, 1, precision, ar);
-    return run_project(pg, false, alpha, accumulate ? 1.0f : 0.0f, (hipStream_t)stream);
+    Ctx cx{(hipStream_t)stream, nullptr};
+    return run_project(pg, false, alpha, accumulate ? 1.0f : 0.0f, cx);
 }
 
 // ---------------------------------------------------------------- average
@@ -528,7 +573,8 @@ int tsr_backproject_apply(float* W, int m, int n, long long ldw, const float* U,
     Arena ar(ws);
     LiftProgram lp;
     build_lift(lp, v, precision, ar);
-    return run_lift(lp, false, lr, wd, scale, (hipStream_t)stream);
+    Ctx cx{(hipStream_t)stream, nullptr};
+    return run_lift(lp, false, lr, wd, scale, cx);
 }
 
 // ---------------------------------------------------------------- refresh
@@ -558,7 +604,8 @@ int tsr_refresh_rsvd(const void* G, int g_dtype, int m, int n, long long ldg, co
     const float* oms[1] = {Omega};
     float* sigs[1] = {sigma};
     build_refresh(rp, v, oms, p, sigs, ar);
-    return run_refresh(rp, false, q, (hipStream_t)stream);
+    Ctx cx{(hipStream_t)stream, nullptr};
+    return run_refresh(rp, false, q, cx);
 }
 
 // ---------------------------------------------------------------- plan
@@ -663,10 +710,13 @@ int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream) {
     if (!plan || !h) return TSR_INVALID_ARG;
     AdamScalars s;
     TSR_TRY(adam_scalars(s, t, h->beta1, h->beta2, h->eps));
-    hipStream_t st = (hipStream_t)stream;
-    TSR_TRY(run_project(plan->project, true, 1.0f / (float)plan->n_workers, 0.0f, st));
-    TSR_HIP(launch_adam(plan->d_cores, nullptr, (int)plan->cores.size(), plan->max_core, s, st));
-    return run_lift(plan->lift, true, h->lr, h->wd, h->scale, st);
+    Ctx cx{(hipStream_t)stream, &plan->prof};
+    TSR_TRY(run_project(plan->project, true, 1.0f / (float)plan->n_workers, 0.0f, cx));
+    {
+        Timed timed(cx, TSR_PROF_ADAM);
+        TSR_HIP(launch_adam(plan->d_cores, nullptr, (int)plan->cores.size(), plan->max_core, s, cx.s));
+    }
+    return run_lift(plan->lift, true, h->lr, h->wd, h->scale, cx);
 }
 
 int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void* stream) {
@@ -688,7 +738,30 @@ int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void*
                                hipMemcpyHostToDevice, st));
     }
     TSR_HIP(hipStreamSynchronize(st));
-    return run_refresh(rp, true, q, st);
+    Ctx cx{st, &plan->prof};
+    return run_refresh(rp, true, q, cx);
+}
+
+int tsr_plan_profile_begin(tsr_plan* plan) {
+    if (!plan) return TSR_INVALID_ARG;
+    plan->prof.clear();
+    plan->prof.on = true;
+    return TSR_OK;
+}
+
+int tsr_plan_profile_end(tsr_plan* plan, void* stream, float* ms, int* launches) {
+    if (!plan || !ms) return TSR_INVALID_ARG;
+    plan->prof.on = false;
+    for (int i = 0; i < TSR_PROF_KINDS; ++i) { ms[i] = 0.0f; if (launches) launches[i] = 0; }
+    TSR_HIP(hipStreamSynchronize((hipStream_t)stream));
+    for (const Prof::Span& sp : plan->prof.spans) {
+        float t = 0.0f;
+        TSR_HIP(hipEventElapsedTime(&t, sp.a, sp.b));
+        ms[sp.kind] += t;
+        if (launches) launches[sp.kind] += 1;
+    }
+    plan->prof.clear();
+    return TSR_OK;
 }
 
 void tsr_plan_payload_bytes(const tsr_plan* plan, int bytes_per_dense_element, long long* core_bytes,

@@ -9,7 +9,7 @@ namespace tsr {
 __global__ __launch_bounds__(256) void adam_kernel(const CoreBlock* table, const CoreBlock single,
                                                    const AdamScalars s) {
     const CoreBlock* b = table ? table + blockIdx.y : &single;
-    const float* __restrict__ C = b->C;
+    const float* C = b->C;
     float* __restrict__ M = b->M;
     float* __restrict__ Vm = b->Vm;
     float* D = b->D;
