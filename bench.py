@@ -153,7 +153,7 @@ def main():
                        p=w.p, q=w.q)
 
     # ---- the timed step loop
-    hyper = dict(lr=1e-3, wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0)
+    hyper = dict(lr=float(os.environ.get("TSR_BENCH_LR", "1e-3")), wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0)
     t = 1
     for _ in range(args.warmup):
         plan.tsr_step_batched(t, **hyper); t += 1

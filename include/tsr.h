@@ -103,6 +103,13 @@ int tsr_project_core(const void* G, int g_dtype, int m, int n, long long ldg,
  * Stands in, on one GPU, for the all-reduce-average of Algorithm 1.  Cbar may alias Cs. */
 int tsr_core_average(const float* Cs, int K, int r, float* Cbar, void* stream);
 
+/* ---------------------------------------------------------------- calibration
+ * dst[i] = scale * src[i] for `count` floats (count % 4 == 0, 16-byte aligned, dst may equal
+ * src): a plain streaming kernel of known traffic (4*count bytes read, 4*count written).  Not
+ * part of the method: benchmarks use it to measure the HBM rate the machine actually reaches
+ * and to calibrate the memory-traffic counters of the profiler. */
+int tsr_stream_scale(float* dst, const float* src, long long count, float scale, void* stream);
+
 /* ---------------------------------------------------------------- Adam on the core (Section 3.4)
  * m <- beta1 m + (1-beta1) C ; v <- beta2 v + (1-beta2) C.C ;
  * D = (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps).   t >= 1 is the global step count.
@@ -149,11 +156,17 @@ int tsr_refresh_rsvd(const void* G, int g_dtype, int m, int n, long long ldg,
  * tsr_plan_create synchronizes the stream once (table upload); the other calls do not. */
 typedef struct tsr_plan tsr_plan;
 size_t tsr_plan_workspace_bytes(const tsr_matrix_desc* descs, int count, int n_workers,
-                                int with_refresh, int p);
+                                int precision, int with_refresh, int p);
 int tsr_plan_create(const tsr_matrix_desc* descs, int count, int n_workers, int precision,
                     int with_refresh, int p,
                     void* ws, size_t ws_bytes, void* stream, tsr_plan** plan_out);
 void tsr_plan_destroy(tsr_plan* plan);
+
+/* With TSR_PREC_BF16 the plan keeps bf16 copies of U, U^T, V, V^T in its workspace and
+ * rebuilds them on the first step after creation and after every tsr_refresh_batched.  A
+ * caller that writes U or V itself (a restored checkpoint, bases computed elsewhere) must
+ * call this before the next step. */
+int tsr_plan_bases_changed(tsr_plan* plan);
 
 /* One TSR-Adam step (no refresh) for every block of the plan:
  * project all workers -> average -> Adam on the cores -> lift + apply.  t >= 1. */

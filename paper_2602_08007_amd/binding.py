@@ -14,7 +14,7 @@ import torch
 __all__ = [
     "TSR_F32", "TSR_BF16", "TSR_PREC_SPLIT", "TSR_PREC_BF16", "TsrError", "lib", "lib_path",
     "tsr_status_string", "tsr_device_count",
-    "tsr_project_workspace_bytes", "tsr_project_core", "tsr_core_average", "tsr_adam_core", "tsr_sgd_core",
+    "tsr_stream_scale", "tsr_project_workspace_bytes", "tsr_project_core", "tsr_core_average", "tsr_adam_core", "tsr_sgd_core",
     "tsr_backproject_workspace_bytes", "tsr_backproject_apply",
     "tsr_refresh_workspace_bytes", "tsr_refresh_rsvd",
     "tsr_matrix_desc", "tsr_hyper", "Plan", "workspace",
@@ -56,13 +56,15 @@ _device_count = _sig("tsr_device_count", _i)
 _project_ws = _sig("tsr_project_workspace_bytes", _sz, _i, _i, _i)
 _project = _sig("tsr_project_core", _i, _vp, _i, _i, _i, _ll, _vp, _vp, _i, _f, _i, _vp, _i, _vp, _sz, _vp)
 _average = _sig("tsr_core_average", _i, _vp, _i, _i, _vp, _vp)
+_stream_scale = _sig("tsr_stream_scale", _i, _vp, _vp, _ll, _f, _vp)
 _adam = _sig("tsr_adam_core", _i, _vp, _vp, _vp, _vp, _ll, _i, _f, _f, _f, _vp)
 _sgd = _sig("tsr_sgd_core", _i, _vp, _vp, _vp, _ll, _f, _vp)
 _lift_ws = _sig("tsr_backproject_workspace_bytes", _sz, _i, _i, _i)
 _lift = _sig("tsr_backproject_apply", _i, _vp, _i, _i, _ll, _vp, _vp, _vp, _i, _f, _f, _f, _i, _vp, _sz, _vp)
 _refresh_ws = _sig("tsr_refresh_workspace_bytes", _sz, _i, _i, _i, _i)
 _refresh = _sig("tsr_refresh_rsvd", _i, _vp, _i, _i, _i, _ll, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp)
-_plan_ws = _sig("tsr_plan_workspace_bytes", _sz, ctypes.POINTER(tsr_matrix_desc), _i, _i, _i, _i)
+_plan_ws = _sig("tsr_plan_workspace_bytes", _sz, ctypes.POINTER(tsr_matrix_desc), _i, _i, _i, _i, _i)
+_bases_changed = _sig("tsr_plan_bases_changed", _i, _vp)
 _plan_create = _sig("tsr_plan_create", _i, ctypes.POINTER(tsr_matrix_desc), _i, _i, _i, _i, _i, _vp, _sz, _vp,
                     ctypes.POINTER(_vp))
 _plan_destroy = _sig("tsr_plan_destroy", None, _vp)
@@ -152,6 +154,12 @@ def tsr_core_average(Cs, Cbar, stream=None):
     return Cbar
 
 
+def tsr_stream_scale(dst, src, scale=1.0, stream=None):
+    _f32c(dst, src)
+    _check(_stream_scale(_ptr(dst), _ptr(src), src.numel(), scale, _stream(stream)))
+    return dst
+
+
 def tsr_adam_core(C, M, Vm, D, t, beta1=0.9, beta2=0.999, eps=1e-8, stream=None):
     _f32c(C, M, Vm, D)
     _check(_adam(_ptr(C), _ptr(M), _ptr(Vm), _ptr(D), C.numel(), t, beta1, beta2, eps, _stream(stream)))
@@ -222,7 +230,7 @@ class Plan:
             d.W = _ptr(W); d.ldw = _ld(W)
             d.U = _ptr(U); d.V = _ptr(b["V"]); d.M = _ptr(b["M"]); d.Vm = _ptr(b["Vm"]); d.C = _ptr(b["C"]); d.D = _ptr(b["D"])
         self._descs = arr
-        nbytes = int(_plan_ws(arr, self.count, n_workers, int(with_refresh), p))
+        nbytes = int(_plan_ws(arr, self.count, n_workers, precision, int(with_refresh), p))
         if nbytes == 0:
             raise TsrError(-2)
         self.ws = workspace(nbytes, blocks[0]["W"].device)
@@ -232,6 +240,9 @@ class Plan:
     def tsr_step_batched(self, t, lr, wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0, stream=None):
         h = tsr_hyper(lr, wd, beta1, beta2, eps, scale)
         _check(_step_batched(self._handle, t, ctypes.byref(h), _stream(stream)))
+
+    def tsr_plan_bases_changed(self):
+        _check(_bases_changed(self._handle))
 
     def tsr_refresh_batched(self, omegas: List[torch.Tensor], q, stream=None):
         _f32c(*omegas)

@@ -14,77 +14,20 @@
 #include "../../include/tsr.h"
 #include "gemm.h"
 #include "small.h"
+#include "nt_gemm.h"
+#include "host_util.h"
+#include "fast_step.h"
 
 using namespace tsr;
 
-namespace {
-
-thread_local int g_last_hip = 0;
-
-inline int hip_fail(hipError_t e) {
-    g_last_hip = (int)e;
-    return TSR_HIP_ERROR;
+namespace tsr {
+int& last_hip_error() {
+    static thread_local int e = 0;
+    return e;
 }
-#define TSR_HIP(call)                                  \
-    do {                                               \
-        hipError_t e__ = (call);                       \
-        if (e__ != hipSuccess) return hip_fail(e__);   \
-    } while (0)
-#define TSR_TRY(call)                    \
-    do {                                 \
-        int s__ = (call);                \
-        if (s__ != TSR_OK) return s__;   \
-    } while (0)
+}  // namespace tsr
 
-constexpr size_t ALIGN = 256;
-inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
-
-// Bump allocator over the caller's workspace.  With base == nullptr it only measures.
-struct Arena {
-    char* base;
-    size_t off = 0;
-    explicit Arena(void* b) : base((char*)b) {}
-    template <typename T> T* take(size_t count) {
-        off = align_up(off);
-        T* p = base ? (T*)(base + off) : (T*)nullptr;
-        off += count * sizeof(T);
-        return p;
-    }
-    size_t used() const { return align_up(off); }
-};
-
-inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
-
-// Optional per-stage timing: HIP events recorded on the work stream around every stage.
-struct Prof {
-    struct Span { int kind; hipEvent_t a, b; };
-    std::vector<Span> spans;
-    bool on = false;
-    void clear() {
-        for (Span& s : spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
-        spans.clear();
-    }
-};
-
-struct Ctx {                  // where to enqueue, and whether to time it
-    hipStream_t s;
-    Prof* prof;
-};
-
-struct Timed {                // RAII bracket of one stage
-    Ctx& c; int idx = -1;
-    Timed(Ctx& ctx, int kind) : c(ctx) {
-        if (c.prof && c.prof->on) {
-            Prof::Span sp{kind, nullptr, nullptr};
-            if (hipEventCreate(&sp.a) == hipSuccess && hipEventCreate(&sp.b) == hipSuccess) {
-                (void)hipEventRecord(sp.a, c.s);
-                c.prof->spans.push_back(sp);
-                idx = (int)c.prof->spans.size() - 1;
-            }
-        }
-    }
-    ~Timed() { if (idx >= 0) (void)hipEventRecord(c.prof->spans[idx].b, c.s); }
-};
+namespace {
 
 // ------------------------------------------------------------------ GEMM stages
 struct LogicalGemm {
@@ -201,24 +144,6 @@ int run_stage(const GemmStage& st, bool grouped, float alpha, float beta, Ctx& c
     return TSR_OK;
 }
 
-// Device tables, carved from the arena after every data buffer and mirrored in `host`
-// (host[0] corresponds to arena offset `first`) so that one copy uploads them all.
-struct Uploader {
-    std::vector<char> host;
-    size_t first = (size_t)-1;
-    template <typename T> const T* put(const std::vector<T>& v, Arena& ar) {
-        T* d = ar.take<T>(v.size());
-        if (ar.base) {
-            const size_t o = (size_t)((char*)d - ar.base);
-            if (first == (size_t)-1) first = o;
-            const size_t rel = o - first;
-            if (host.size() < rel + v.size() * sizeof(T)) host.resize(rel + v.size() * sizeof(T));
-            if (!v.empty()) memcpy(host.data() + rel, v.data(), v.size() * sizeof(T));
-        }
-        return d;
-    }
-};
-
 void upload_stage(GemmStage& st, Arena& ar, Uploader& up) {
     if (st.empty()) return;
     st.d_probs = up.put(st.probs, ar);
@@ -243,11 +168,6 @@ int check_dtype(int d) { return (d == TSR_F32 || d == TSR_BF16) ? TSR_OK : TSR_B
 int check_prec(int p) { return (p == TSR_PREC_SPLIT || p == TSR_PREC_BF16) ? TSR_OK : TSR_INVALID_ARG; }
 
 // ------------------------------------------------------------------ per-step programs
-struct BlockView {          // what the step needs to know about one block
-    const void* G; int g_dtype; int m, n, r; long long ldg, g_stride;
-    float* W; long long ldw; float* U; float* V; float* M; float* Vm; float* C; float* D;
-};
-
 struct ProjectProgram {
     GemmStage gv[2];        // P = G V, index = dtype of G
     GemmStage utp;          // C = U^T P (summed over workers and k-splits)
@@ -443,6 +363,8 @@ struct tsr_plan {
     bool with_refresh = false;
     ProjectProgram project;
     LiftProgram lift;
+    FastStep fast;              // used instead of project / lift when precision == TSR_PREC_BF16
+    bool use_fast = false;
     std::vector<CoreBlock> cores; const CoreBlock* d_cores = nullptr; long long max_core = 0;
     RefreshProgram refresh;
     char* ws = nullptr;
@@ -465,7 +387,7 @@ const char* tsr_status_string(int status) {
     }
 }
 
-int tsr_last_hip_error(void) { return g_last_hip; }
+int tsr_last_hip_error(void) { return tsr::last_hip_error(); }
 
 int tsr_device_count(void) {
     int n = 0;
@@ -516,6 +438,15 @@ int tsr_core_average(const float* Cs, int K, int r, float* Cbar, void* stream) {
     if (!Cs || !Cbar) return TSR_INVALID_ARG;
     if (K <= 0 || r <= 0) return TSR_BAD_SHAPE;
     TSR_HIP(launch_average(Cs, K, (long long)r * r, Cbar, (hipStream_t)stream));
+    return TSR_OK;
+}
+
+// ---------------------------------------------------------------- calibration stream
+int tsr_stream_scale(float* dst, const float* src, long long count, float scale, void* stream) {
+    if (!dst || !src) return TSR_INVALID_ARG;
+    if (count <= 0 || (count % 4) != 0) return TSR_BAD_SHAPE;
+    if (((uintptr_t)dst % 16) || ((uintptr_t)src % 16)) return TSR_INVALID_ARG;
+    TSR_HIP(launch_stream(dst, src, count, scale, (hipStream_t)stream));
     return TSR_OK;
 }
 
@@ -637,8 +568,13 @@ static void views_from_descs(std::vector<BlockView>& v, const tsr_matrix_desc* d
 
 // Builds every program of the plan into `ar`; with plan == nullptr only measures.
 static void build_plan(tsr_plan& pl, Arena& ar) {
-    build_project(pl.project, pl.blocks, pl.n_workers, pl.precision, ar);
-    build_lift(pl.lift, pl.blocks, pl.precision, ar);
+    pl.use_fast = (pl.precision == TSR_PREC_BF16);
+    if (pl.use_fast) {
+        build_fast_step(pl.fast, pl.blocks, pl.n_workers, ar);
+    } else {
+        build_project(pl.project, pl.blocks, pl.n_workers, pl.precision, ar);
+        build_lift(pl.lift, pl.blocks, pl.precision, ar);
+    }
     pl.cores.clear();
     pl.max_core = 0;
     for (const BlockView& b : pl.blocks) {
@@ -649,11 +585,15 @@ static void build_plan(tsr_plan& pl, Arena& ar) {
     if (pl.with_refresh) build_refresh(pl.refresh, pl.blocks, nullptr, pl.p, nullptr, ar);
     // device tables
     Uploader& up = pl.up;
-    for (int d = 0; d < 2; ++d) upload_stage(pl.project.gv[d], ar, up);
-    upload_stage(pl.project.utp, ar, up);
-    upload_stage(pl.lift.ud, ar, up);
-    upload_stage(pl.lift.tvt, ar, up);
     pl.d_cores = up.put(pl.cores, ar);
+    if (pl.use_fast) {
+        upload_fast_step(pl.fast, ar, up);
+    } else {
+        for (int d = 0; d < 2; ++d) upload_stage(pl.project.gv[d], ar, up);
+        upload_stage(pl.project.utp, ar, up);
+        upload_stage(pl.lift.ud, ar, up);
+        upload_stage(pl.lift.tvt, ar, up);
+    }
     if (pl.with_refresh) {
         RefreshProgram& rp = pl.refresh;
         for (int d = 0; d < 2; ++d) {
@@ -669,11 +609,13 @@ static void build_plan(tsr_plan& pl, Arena& ar) {
     }
 }
 
-size_t tsr_plan_workspace_bytes(const tsr_matrix_desc* descs, int count, int n_workers, int with_refresh, int p) {
+size_t tsr_plan_workspace_bytes(const tsr_matrix_desc* descs, int count, int n_workers, int precision,
+                                int with_refresh, int p) {
     if (check_descs(descs, count, n_workers, with_refresh, p, false) != TSR_OK) return 0;
+    if (check_prec(precision) != TSR_OK) return 0;
     tsr_plan pl;
     views_from_descs(pl.blocks, descs, count);
-    pl.n_workers = n_workers; pl.precision = TSR_PREC_SPLIT; pl.with_refresh = with_refresh != 0; pl.p = p;
+    pl.n_workers = n_workers; pl.precision = precision; pl.with_refresh = with_refresh != 0; pl.p = p;
     Arena ar(nullptr);
     build_plan(pl, ar);
     return ar.used();
@@ -686,7 +628,8 @@ int tsr_plan_create(const tsr_matrix_desc* descs, int count, int n_workers, int 
     TSR_TRY(check_descs(descs, count, n_workers, with_refresh, p, true));
     TSR_TRY(check_prec(precision));
     if (!ws || !aligned256(ws)) return TSR_INVALID_ARG;
-    if (ws_bytes < tsr_plan_workspace_bytes(descs, count, n_workers, with_refresh, p)) return TSR_WORKSPACE_TOO_SMALL;
+    if (ws_bytes < tsr_plan_workspace_bytes(descs, count, n_workers, precision, with_refresh, p))
+        return TSR_WORKSPACE_TOO_SMALL;
     tsr_plan* pl = new (std::nothrow) tsr_plan;
     if (!pl) return TSR_INVALID_ARG;
     views_from_descs(pl->blocks, descs, count);
@@ -711,6 +654,7 @@ int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream) {
     AdamScalars s;
     TSR_TRY(adam_scalars(s, t, h->beta1, h->beta2, h->eps));
     Ctx cx{(hipStream_t)stream, &plan->prof};
+    if (plan->use_fast) return run_fast_step(plan->fast, plan->n_workers, s, h->lr, h->wd, h->scale, cx);
     TSR_TRY(run_project(plan->project, true, 1.0f / (float)plan->n_workers, 0.0f, cx));
     {
         Timed timed(cx, TSR_PROF_ADAM);
@@ -739,7 +683,14 @@ int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void*
     }
     TSR_HIP(hipStreamSynchronize(st));
     Ctx cx{st, &plan->prof};
+    plan->fast.bases_dirty = true;
     return run_refresh(rp, true, q, cx);
+}
+
+int tsr_plan_bases_changed(tsr_plan* plan) {
+    if (!plan) return TSR_INVALID_ARG;
+    plan->fast.bases_dirty = true;
+    return TSR_OK;
 }
 
 int tsr_plan_profile_begin(tsr_plan* plan) {

@@ -1,0 +1,49 @@
+// The bf16 per-step path: every contraction of project / lift as a k-contiguous bf16 NT GEMM
+// over bf16 shadows of the bases (internal interface).
+#pragma once
+#include <vector>
+
+#include "gemm.h"
+#include "host_util.h"
+#include "lift.h"
+#include "nt_gemm.h"
+#include "small.h"
+
+namespace tsr {
+
+struct NtStageH {
+    NtVariant var{};
+    std::vector<NtProblem> probs;
+    std::vector<NtTile> tiles;            // XCD-interleaved, idle entries have prob < 0
+    std::vector<ReduceProblem> reduces;   // empty when the GEMM writes its output directly
+    int max_reduce_elems = 0;
+    const NtProblem* d_probs = nullptr;
+    const NtTile* d_tiles = nullptr;
+    const ReduceProblem* d_reduces = nullptr;
+    bool empty() const { return probs.empty(); }
+};
+
+struct FastStep {
+    std::vector<ShadowBlock> shadows;  const ShadowBlock* d_shadows = nullptr;
+    int max_rows = 0, max_r = 0;
+    NtStageH gv[2];      // P^T = V^T G^T   (index: dtype of G)
+    NtStageH utp;        // C = U^T P
+    std::vector<AdamTBlock> adam;  const AdamTBlock* d_adam = nullptr;
+    NtStageH ud;         // T = U D                      (blocks the fused kernel cannot take)
+    NtStageH tvt;        // W = beta W + alpha T V^T
+    struct LiftGroup {   // blocks of one rank handled by the fused lift kernel
+        int r = 0;
+        int mode = 0;        // kernel variant (panel height / prefetch), see lift.hip
+        bool vec4 = false;   // W rows 16-byte aligned and n % 4 == 0 for every block of the group
+        std::vector<LiftBlock> blocks;  const LiftBlock* d_blocks = nullptr;
+        std::vector<LiftTile> tiles;    const LiftTile* d_tiles = nullptr;
+    };
+    std::vector<LiftGroup> lifts;
+    bool bases_dirty = true;
+};
+
+void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_workers, Arena& ar);
+void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up);
+int run_fast_step(FastStep& fs, int n_workers, const AdamScalars& s, float lr, float wd, float scale, Ctx& cx);
+
+}  // namespace tsr

@@ -1,0 +1,267 @@
+// Launch-sequence builder of the bf16 per-step path (see fast_step.h).
+#include "fast_step.h"
+
+#include <algorithm>
+#include <cstdlib>
+#include <map>
+#include <numeric>
+
+namespace tsr {
+
+namespace {
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+inline long long round8(long long x) { return (x + 7) / 8 * 8; }
+constexpr int N_XCD = 8;
+
+struct NtLogical {
+    const void* A; const void* B; void* out;
+    long long lda, ldb, ldc;
+    int M, N, K;
+    int block;      // owning matrix block (tiles of one block stay on one XCD)
+    int group;      // consecutive entries with the same group >= 0 are summed into `out`
+};
+
+// Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2:
+// give every block to one XCD (greedy by work) and interleave the per-XCD tile lists, so the
+// tiles that re-read a block's operands hit the L2 that already holds them.
+// Tuning knobs read from the environment at plan creation (integers): TSR_TUNE_GV, TSR_TUNE_UTP,
+// TSR_TUNE_UD, TSR_TUNE_TVT select the NtShape of a stage, TSR_TUNE_XCD=0 keeps the natural
+// tile order, TSR_TUNE_FUSED_LIFT=0 uses the two-GEMM lift, TSR_TUNE_LIFT_CHUNK sets the number
+// of column tiles one workgroup of the fused lift streams.  Unset = the built-in choice.
+int tune_int(const char* name, int dflt, int lo, int hi) {
+    const char* v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    const int x = std::atoi(v);
+    return (x >= lo && x <= hi) ? x : dflt;
+}
+int tune(const char* name, int dflt) { return tune_int(name, dflt, 0, NT_SHAPES - 1); }
+
+template <typename TileT>
+void interleave_xcd(std::vector<TileT>& tiles, const std::vector<int>& tile_block, const std::vector<long long>& tile_work,
+                    int n_blocks, const TileT& idle) {
+    if (tune("TSR_TUNE_XCD", 1) == 0) return;
+    std::vector<long long> work(n_blocks, 0);
+    for (size_t i = 0; i < tiles.size(); ++i) work[tile_block[i]] += tile_work[i];
+    std::vector<int> order(n_blocks);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return work[a] > work[b]; });
+    std::vector<int> xcd_of(n_blocks, 0);
+    long long load[N_XCD] = {0};
+    for (int b : order) {
+        int best = 0;
+        for (int x = 1; x < N_XCD; ++x) if (load[x] < load[best]) best = x;
+        xcd_of[b] = best;
+        load[best] += work[b];
+    }
+    std::vector<TileT> lists[N_XCD];
+    for (size_t i = 0; i < tiles.size(); ++i) lists[xcd_of[tile_block[i]]].push_back(tiles[i]);
+    size_t longest = 0;
+    for (auto& l : lists) longest = std::max(longest, l.size());
+    std::vector<TileT> out;
+    out.reserve(longest * N_XCD);
+    for (size_t s = 0; s < longest; ++s)
+        for (int x = 0; x < N_XCD; ++x) out.push_back(s < lists[x].size() ? lists[x][s] : idle);
+    tiles.swap(out);
+}
+
+void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogical>& gemms, int n_blocks, Arena& ar,
+                    int want_tiles) {
+    st = NtStageH{};
+    st.var = var;
+    if (gemms.empty()) return;
+    const int TM = nt_tile_m(var.shape), TN = nt_tile_n(var.shape);
+    long long base_tiles = 0;
+    bool shared = false;
+    for (size_t i = 0; i < gemms.size(); ++i) {
+        base_tiles += (long long)cdiv(gemms[i].M, TM) * cdiv(gemms[i].N, TN);
+        if (i > 0 && gemms[i].group >= 0 && gemms[i].group == gemms[i - 1].group) shared = true;
+    }
+    const int want_split = (int)std::max<long long>(1, want_tiles / std::max<long long>(1, base_tiles));
+    std::vector<int> ksplit(gemms.size()), kchunk(gemms.size());
+    bool any_split = false;
+    for (size_t i = 0; i < gemms.size(); ++i) {
+        const int K = gemms[i].K;
+        int s = std::min(want_split, std::max(1, K / 256));
+        int chunk = cdiv(cdiv(K, s), 64) * 64;
+        s = cdiv(K, chunk);
+        ksplit[i] = s; kchunk[i] = chunk;
+        if (s > 1) any_split = true;
+    }
+    const bool direct = !(any_split || shared);
+    st.probs.resize(gemms.size());
+    std::vector<int> tile_block;
+    std::vector<long long> tile_work;
+    size_t i = 0;
+    while (i < gemms.size()) {
+        size_t e = i + 1;
+        while (e < gemms.size() && gemms[i].group >= 0 && gemms[e].group == gemms[i].group) ++e;
+        const size_t mn = (size_t)gemms[i].M * gemms[i].N;
+        float* part = nullptr;
+        if (!direct) {
+            int gs = 0;
+            for (size_t j = i; j < e; ++j) gs += ksplit[j];
+            part = ar.take<float>(mn * gs);
+            ReduceProblem r{};
+            r.part = part; r.out = (float*)gemms[i].out; r.stride = (long long)mn; r.ldc = gemms[i].ldc;
+            r.M = gemms[i].M; r.N = gemms[i].N; r.splits = gs;
+            st.reduces.push_back(r);
+            st.max_reduce_elems = std::max(st.max_reduce_elems, (int)std::min<size_t>(mn, 1u << 30));
+        }
+        int prefix = 0;
+        for (size_t j = i; j < e; ++j) {
+            const NtLogical& g = gemms[j];
+            NtProblem& p = st.probs[j];
+            p.A = g.A; p.B = g.B; p.lda = g.lda; p.ldb = g.ldb; p.M = g.M; p.N = g.N; p.K = g.K;
+            if (direct) {
+                p.C = g.out; p.ldc = g.ldc; p.c_split_stride = 0; p.kchunk = std::max(64, cdiv(g.K, 64) * 64);
+                ksplit[j] = 1;
+            } else {
+                p.C = part ? (void*)(part + mn * prefix) : nullptr;
+                p.ldc = g.N; p.c_split_stride = (long long)mn; p.kchunk = kchunk[j];
+                prefix += ksplit[j];
+            }
+            const int tmn = cdiv(g.M, TM), tnn = cdiv(g.N, TN);
+            for (int ks = 0; ks < ksplit[j]; ++ks)
+                for (int tm = 0; tm < tmn; ++tm)
+                    for (int tn = 0; tn < tnn; ++tn) {
+                        st.tiles.push_back(NtTile{(int)j, tm, tn, ks});
+                        tile_block.push_back(g.block);
+                        tile_work.push_back(std::min(p.kchunk, g.K) + 64);
+                    }
+        }
+        i = e;
+    }
+    interleave_xcd(st.tiles, tile_block, tile_work, n_blocks, NtTile{-1, 0, 0, 0});
+}
+
+int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind) {
+    if (st.empty()) return TSR_OK;
+    Timed timed(cx, kind);
+    NtLaunch L{};
+    L.probs = st.d_probs; L.tiles = st.d_tiles; L.n_tiles = (int)st.tiles.size();
+    if (st.reduces.empty()) {
+        L.alpha = alpha; L.beta = beta;
+        TSR_HIP(launch_nt_gemm(L, st.var, cx.s));
+    } else {
+        L.alpha = 1.0f; L.beta = 0.0f;
+        TSR_HIP(launch_nt_gemm(L, st.var, cx.s));
+        TSR_HIP(launch_splitk_reduce(st.d_reduces, nullptr, (int)st.reduces.size(), st.max_reduce_elems, alpha, beta,
+                                     cx.s));
+    }
+    return TSR_OK;
+}
+
+void upload_nt_stage(NtStageH& st, Arena& ar, Uploader& up) {
+    if (st.empty()) return;
+    st.d_probs = up.put(st.probs, ar);
+    st.d_tiles = up.put(st.tiles, ar);
+    if (!st.reduces.empty()) st.d_reduces = up.put(st.reduces, ar);
+}
+
+}  // namespace
+
+void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_workers, Arena& ar) {
+    fs.shadows.clear(); fs.adam.clear(); fs.lifts.clear();
+    fs.max_rows = 0; fs.max_r = 0;
+    const bool fused_lift = tune_int("TSR_TUNE_FUSED_LIFT", 1, 0, 1) != 0;
+    const int lift_chunk = tune_int("TSR_TUNE_LIFT_CHUNK", 6, 1, 64);
+    const int lift_mode = tune_int("TSR_TUNE_LIFT_MODE", 0, 0, 2);
+    const bool lift_vec4 = tune_int("TSR_TUNE_LIFT_VEC4", 0, 0, 1) != 0;
+    std::map<int, std::vector<int>> lift_tile_block;
+    std::map<int, std::vector<long long>> lift_tile_work;
+    std::vector<NtLogical> gv[2], utp, ud, tvt;
+    const int nb = (int)blocks.size();
+    int r_max = 0;
+    for (int bi = 0; bi < nb; ++bi) {
+        const BlockView& b = blocks[bi];
+        const long long ldr = round8(b.r), ldm = round8(b.m), ldn = round8(b.n);
+        typedef unsigned short bf;
+        bf* Ub = ar.take<bf>((size_t)b.m * ldr);
+        bf* UTb = ar.take<bf>((size_t)b.r * ldm);
+        bf* Vb = ar.take<bf>((size_t)b.n * ldr);
+        bf* VTb = ar.take<bf>((size_t)b.r * ldn);
+        bf* Tb = ar.take<bf>((size_t)b.m * ldr);
+        bf* DTb = ar.take<bf>((size_t)b.r * ldr);
+        fs.shadows.push_back(ShadowBlock{b.U, Ub, UTb, b.m, b.r, ldr, ldm});
+        fs.shadows.push_back(ShadowBlock{b.V, Vb, VTb, b.n, b.r, ldr, ldn});
+        fs.max_rows = std::max(fs.max_rows, std::max(b.m, b.n));
+        fs.max_r = std::max(fs.max_r, b.r);
+        r_max = std::max(r_max, b.r);
+        const int esz = (b.g_dtype == TSR_BF16) ? 2 : 4;
+        for (int w = 0; w < n_workers; ++w) {
+            bf* PT = ar.take<bf>((size_t)b.r * ldm);
+            const char* Gw = b.G ? (const char*)b.G + (size_t)w * b.g_stride * esz : nullptr;
+            gv[b.g_dtype].push_back(NtLogical{VTb, Gw, PT, ldn, b.ldg, ldm, b.r, b.m, b.n, bi, -1});
+            utp.push_back(NtLogical{UTb, PT, b.C, ldm, ldm, b.r, b.r, b.r, b.m, bi, bi});
+        }
+        fs.adam.push_back(AdamTBlock{b.C, b.M, b.Vm, b.D, DTb, b.r, ldr});
+        const bool fits32 = (long long)(b.m + 128) * b.ldw * 4 < (1LL << 31) && (long long)(std::max(b.m, b.n) + 128) * ldr * 2 < (1LL << 31);
+        if (fused_lift && lift_supports_rank(b.r) && fits32) {
+            const bool vec4 = lift_vec4 && (b.n % 4 == 0) && (b.ldw % 4 == 0) && (((uintptr_t)b.W) % 16 == 0);
+            FastStep::LiftGroup* grp = nullptr;
+            for (auto& g : fs.lifts) if (g.r == b.r && g.vec4 == vec4) grp = &g;
+            if (!grp) { fs.lifts.emplace_back(); grp = &fs.lifts.back(); grp->r = b.r; grp->vec4 = vec4; grp->mode = lift_mode; }
+            const int gkey = grp->r * 2 + (vec4 ? 1 : 0);
+            const int bidx = (int)grp->blocks.size();
+            grp->blocks.push_back(LiftBlock{Ub, DTb, Vb, b.W, ldr, b.ldw, b.m, b.n, b.r});
+            const int ntiles = cdiv(b.n, 128);
+            const int nchunks = cdiv(ntiles, lift_chunk);
+            const int per = cdiv(ntiles, nchunks);
+            for (int row0 = 0; row0 < b.m; row0 += lift_panel_rows(lift_mode))
+                for (int c0 = 0; c0 < ntiles; c0 += per) {
+                    grp->tiles.push_back(LiftTile{bidx, row0, c0, std::min(per, ntiles - c0)});
+                    lift_tile_block[gkey].push_back(bi);
+                    lift_tile_work[gkey].push_back(std::min(per, ntiles - c0) + 1);
+                }
+        } else {
+            ud.push_back(NtLogical{Ub, DTb, Tb, ldr, ldr, ldr, b.m, b.r, b.r, bi, -1});
+            tvt.push_back(NtLogical{Tb, Vb, b.W, ldr, ldr, b.ldw, b.m, b.n, b.r, bi, -1});
+        }
+    }
+    for (auto& g : fs.lifts)
+        interleave_xcd(g.tiles, lift_tile_block[g.r * 2 + (g.vec4 ? 1 : 0)], lift_tile_work[g.r * 2 + (g.vec4 ? 1 : 0)], nb,
+                       LiftTile{-1, 0, 0, 0});
+    const int s1_shape = tune("TSR_TUNE_GV", (r_max > 64) ? NT_128x128 : NT_64x256);
+    build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1);
+    build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1);
+    build_nt_stage(fs.utp, NtVariant{tune("TSR_TUNE_UTP", r_max > 64 ? NT_128x128 : NT_64x64), 0, 0}, utp, nb, ar, 512);
+    build_nt_stage(fs.ud, NtVariant{tune("TSR_TUNE_UD", NT_128x128), 0, 1}, ud, nb, ar, 1);
+    build_nt_stage(fs.tvt, NtVariant{tune("TSR_TUNE_TVT", NT_128x128), 0, 0}, tvt, nb, ar, 1);
+}
+
+void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {
+    fs.d_shadows = up.put(fs.shadows, ar);
+    fs.d_adam = up.put(fs.adam, ar);
+    for (int d = 0; d < 2; ++d) upload_nt_stage(fs.gv[d], ar, up);
+    upload_nt_stage(fs.utp, ar, up);
+    upload_nt_stage(fs.ud, ar, up);
+    upload_nt_stage(fs.tvt, ar, up);
+    for (auto& g : fs.lifts) {
+        g.d_blocks = up.put(g.blocks, ar);
+        g.d_tiles = up.put(g.tiles, ar);
+    }
+}
+
+int run_fast_step(FastStep& fs, int n_workers, const AdamScalars& s, float lr, float wd, float scale, Ctx& cx) {
+    if (fs.bases_dirty) {
+        TSR_HIP(launch_shadows(fs.d_shadows, (int)fs.shadows.size(), fs.max_rows, fs.max_r, cx.s));
+        fs.bases_dirty = false;
+    }
+    TSR_TRY(run_nt_stage(fs.gv[TSR_F32], 1.0f, 0.0f, cx, TSR_PROF_GV));
+    TSR_TRY(run_nt_stage(fs.gv[TSR_BF16], 1.0f, 0.0f, cx, TSR_PROF_GV));
+    TSR_TRY(run_nt_stage(fs.utp, 1.0f / (float)n_workers, 0.0f, cx, TSR_PROF_UTP));
+    {
+        Timed timed(cx, TSR_PROF_ADAM);
+        TSR_HIP(launch_adam_t(fs.d_adam, (int)fs.adam.size(), fs.max_r, s, cx.s));
+    }
+    TSR_TRY(run_nt_stage(fs.ud, 1.0f, 0.0f, cx, TSR_PROF_UD));
+    TSR_TRY(run_nt_stage(fs.tvt, -lr * scale, 1.0f - lr * wd, cx, TSR_PROF_TVT));
+    for (const auto& g : fs.lifts) {
+        Timed timed(cx, TSR_PROF_TVT);
+        TSR_HIP(launch_lift(g.d_blocks, g.d_tiles, (int)g.tiles.size(), g.r, g.vec4, g.mode, -lr * scale, 1.0f - lr * wd, cx.s));
+    }
+    return TSR_OK;
+}
+
+}  // namespace tsr

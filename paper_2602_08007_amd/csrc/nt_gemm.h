@@ -1,0 +1,63 @@
+// bf16 x bf16 -> fp32 "NT" GEMM family for the bf16 step path (internal interface).
+//
+//   C[tile] = alpha * A B^T [tile] + beta * C[tile]
+// A is M x K, B is N x K, both row-major with k contiguous (bf16; B may also be fp32 and is
+// then rounded to bf16 on the way into LDS).  Output is fp32 (optionally into k-split
+// partial buffers) or bf16.  All operands of the per-step path are brought into this one
+// form (bf16 shadows of U, U^T, V, V^T; P^T and T as bf16 intermediates; D^T from the Adam
+// kernel), so a single tuned kernel serves G V, U^T P, U D and the fused T V^T update.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace tsr {
+
+struct NtProblem {
+    const void* A;          // bf16, M x K, leading dimension lda
+    const void* B;          // bf16 (or fp32), N x K, leading dimension ldb
+    void* C;                // fp32 or bf16, M x N, leading dimension ldc
+    long long lda, ldb, ldc;
+    long long c_split_stride;
+    int M, N, K;
+    int kchunk;             // multiple of 64
+};
+
+struct NtTile { int prob, tm, tn, ks; };     // prob < 0: idle workgroup
+
+struct NtLaunch {
+    const NtProblem* probs;
+    const NtTile* tiles;
+    int n_tiles;
+    float alpha, beta;
+};
+
+enum NtShape {
+    NT_128x128 = 0, NT_256x64 = 1, NT_64x256 = 2, NT_64x64 = 3,               // 64-deep k-tiles
+    NT_128x128_K32 = 4, NT_256x64_K32 = 5, NT_256x128_K32 = 6, NT_128x256_K32 = 7,   // 32-deep
+    NT_256x128 = 8, NT_SHAPES = 9
+};
+inline int nt_tile_m(int s) {
+    static const int tm[NT_SHAPES] = {128, 256, 64, 64, 128, 256, 256, 128, 256};
+    return tm[s];
+}
+inline int nt_tile_n(int s) {
+    static const int tn[NT_SHAPES] = {128, 64, 256, 64, 128, 64, 128, 256, 128};
+    return tn[s];
+}
+
+struct NtVariant {
+    int shape;      // NtShape
+    int b_f32;      // B operand stored as fp32
+    int out_bf16;   // C stored as bf16 (beta ignored)
+};
+
+hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream);
+
+// fp32 bases -> bf16 shadows: X (rows x r, contiguous fp32) -> Xb (rows x ldx bf16) and
+// XTb (r x ldt bf16, the transpose); padding columns are written as zeros.
+struct ShadowBlock {
+    const float* X; void* Xb; void* XTb;
+    int rows, r; long long ldx, ldt;
+};
+hipError_t launch_shadows(const ShadowBlock* table_dev, int blocks, int max_rows, int max_r, hipStream_t stream);
+
+}  // namespace tsr

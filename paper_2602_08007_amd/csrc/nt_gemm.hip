@@ -1,0 +1,320 @@
+// bf16 NT GEMM for the per-step path on gfx950: C = alpha A B^T + beta C with A (M x K) and
+// B (N x K) both k-contiguous.  256 threads, 64-deep k-tiles, double-buffered LDS (one
+// barrier per k-tile), register prefetch of the next k-tile, v_mfma_f32_32x32x16_bf16 with
+// fp32 accumulation.  For the read-modify-write epilogue (beta != 0) the C tile is fetched
+// before the k-loop so that its HBM latency hides behind the whole loop.
+#include "nt_gemm.h"
+
+namespace tsr {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int NT_THREADS = 256;
+// LDS rows are padded by 8 bf16 (16 bytes): 80-byte rows for 32-deep k-tiles, 144-byte rows
+// for 64-deep ones; both give conflict-free 16-byte fragment reads.
+
+template <int CH, bool F32> struct NtStage;      // CH = 16-byte chunks per thread
+template <int CH> struct NtStage<CH, false> { u32x4 v[CH]; };
+template <int CH> struct NtStage<CH, true> { f32x4 v[CH][2]; };
+
+// rows x K operand, k contiguous; tile rows row0.., k0..k0+BK-1.  Thread t owns chunks
+// c = t + 256*it: row c/(BK/8), k offset (c%(BK/8))*8.
+template <int ROWS, int BK, bool F32>
+__device__ inline void nt_load(NtStage<ROWS * BK / 8 / NT_THREADS, F32>& s, const void* base, long long ld, int rows,
+                               int row0, int k0, int kend, bool vec_ok, int tid) {
+    constexpr int CPR = BK / 8;
+#pragma unroll
+    for (int it = 0; it < ROWS * CPR / NT_THREADS; ++it) {
+        const int c = tid + NT_THREADS * it;
+        const int grow = row0 + c / CPR;
+        const int gk = k0 + (c % CPR) * 8;
+        if constexpr (F32) {
+            const float* p = (const float*)base + (long long)grow * ld + gk;
+            if (grow < rows && vec_ok && gk + 8 <= kend) {
+                s.v[it][0] = *(const f32x4*)p;
+                s.v[it][1] = *(const f32x4*)(p + 4);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) s.v[it][j >> 2][j & 3] = (grow < rows && gk + j < kend) ? p[j] : 0.0f;
+            }
+        } else {
+            const unsigned short* p = (const unsigned short*)base + (long long)grow * ld + gk;
+            u32x4 r = {0u, 0u, 0u, 0u};
+            if (grow < rows) {
+                if (vec_ok && gk + 8 <= kend) {
+                    r = *(const u32x4*)p;
+                } else {
+                    unsigned short e[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) e[j] = (gk + j < kend) ? p[j] : (unsigned short)0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) r[j] = (unsigned int)e[2 * j] | ((unsigned int)e[2 * j + 1] << 16);
+                }
+            }
+            s.v[it] = r;
+        }
+    }
+}
+
+template <int ROWS, int BK, bool F32>
+__device__ inline void nt_store(const NtStage<ROWS * BK / 8 / NT_THREADS, F32>& s, unsigned short* lds, int tid) {
+    constexpr int CPR = BK / 8, KP = BK + 8;
+#pragma unroll
+    for (int it = 0; it < ROWS * CPR / NT_THREADS; ++it) {
+        const int c = tid + NT_THREADS * it;
+        unsigned short* dst = lds + (c / CPR) * KP + (c % CPR) * 8;
+        if constexpr (F32) {
+            bf16x8 h;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = (__bf16)s.v[it][j >> 2][j & 3];
+            *(bf16x8*)dst = h;
+        } else {
+            *(u32x4*)dst = s.v[it];
+        }
+    }
+}
+
+__device__ inline unsigned short f32_to_bf16_bits(float f) {
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(unsigned short, h);
+}
+
+// OUT: 0 = fp32 store (alpha only), 1 = bf16 store (alpha only), 2 = fp32 read-modify-write
+template <int TM, int TN, int WM, int WN, int NT_BK, bool B_F32, int OUT, int MINB>
+__global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunch L) {
+    constexpr bool OUT_BF16 = (OUT == 1);
+    constexpr bool RMW = (OUT == 2);
+    static_assert(WM * WN == 4, "four waves");
+    constexpr int NT_KP = NT_BK + 8;
+    constexpr int FM = TM / WM / 32, FN = TN / WN / 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+    constexpr int A_ELEMS = TM * NT_KP, B_ELEMS = TN * NT_KP, BUF = A_ELEMS + B_ELEMS;
+
+    const NtTile t = L.tiles[blockIdx.x];
+    if (t.prob < 0) return;
+    const NtProblem* pp = L.probs + t.prob;
+    const void* A = pp->A;
+    const void* B = pp->B;
+    const long long lda = pp->lda, ldb = pp->ldb, ldc = pp->ldc;
+    const int M = pp->M, N = pp->N, K = pp->K;
+    const float alpha = L.alpha, beta = L.beta;
+    const int kbeg = t.ks * pp->kchunk;
+    const int kend = min(K, kbeg + pp->kchunk);
+    const int row0 = t.tm * TM, col0 = t.tn * TN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const bool a_vec = (((unsigned long long)A) % 16 == 0) && ((lda * 2) % 16 == 0);
+    const bool b_vec = (((unsigned long long)B) % 16 == 0) && ((ldb * (B_F32 ? 4 : 2)) % 16 == 0);
+
+    // For the read-modify-write epilogue the C tile is fetched into registers before the k-loop
+    // and only consumed after it, so its HBM latency hides behind the whole loop.
+    f32x16 cold[RMW ? FM : 1][RMW ? FN : 1];
+    const float out_scale = alpha;
+    const bool skip_products = RMW && alpha == 0.0f;
+    if constexpr (RMW) {
+        const float* C = (const float*)pp->C + (long long)t.ks * pp->c_split_stride;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
+                const int rbase = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = rbase + (e >> 2) * 8 + (e & 3);
+                    cold[i][j][e] = (row < M && col < N) ? C[(long long)row * ldc + col] : 0.0f;
+                }
+            }
+    }
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // Two k-tiles travel in registers ahead of the one being multiplied (ring of two register
+    // stages), one more sits in the other LDS buffer: global latency hides behind two k-tiles of
+    // MFMAs per workgroup.  The read-modify-write variant keeps one stage only (its k-loop is
+    // short and its registers hold the C tile).
+    constexpr int NSTAGE = RMW ? 1 : 2;
+    NtStage<TM * NT_BK / 8 / NT_THREADS, false> stA[NSTAGE];
+    NtStage<TN * NT_BK / 8 / NT_THREADS, B_F32> stB[NSTAGE];
+    const int nk = (kend > kbeg && !skip_products) ? (kend - kbeg + NT_BK - 1) / NT_BK : 0;
+
+    auto load = [&](int slot, int tile) {
+        const int k0 = kbeg + tile * NT_BK;
+        nt_load<TM, NT_BK, false>(stA[slot], A, lda, M, row0, k0, kend, a_vec, tid);
+        nt_load<TN, NT_BK, B_F32>(stB[slot], B, ldb, N, col0, k0, kend, b_vec, tid);
+    };
+    auto store = [&](int slot, int buf) {
+        unsigned short* d = lds + buf * BUF;
+        nt_store<TM, NT_BK, false>(stA[slot], d, tid);
+        nt_store<TN, NT_BK, B_F32>(stB[slot], d + A_ELEMS, tid);
+    };
+    auto compute = [&](int buf) {
+        const unsigned short* sA = lds + buf * BUF;
+        const unsigned short* sB = sA + A_ELEMS;
+#pragma unroll
+        for (int kk = 0; kk < NT_BK / 16; ++kk) {
+            const int kofs = kk * 16 + (lane >> 5) * 8;
+            bf16x8 fa[FM], fb[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+                fa[i] = *(const bf16x8*)(sA + (wm * (FM * 32) + i * 32 + (lane & 31)) * NT_KP + kofs);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                fb[j] = *(const bf16x8*)(sB + (wn * (FN * 32) + j * 32 + (lane & 31)) * NT_KP + kofs);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    if constexpr (NSTAGE == 2) {
+        // prologue: tile 0 -> LDS buffer 0; tiles 1 and 2 -> register stages 1 and 0
+        if (nk > 0) {
+            load(0, 0);
+            store(0, 0);
+            __syncthreads();
+            if (nk > 1) load(1, 1);
+            if (nk > 2) load(0, 2);
+        }
+        // iteration `it` multiplies LDS buffer it&1, moves tile it+1 (register stage (it+1)&1) into
+        // the other buffer and refills that stage with tile it+3
+        for (int it = 0; it < nk; it += 2) {
+            compute(0);
+            if (it + 1 < nk) store(1, 1);
+            __syncthreads();
+            if (it + 3 < nk) load(1, it + 3);
+            if (it + 1 < nk) {
+                compute(1);
+                if (it + 2 < nk) store(0, 0);
+                __syncthreads();
+                if (it + 4 < nk) load(0, it + 4);
+            }
+        }
+    } else {
+        if (nk > 0) {
+            load(0, 0);
+            store(0, 0);
+            __syncthreads();
+            if (nk > 1) load(0, 1);
+        }
+        for (int it = 0; it < nk; ++it) {
+            compute(it & 1);
+            if (it + 1 < nk) store(0, (it + 1) & 1);
+            __syncthreads();
+            if (it + 2 < nk) load(0, it + 2);
+        }
+    }
+
+    // epilogue: lane holds column (lane & 31); rows 8*(e/4) + 4*(lane>>5) + e%4 of each 32x32 tile
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
+            const int rbase = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4;
+            if (col >= N) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = rbase + (e >> 2) * 8 + (e & 3);
+                if (row >= M) continue;
+                if constexpr (OUT_BF16) {
+                    unsigned short* C = (unsigned short*)pp->C;
+                    C[(long long)row * ldc + col] = f32_to_bf16_bits(out_scale * acc[i][j][e]);
+                } else {
+                    float* C = (float*)pp->C + (long long)t.ks * pp->c_split_stride;
+                    float v = out_scale * acc[i][j][e];
+                    if constexpr (RMW) v += beta * cold[i][j][e];
+                    C[(long long)row * ldc + col] = v;
+                }
+            }
+        }
+}
+
+// ------------------------------------------------------------------ dispatch
+typedef void (*nt_fn)(const NtLaunch);
+struct NtEntry { int shape, b_f32, out; nt_fn fn; int lds_bytes; };
+
+#define NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, bf32, out) \
+    { shape, bf32, out, nt_gemm_kernel<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>, 2 * (TM + TN) * (BK + 8) * 2 }
+// MINB / MINB_RMW: workgroups per CU the register allocation must allow (the read-modify-write
+// variant also holds the C tile in registers)
+#define NT_SHAPE(shape, TM, TN, WM, WN, BK, MINB, MINB_RMW)                                                   \
+    NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, 0, 0), NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, 0, 1),         \
+    NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB_RMW, 0, 2), NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, 1, 0),     \
+    NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, 1, 1)
+
+static const NtEntry kNt[] = {
+    NT_SHAPE(NT_128x128, 128, 128, 2, 2, 64, 2, 1), NT_SHAPE(NT_256x64, 256, 64, 4, 1, 64, 1, 1),
+    NT_SHAPE(NT_64x256, 64, 256, 1, 4, 64, 1, 1),   NT_SHAPE(NT_64x64, 64, 64, 2, 2, 64, 4, 4),
+    NT_SHAPE(NT_128x128_K32, 128, 128, 2, 2, 32, 3, 2), NT_SHAPE(NT_256x64_K32, 256, 64, 4, 1, 32, 3, 2),
+    NT_SHAPE(NT_256x128_K32, 256, 128, 2, 2, 32, 2, 1), NT_SHAPE(NT_128x256_K32, 128, 256, 2, 2, 32, 2, 1),
+    NT_SHAPE(NT_256x128, 256, 128, 2, 2, 64, 1, 1),
+};
+
+hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream) {
+    if (L.n_tiles <= 0) return hipSuccess;
+    const int out = v.out_bf16 ? 1 : (L.beta != 0.0f ? 2 : 0);
+    for (const NtEntry& e : kNt) {
+        if (e.shape == v.shape && e.b_f32 == v.b_f32 && e.out == out) {
+            static thread_local const void* configured[128] = {nullptr};
+            bool done = false;
+            for (const void* c : configured) if (c == (const void*)e.fn) { done = true; break; }
+            if (!done) {
+                hipError_t er = hipFuncSetAttribute((const void*)e.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                    e.lds_bytes);
+                if (er != hipSuccess) return er;
+                for (const void*& c : configured) if (c == nullptr) { c = (const void*)e.fn; break; }
+            }
+            hipLaunchKernelGGL(e.fn, dim3(L.n_tiles), dim3(NT_THREADS), e.lds_bytes, stream, L);
+            return hipGetLastError();
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------ bf16 shadows of the bases
+// One workgroup converts a 64 x 64 patch: Xb[row][c] and, through LDS, XTb[c][row].
+__global__ __launch_bounds__(256) void shadow_kernel(const ShadowBlock* table) {
+    const ShadowBlock b = table[blockIdx.z];
+    const int rows = b.rows, r = b.r;
+    const int row0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    // patches cover the padded extents (ldx columns, ldt columns of the transpose)
+    if (row0 >= (int)b.ldt || c0 >= (int)b.ldx) return;
+    __shared__ unsigned short tile[64][66];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    unsigned short* Xb = (unsigned short*)b.Xb;
+    unsigned short* XTb = (unsigned short*)b.XTb;
+    for (int i = ty; i < 64; i += 4) {
+        const int row = row0 + i, c = c0 + tx;
+        const float v = (row < rows && c < r) ? b.X[(long long)row * r + c] : 0.0f;
+        const unsigned short h = f32_to_bf16_bits(v);
+        tile[i][tx] = h;
+        if (row < rows && c < (int)b.ldx) Xb[(long long)row * b.ldx + c] = h;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int c = c0 + i, row = row0 + tx;
+        if (c < r && row < (int)b.ldt) XTb[(long long)c * b.ldt + row] = tile[tx][i];
+    }
+}
+
+hipError_t launch_shadows(const ShadowBlock* table_dev, int blocks, int max_rows, int max_r, hipStream_t stream) {
+    if (blocks <= 0) return hipSuccess;
+    dim3 grid((max_r + 8 + 63) / 64, (max_rows + 8 + 63) / 64, blocks);
+    hipLaunchKernelGGL(shadow_kernel, grid, dim3(256), 0, stream, table_dev);
+    return hipGetLastError();
+}
+
+}  // namespace tsr

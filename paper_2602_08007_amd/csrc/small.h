@@ -15,8 +15,20 @@ struct AdamScalars { float beta1, beta2, eps, inv_c1, inv_c2; };
 
 hipError_t launch_adam(const CoreBlock* table_dev, const CoreBlock* single, int blocks,
                        long long max_count, const AdamScalars& s, hipStream_t stream);
+// Adam on square r x r cores that also writes D^T as bf16 (leading dimension ldt), the operand
+// layout the bf16 lift GEMM U D = U (D^T)^T consumes.
+struct AdamTBlock {
+    const float* C; float* M; float* Vm; float* D;
+    void* DTb; int r; long long ldt;
+};
+hipError_t launch_adam_t(const AdamTBlock* table_dev, int blocks, int max_r, const AdamScalars& s,
+                         hipStream_t stream);
 hipError_t launch_sgd(const float* C, float* M, float* D, long long count, float beta, hipStream_t stream);
 hipError_t launch_average(const float* Cs, int K, long long count, float* out, hipStream_t stream);
+
+// ---- plain streaming kernel dst[i] = scale * src[i] (dst may equal src): the measured HBM
+// rate of the machine and the calibration of the memory-traffic counters
+hipError_t launch_stream(float* dst, const float* src, long long count, float scale, hipStream_t stream);
 
 // ---- Cholesky-based orth helper: from the k x k Gram matrix S (fp32, symmetric) of a
 // tall matrix Y compute, in fp64, S = R^T R and write

@@ -37,6 +37,48 @@ hipError_t launch_adam(const CoreBlock* table_dev, const CoreBlock* single, int 
     return hipGetLastError();
 }
 
+// 32 x 32 patch per workgroup (256 threads = 32 x 8): coalesced reads and writes of the fp32
+// arrays, LDS transpose for the bf16 D^T.
+__global__ __launch_bounds__(256) void adam_t_kernel(const AdamTBlock* table, const AdamScalars s) {
+    const AdamTBlock b = table[blockIdx.z];
+    const int r = b.r;
+    const int row0 = blockIdx.y * 32, col0 = blockIdx.x * 32;
+    if (row0 >= r || col0 >= r) return;
+    __shared__ unsigned short tile[32][34];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const float omb1 = 1.0f - s.beta1, omb2 = 1.0f - s.beta2;
+    for (int i = ty; i < 32; i += 8) {
+        const int row = row0 + i, col = col0 + tx;
+        float d = 0.0f;
+        if (row < r && col < r) {
+            const long long idx = (long long)row * r + col;
+            const float g = b.C[idx];
+            const float m = s.beta1 * b.M[idx] + omb1 * g;
+            const float v = s.beta2 * b.Vm[idx] + omb2 * (g * g);
+            b.M[idx] = m;
+            b.Vm[idx] = v;
+            d = (m * s.inv_c1) / (sqrtf(v * s.inv_c2) + s.eps);
+            b.D[idx] = d;
+        }
+        __bf16 h = (__bf16)d;
+        tile[i][tx] = __builtin_bit_cast(unsigned short, h);
+    }
+    __syncthreads();
+    unsigned short* DT = (unsigned short*)b.DTb;
+    for (int i = ty; i < 32; i += 8) {
+        const int trow = col0 + i, tcol = row0 + tx;     // D^T[col][row]
+        if (trow < r && tcol < r) DT[(long long)trow * b.ldt + tcol] = tile[tx][i];
+    }
+}
+
+hipError_t launch_adam_t(const AdamTBlock* table_dev, int blocks, int max_r, const AdamScalars& s,
+                         hipStream_t stream) {
+    if (blocks <= 0 || max_r <= 0) return hipSuccess;
+    const int g = (max_r + 31) / 32;
+    hipLaunchKernelGGL(adam_t_kernel, dim3(g, g, blocks), dim3(256), 0, stream, table_dev, s);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void sgd_kernel(const float* C, float* M, float* D, long long n, float beta) {
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (long long)gridDim.x * blockDim.x) {
@@ -69,6 +111,26 @@ hipError_t launch_average(const float* Cs, int K, long long count, float* out, h
     long long bx = (count + 255) / 256;
     if (bx > 4096) bx = 4096;
     hipLaunchKernelGGL(average_kernel, dim3((unsigned)bx), dim3(256), 0, stream, Cs, K, count, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ stream calibration
+typedef __attribute__((ext_vector_type(4))) float f32x4_s;
+__global__ __launch_bounds__(256) void stream_kernel(f32x4_s* dst, const f32x4_s* src, long long n4, float scale) {
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+         i += (long long)gridDim.x * blockDim.x) {
+        f32x4_s v = src[i];
+        dst[i] = v * scale;
+    }
+}
+
+hipError_t launch_stream(float* dst, const float* src, long long count, float scale, hipStream_t stream) {
+    const long long n4 = count / 4;
+    if (n4 <= 0) return hipSuccess;
+    long long bx = (n4 + 255) / 256;
+    if (bx > 256 * 32) bx = 256 * 32;
+    hipLaunchKernelGGL(stream_kernel, dim3((unsigned)bx), dim3(256), 0, stream, (f32x4_s*)dst, (const f32x4_s*)src, n4,
+                       scale);
     return hipGetLastError();
 }
 

@@ -78,7 +78,7 @@ def test_argument_validation_happens_on_the_host(tsr):
     assert r(fake, 0, 64, 32, 32, fake, 16, 4, -1, fake, fake, null, ws, 1 << 30, null) == -1
     assert r(fake, 0, 64, 32, 32, fake, 16, 4, 1, fake, fake, null, ws, 64, null) == -4
     # plan
-    assert lib.tsr_plan_workspace_bytes(None, 0, 1, 0, 0) == 0
+    assert lib.tsr_plan_workspace_bytes(None, 0, 1, 0, 0, 0) == 0
     assert lib.tsr_step_batched(None, 1, None, null) == -1
 
 
@@ -87,9 +87,11 @@ def test_plan_workspace_counts_every_block(tsr):
     for i, (m, n) in enumerate([(768, 768), (768, 2048)]):
         d[i].m, d[i].n, d[i].r, d[i].ldg, d[i].ldw, d[i].g_dtype = m, n, 256, n, n, 1
         d[i].g_stride = m * n
-    one = tsr.lib.tsr_plan_workspace_bytes(d, 1, 1, 0, 0)
-    two = tsr.lib.tsr_plan_workspace_bytes(d, 2, 1, 0, 0)
-    two8 = tsr.lib.tsr_plan_workspace_bytes(d, 2, 8, 0, 0)
-    with_refresh = tsr.lib.tsr_plan_workspace_bytes(d, 2, 1, 1, 8)
-    assert 0 < one < two < two8 and two < with_refresh
-    assert two >= 2 * 768 * 256 * 4
+    for prec in (0, 1):
+        one = tsr.lib.tsr_plan_workspace_bytes(d, 1, 1, prec, 0, 0)
+        two = tsr.lib.tsr_plan_workspace_bytes(d, 2, 1, prec, 0, 0)
+        two8 = tsr.lib.tsr_plan_workspace_bytes(d, 2, 8, prec, 0, 0)
+        with_refresh = tsr.lib.tsr_plan_workspace_bytes(d, 2, 1, prec, 1, 8)
+        assert 0 < one < two < two8 and two < with_refresh
+        assert two >= 2 * 768 * 256 * 2
+    assert tsr.lib.tsr_plan_workspace_bytes(d, 2, 1, 9, 0, 0) == 0

@@ -310,7 +310,22 @@ def test_config1_refresh_then_ten_steps(tsr):
 
 
 # ------------------------------------------------------------------ batched plan
-def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3):
+SENTINEL = 12345.0
+
+
+def guarded(x: torch.Tensor, extra_rows=3, extra_cols=8):
+    """GPU copy of x as a view inside a larger buffer whose surroundings hold a sentinel."""
+    m, n = x.shape
+    full = torch.full((m + extra_rows, n + extra_cols), SENTINEL, dtype=x.dtype, device="cuda")
+    full[:m, :n] = x.to("cuda")
+    return full[:m, :n], full
+
+
+def guards_intact(full: torch.Tensor, m: int, n: int) -> bool:
+    return bool((full[m:, :] == SENTINEL).all() and (full[:m, n:] == SENTINEL).all())
+
+
+def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3, guard_w=False):
     blocks, host = [], []
     for i, (m, n) in enumerate(shapes):
         k = si.stream_key(key, i)
@@ -319,14 +334,17 @@ def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3):
         U, V = bases(m, n, r, k)
         W0 = si.weights(m, n, si.stream_key(k, 4))
         host.append(dict(G=Gs, U=U, V=V, W=W0))
-        blocks.append(dict(G=dev(Gs) if workers > 1 else dev(Gs[0]), W=dev(W0), U=dev(U), V=dev(V),
+        Wd, Wfull = guarded(W0) if guard_w else (dev(W0), None)
+        host[-1]["W_full"] = Wfull
+        blocks.append(dict(G=dev(Gs) if workers > 1 else dev(Gs[0]), W=Wd, U=dev(U), V=dev(V),
                            M=torch.zeros(r, r, device="cuda"), Vm=torch.zeros(r, r, device="cuda"),
                            C=torch.empty(r, r, device="cuda"), D=torch.empty(r, r, device="cuda")))
     return blocks, host
 
 
 @pytest.mark.parametrize("workers,g_dtype,prec", [(1, torch.float32, "split"), (1, torch.bfloat16, "bf16"),
-                                                  (3, torch.bfloat16, "split")])
+                                                  (3, torch.bfloat16, "split"), (3, torch.bfloat16, "bf16"),
+                                                  (1, torch.float32, "bf16")])
 def test_step_batched_matches_oracle(tsr, workers, g_dtype, prec):
     shapes = [(256, 256), (256, 688), (688, 256), (200, 333), (256, 256)]
     r = 32
@@ -345,6 +363,70 @@ def test_step_batched_matches_oracle(tsr, workers, g_dtype, prec):
             assert max(errs) < tol, (t, errs)
     core, dense = plan.payload_bytes(4)
     assert core == len(shapes) * r * r * 4 and dense == 4 * sum(m * n for m, n in shapes)
+    plan.close()
+
+
+@pytest.mark.parametrize("r", [64, 128, 256])
+@pytest.mark.parametrize("workers", [1, 2])
+def test_bf16_plan_fused_lift_ranks(tsr, r, workers):
+    # ranks served by the fused lift kernel, on ragged shapes (partial row panels, partial
+    # column tiles, odd leading dimensions) and with weight decay
+    shapes = [(r + 37, 2 * r + 61), (3 * r + 5, r), (r, r), (2 * r, 5 * r + 130), (r + 1, 2 * r + 4)]
+    blocks, host = make_blocks(shapes, r, workers, torch.bfloat16, si.stream_key(631, r), guard_w=True)
+    plan = tsr.Plan(blocks, n_workers=workers, precision=tsr.TSR_PREC_BF16)
+    state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
+    for t in (1, 2):
+        plan.tsr_step_batched(t, lr=1e-3, wd=0.05)
+        torch.cuda.synchronize()
+        for b, h, s in zip(blocks, host, state):
+            W_before = s["W"].copy()
+            Cbar, D = orc.tsr_adam_step(s["W"], [g for g in h["G"]], h["U"], h["V"], s["M"], s["Vm"], t, lr=f32(1e-3),
+                                        wd=f32(0.05), beta1=B1, beta2=B2, eps=EPS)
+            assert rel_fro(b["C"], Cbar) < TOL_BF16
+            # the lift itself, from the GPU's own D (at t = 1 the oracle's D is sign(c), which a
+            # bf16 core flips for the smallest entries; these tiny blocks would show that, not
+            # the kernel): updated weights and the movement relative to the movement
+            W_k = orc.backproject_apply(W_before.copy(), h["U"], h["V"], orc.f64(b["D"]), f32(1e-3), f32(0.05))
+            assert rel_fro(b["W"], W_k) < TOL_BF16
+            moved_gpu = orc.f64(b["W"]) - W_before
+            # GPU W started from its own previous W; compare movements (both include the decay term)
+            assert rel_fro(moved_gpu, W_k - W_before) < 3e-2, (t, rel_fro(moved_gpu, W_k - W_before))
+            s["W"][...] = orc.f64(b["W"])       # keep the trajectories together for the next step
+            assert guards_intact(h["W_full"], *b["W"].shape)    # nothing written outside the m x n block
+    plan.close()
+
+
+def test_bf16_plan_follows_changed_bases(tsr):
+    # the bf16 plan keeps bf16 copies of the bases: after the caller rewrites U, V and says
+    # so, the next step must use the new ones
+    shapes = [(320, 448), (130, 257)]
+    r = 64
+    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, 611)
+    plan = tsr.Plan(blocks, precision=tsr.TSR_PREC_BF16)
+    plan.tsr_step_batched(1, lr=1e-3)
+    for i, (b, h, (m, n)) in enumerate(zip(blocks, host, shapes)):
+        U2, V2 = bases(m, n, r, si.stream_key(612, i))
+        h["U"], h["V"] = U2, V2
+        b["U"].copy_(U2); b["V"].copy_(V2)
+    plan.tsr_plan_bases_changed()
+    plan.tsr_step_batched(2, lr=1e-3)
+    torch.cuda.synchronize()
+    for b, h in zip(blocks, host):
+        C_ref = orc.project_core(h["G"][0], h["U"], h["V"])
+        assert rel_fro(b["C"], C_ref) < TOL_BF16
+    plan.close()
+
+
+@pytest.mark.parametrize("prec", ["split", "bf16"])
+def test_zero_learning_rate_leaves_weights_untouched(tsr, prec):
+    shapes = [(256, 384), (130, 257)]
+    blocks, host = make_blocks(shapes, 32, 1, torch.bfloat16, 621)
+    W0 = [b["W"].clone() for b in blocks]
+    plan = tsr.Plan(blocks, precision=tsr.TSR_PREC_SPLIT if prec == "split" else tsr.TSR_PREC_BF16)
+    plan.tsr_step_batched(1, lr=0.0, wd=0.1)
+    torch.cuda.synchronize()
+    for b, w0 in zip(blocks, W0):
+        assert torch.equal(b["W"], w0)
     plan.close()
 
 
