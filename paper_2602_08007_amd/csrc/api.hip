@@ -270,16 +270,18 @@ void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool o
 
 int run_orth(const OrthProgram& op, bool grouped, Ctx& cx) {
     const int nb = (int)op.chol1.size();
+    int max_k = 0;
+    for (const CholBlock& cb : op.chol1) max_k = std::max(max_k, cb.k);
     TSR_TRY(run_stage(op.gram1, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     {
         Timed timed(cx, TSR_PROF_CHOL);
-        TSR_HIP(launch_chol_inv(grouped ? op.d_chol1 : nullptr, grouped ? nullptr : &op.chol1[0], nb, 1e-6, cx.s));
+        TSR_HIP(launch_chol_inv(grouped ? op.d_chol1 : nullptr, grouped ? nullptr : &op.chol1[0], nb, max_k, 1e-6, cx.s));
     }
     TSR_TRY(run_stage(op.q1, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     TSR_TRY(run_stage(op.gram2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     {
         Timed timed(cx, TSR_PROF_CHOL);
-        TSR_HIP(launch_chol_inv(grouped ? op.d_chol2 : nullptr, grouped ? nullptr : &op.chol2[0], nb, 1e-6, cx.s));
+        TSR_HIP(launch_chol_inv(grouped ? op.d_chol2 : nullptr, grouped ? nullptr : &op.chol2[0], nb, max_k, 1e-6, cx.s));
     }
     return run_stage(op.q2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM);
 }
@@ -340,7 +342,9 @@ int run_refresh(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
     TSR_TRY(run_orth(rp.orthZ, grouped, cx));
     {
         Timed timed(cx, TSR_PROF_JACOBI);
-        TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), cx.s));
+        int max_k = 0;
+        for (const JacobiBlock& jb : rp.jac) max_k = std::max(max_k, jb.k);
+        TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
     }
     TSR_TRY(run_stage(rp.uout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
     return run_stage(rp.vout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM);

@@ -42,7 +42,7 @@ struct CholBlock {
     double* work;
     int k;
 };
-hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, int blocks,
+hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, int blocks, int max_k,
                            double tol, hipStream_t stream);
 
 // ---- one-sided Jacobi SVD of the k x k upper-triangular factor R (fp64, destroyed):
@@ -54,7 +54,7 @@ struct JacobiBlock {
     float* XrT; float* GrT; float* sigma;
     int k, r;
 };
-hipError_t launch_jacobi(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks,
+hipError_t launch_jacobi(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
                          hipStream_t stream);
 
 }  // namespace tsr
