@@ -315,7 +315,7 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Z, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
         uo.push_back(LogicalGemm{b.Y, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
         vo.push_back(LogicalGemm{b.Z, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
-        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.XrT, b.GrT, b.sigma, b.k, b.r});
+        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r});
     }
     for (int d = 0; d < 2; ++d) {
         build_stage(rp.sketch[d], variant(0, 1, d, 2, 2), sk[d], ar);

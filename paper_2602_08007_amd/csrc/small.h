@@ -45,12 +45,13 @@ struct CholBlock {
 hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, int blocks, int max_k,
                            double tol, hipStream_t stream);
 
-// ---- one-sided Jacobi SVD of the k x k upper-triangular factor R (fp64, destroyed):
-// rows of R are rotated until mutually orthogonal: Gacc R = diag(sigma) X^T.  Outputs, for the
-// r largest sigma in descending order: XrT (r x k fp32) rows x_j^T, GrT (r x k fp32) rows
-// of Gacc, and sigma (k fp32, optional, all k values descending).  Gacc = k x k doubles of work.
+// ---- SVD of the k x k upper-triangular factor R (fp64): an orthogonal Gacc with
+// Gacc R = diag(sigma) X^T (rows mutually orthogonal), from the symmetric eigenproblem of R R^T.
+// Outputs, for the r largest sigma in descending order: XrT (r x k fp32) rows x_j^T, GrT
+// (r x k fp32) rows of Gacc, and sigma (k fp32, optional, all k values descending).
+// Gacc and tmp are k x k doubles of work each.
 struct JacobiBlock {
-    double* R; double* Gacc;
+    double* R; double* Gacc; double* tmp;
     float* XrT; float* GrT; float* sigma;
     int k, r;
 };

@@ -366,7 +366,17 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
             double sacc = 0.0;
             if (ti < ib) {
                 const double* lrow = A + (size_t)(I * CHB + ti) * k;
-                for (int c = J * CHB; c < I * CHB; ++c) sacc += lrow[c] * X[(size_t)c * k + J * CHB + tc];
+                // independent partial sums keep several loads in flight
+                double pa[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+                const double* xcol = X + J * CHB + tc;
+                for (int c = J * CHB; c < I * CHB; c += 8) {      // both bounds are multiples of 32
+                    double xv[8], lv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) { xv[u] = xcol[(size_t)(c + u) * k]; lv[u] = lrow[c + u]; }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) pa[u] += lv[u] * xv[u];
+                }
+                sacc = ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pa[4] + pa[5]) + (pa[6] + pa[7]));
             }
             Ld[ti][tc] = sacc;
             __syncthreads();
@@ -398,7 +408,17 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
                 if (Rp == nullptr) {
                     sacc = A[(size_t)b * k + a];
                 } else {
-                    for (int c = a; c <= b; ++c) sacc += A[(size_t)c * k + a] * Rp[(size_t)c * k + b];
+                    double pa[4] = {0.0, 0.0, 0.0, 0.0};
+                    int c = a;
+                    for (; c + 3 <= b; c += 4) {
+                        double av[4], rv[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) { av[u] = A[(size_t)(c + u) * k + a]; rv[u] = Rp[(size_t)(c + u) * k + b]; }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) pa[u] += av[u] * rv[u];
+                    }
+                    for (; c <= b; ++c) pa[0] += A[(size_t)c * k + a] * Rp[(size_t)c * k + b];
+                    sacc = (pa[0] + pa[1]) + (pa[2] + pa[3]);
                 }
             }
             Rtot[idx] = sacc;
@@ -434,182 +454,276 @@ __device__ inline double wave_sum(double v) {
     return v;
 }
 
-constexpr int JAC_MAX_SWEEPS = 40;
 
-// Pair (i, j) of slot s in round rr of a round-robin tournament of n players (n even): every
-// pair meets exactly once over rounds 0 .. n-2 and the pairs of one round are disjoint.
-__device__ inline void tournament_pair(int n, int rr, int s, int& i, int& j) {
-    i = (rr + s) % (n - 1);
-    j = (s == 0) ? (n - 1) : (rr + n - 1 - s) % (n - 1);
-}
+// SVD of the k x k factor R through the symmetric eigenproblem of its Gram matrix, all in
+// fp64 inside one workgroup:
+//   T = R R^T ;  T = E diag(lambda) E^T  (Householder tridiagonalization + implicit QL with
+//   accumulation of E^T) ;  rows of E^T R are mutually orthogonal with norms sigma_i.
+// Squaring costs relative accuracy of singular values below 1e-8 sigma_1, far below the fp32
+// data R was built from.  Compared with sweeping Jacobi rotations over full rows this needs
+// about k^2 rotations in total (each applied to one k-vector held across the threads) instead
+// of ~10 sweeps of k^2/2 rotations on 2k-vectors, and everything else is matrix products.
+// Outputs as before: R is overwritten by E^T R, Gacc = E^T.
+constexpr int QL_MAX_ITER = 60;
 
-// Block one-sided Jacobi on the rows of R (k x k, fp64): rows are grouped into blocks of B2/2;
-// for every pair of blocks (outer tournament) the B2 rows are brought into LDS and swept once
-// (inner tournament, one wave per row pair, B2/2 disjoint pairs per inner round), the B2 x B2
-// product of the plane rotations is accumulated next to them and then applied to the same
-// rows of Gacc.  All rotation work runs out of LDS; R and Gacc cross L2 once per block pair.
-template <int B2>
 __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock* table, const JacobiBlock single) {
     const JacobiBlock* blk = table ? table + blockIdx.x : &single;
     const int k = blk->k, r = blk->r;
     double* R = blk->R;
-    double* G = blk->Gacc;
+    double* W = blk->Gacc;              // rows become the eigenvectors (E^T)
+    double* T = blk->tmp;               // Gram matrix, later E^T R
     const int tid = threadIdx.x, nt = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
-    constexpr int BH = B2 / 2;                   // rows per block
-    constexpr int JAC_PER_LANE = (B2 == 32) ? 9 : SMALL_MAXK / 64;   // row elements held by one lane (k <= 576 / 1024)
-    constexpr int QP = B2 + 1;                   // padded row of the rotation accumulator
-    extern __shared__ double sm[];
-    double* X = sm;                              // [B2][k]   rows of the block pair
-    double* Q = sm + (size_t)B2 * k;             // [B2][QP]  accumulated rotations
-    __shared__ int s_rot_sweep, s_rot_pair;
-    __shared__ int s_grow[B2];                   // global row of each local row of the block pair, -1 = none
-    __shared__ double s_sig[SMALL_MAXK];
+    __shared__ double s_d[SMALL_MAXK];      // diagonal, later eigenvalues / singular values
+    __shared__ double s_e[SMALL_MAXK];      // sub-diagonal
+    __shared__ double s_v[SMALL_MAXK];      // Householder vector / rotation cosines
+    __shared__ double s_w[SMALL_MAXK];      // work vector / rotation sines
+    __shared__ double s_red[SMALL_THREADS / 64];
+    __shared__ int s_int[4];
     __shared__ int s_rank[SMALL_MAXK];
-    const double tol = 1e-11;
 
-    for (int idx = tid; idx < k * k; idx += nt) G[idx] = (idx / k == idx % k) ? 1.0 : 0.0;
+    auto block_sum = [&](double v) -> double {      // sum over the workgroup, result to all
+        v = wave_sum(v);
+        __syncthreads();
+        if (lane == 0) s_red[wave] = v;
+        __syncthreads();
+        double t = 0.0;
+        for (int i = 0; i < nw; ++i) t += s_red[i];
+        return t;
+    };
+
+    // ---- T = R R^T (4 x 4 register tiles), W = I
+    {
+        const int tiles = (k + 3) >> 2;
+        for (int q = tid; q < tiles * tiles; q += nt) {
+            const int i0 = (q / tiles) * 4, j0 = (q % tiles) * 4;
+            double acc[4][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+            for (int c = 0; c < k; ++c) {
+                double a[4], b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    a[u] = (i0 + u < k) ? R[(size_t)(i0 + u) * k + c] : 0.0;
+                    b[u] = (j0 + u < k) ? R[(size_t)(j0 + u) * k + c] : 0.0;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[u][v] += a[u] * b[v];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (i0 + u < k && j0 + v < k) T[(size_t)(i0 + u) * k + j0 + v] = acc[u][v];
+        }
+        for (int idx = tid; idx < k * k; idx += nt) W[idx] = (idx / k == idx % k) ? 1.0 : 0.0;
+    }
     __syncthreads();
 
-    const int nbk = (k + BH - 1) / BH;           // real blocks
-    const int nbe = (nbk < 2) ? 2 : nbk + (nbk & 1);   // players of the outer tournament
-    const int per = (k + 63) / 64;
-    for (int sweep = 0; sweep < JAC_MAX_SWEEPS; ++sweep) {
-        if (tid == 0) s_rot_sweep = 0;
+    // ---- Householder tridiagonalization of T (full symmetric storage), W <- H_j W as we go
+    for (int j = 0; j + 2 < k; ++j) {
+        const int n1 = k - j - 1;                       // length of the column below the diagonal
+        // x = T[j+1.., j]; alpha = -sign(x0) |x|; v = x - alpha e1; H = I - beta v v^T
+        double part = 0.0;
+        for (int i = tid; i < n1; i += nt) { const double x = T[(size_t)(j + 1 + i) * k + j]; s_v[i] = x; part += x * x; }
+        const double xnorm2 = block_sum(part);
+        const double x0 = s_v[0];
+        const double xn = sqrt(xnorm2);
+        double alpha = (x0 >= 0.0) ? -xn : xn;
+        const double vnorm2 = xnorm2 - 2.0 * alpha * x0 + alpha * alpha;     // |x - alpha e1|^2
+        const bool skip = (xnorm2 - x0 * x0 <= 0.0) || vnorm2 <= 0.0;        // already tridiagonal here
+        if (skip) alpha = x0;
         __syncthreads();
-        for (int orr = 0; orr < nbe - 1; ++orr) {
-            for (int os = 0; os < nbe / 2; ++os) {
-                int bi, bj;
-                tournament_pair(nbe, orr, os, bi, bj);
-                if (bi >= nbk && bj >= nbk) continue;
-                // local row l < BH: row bi*BH + l, else row bj*BH + (l - BH); -1 = no such row
-                if (tid < B2) {
-                    const int l = tid;
-                    const int g = (l < BH) ? bi * BH + l : bj * BH + (l - BH);
-                    const int bb = (l < BH) ? bi : bj;
-                    s_grow[l] = (bb < nbk && g < k) ? g : -1;
-                }
-                __syncthreads();
-                auto grow = [&](int l) -> int { return s_grow[l]; };
-                for (int idx = tid; idx < B2 * k; idx += nt) {
-                    const int l = idx / k, c = idx % k;
-                    const int g = grow(l);
-                    X[idx] = (g >= 0) ? R[(size_t)g * k + c] : 0.0;
-                }
-                for (int idx = tid; idx < B2 * QP; idx += nt) Q[idx] = (idx / QP == idx % QP) ? 1.0 : 0.0;
-                if (tid == 0) s_rot_pair = 0;
-                __syncthreads();
-#pragma unroll 1
-                for (int irr = 0; irr < B2 - 1; ++irr) {
-                    if (wave < B2 / 2) {
-                        int li, lj;
-                        tournament_pair(B2, irr, wave, li, lj);
-                        if (grow(li) >= 0 && grow(lj) >= 0) {
-                            const int p = min(li, lj), q = max(li, lj);
-                            double* xp = X + (size_t)p * k;
-                            double* xq = X + (size_t)q * k;
-                            double x[JAC_PER_LANE], y[JAC_PER_LANE];
-                            double a = 0.0, b = 0.0, g = 0.0;
+        if (tid == 0) { s_d[j] = T[(size_t)j * k + j]; s_e[j] = alpha; if (!skip) s_v[0] = x0 - alpha; }
+        __syncthreads();
+        if (skip) continue;
+        const double beta = 2.0 / vnorm2;
+        // p = beta T22 v   (T22 symmetric: read columns as rows, coalesced over the output index)
+        for (int i = tid; i < n1; i += nt) {
+            // eight independent partial sums keep eight loads in flight (the sum is a serial chain)
+            double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+            const double* col = T + (size_t)(j + 1) * k + (j + 1 + i);
+            int c = 0;
+            for (; c + 8 <= n1; c += 8) {
+                double x[8];
 #pragma unroll
-                            for (int e = 0; e < JAC_PER_LANE; ++e) {
-                                const int c = lane + 64 * e;
-                                if (e < per && c < k) {
-                                    x[e] = xp[c]; y[e] = xq[c];
-                                    a += x[e] * x[e]; b += y[e] * y[e]; g += x[e] * y[e];
-                                } else {
-                                    x[e] = 0.0; y[e] = 0.0;
-                                }
-                            }
-                            a = wave_sum(a); b = wave_sum(b); g = wave_sum(g);
-                            if (g != 0.0 && fabs(g) > tol * sqrt(a * b)) {
-                                const double zeta = (b - a) / (2.0 * g);
-                                const double t = ((zeta >= 0.0) ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                                const double cs = 1.0 / sqrt(1.0 + t * t);
-                                const double sn = cs * t;
+                for (int u = 0; u < 8; ++u) x[u] = col[(size_t)(c + u) * k];
 #pragma unroll
-                                for (int e = 0; e < JAC_PER_LANE; ++e) {
-                                    const int c = lane + 64 * e;
-                                    if (e < per && c < k) {
-                                        xp[c] = cs * x[e] - sn * y[e];
-                                        xq[c] = sn * x[e] + cs * y[e];
-                                    }
-                                }
-                                if (lane < B2) {
-                                    const double u = Q[p * QP + lane], v = Q[q * QP + lane];
-                                    Q[p * QP + lane] = cs * u - sn * v;
-                                    Q[q * QP + lane] = sn * u + cs * v;
-                                }
-                                if (lane == 0) atomicAdd(&s_rot_pair, 1);
-                            }
-                        }
-                    }
-                    __syncthreads();
-                }
-                if (s_rot_pair != 0) {
-                    // rows back to R; the same combination of rows applied to Gacc
-                    for (int idx = tid; idx < B2 * k; idx += nt) {
-                        const int l = idx / k, c = idx % k;
-                        const int g = grow(l);
-                        if (g >= 0) R[(size_t)g * k + c] = X[idx];
-                    }
-                    __syncthreads();                         // X is free from here on
-                    constexpr int RG = 4;                    // thread groups sharing the output rows
-                    constexpr int OUT = B2 / RG;
-                    const int rg = tid / (SMALL_THREADS / RG);
-                    for (int c = tid % (SMALL_THREADS / RG); c < k; c += SMALL_THREADS / RG) {
-                        double acc[OUT];
-#pragma unroll
-                        for (int o = 0; o < OUT; ++o) acc[o] = 0.0;
-#pragma unroll 1
-                        for (int j0 = 0; j0 < B2; j0 += 8) {
-                            double gv[8];
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) {
-                                const int g = grow(j0 + j);
-                                gv[j] = (g >= 0) ? G[(size_t)g * k + c] : 0.0;
-                            }
-#pragma unroll
-                            for (int o = 0; o < OUT; ++o)
-#pragma unroll
-                                for (int j = 0; j < 8; ++j) acc[o] += Q[(rg * OUT + o) * QP + j0 + j] * gv[j];
-                        }
-                        // every group reads all B2 rows of Gacc, so the new rows are parked in LDS
-                        // and written to Gacc only after the barrier below
-#pragma unroll
-                        for (int o = 0; o < OUT; ++o) {
-                            const int l = rg * OUT + o;
-                            if (grow(l) >= 0) X[(size_t)l * k + c] = acc[o];
-                        }
-                    }
-                    __syncthreads();
-                    for (int idx = tid; idx < B2 * k; idx += nt) {
-                        const int l = idx / k, c = idx % k;
-                        const int g = grow(l);
-                        if (g >= 0) G[(size_t)g * k + c] = X[idx];
-                    }
-                    if (tid == 0) s_rot_sweep += s_rot_pair;
-                }
-                __syncthreads();
+                for (int u = 0; u < 8; ++u) acc[u] += x[u] * s_v[c + u];
             }
+            for (; c < n1; ++c) acc[0] += col[(size_t)c * k] * s_v[c];
+            s_w[i] = beta * (((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7])));
         }
-        const int rotated = s_rot_sweep;
         __syncthreads();
-        if (rotated == 0) break;
+        double pv = 0.0;
+        for (int i = tid; i < n1; i += nt) pv += s_w[i] * s_v[i];
+        const double kk2 = 0.5 * beta * block_sum(pv);
+        for (int i = tid; i < n1; i += nt) s_w[i] -= kk2 * s_v[i];           // w = p - (beta/2)(p.v) v
+        __syncthreads();
+        // T22 -= v w^T + w v^T
+        for (int idx = tid; idx < n1 * n1; idx += nt) {
+            const int i = idx / n1, c = idx % n1;
+            T[(size_t)(j + 1 + i) * k + j + 1 + c] -= s_v[i] * s_w[c] + s_w[i] * s_v[c];
+        }
+        // W[j+1.., :] -= beta v (v^T W[j+1.., :])
+        for (int c = tid; c < k; c += nt) {
+            double* wc = W + (size_t)(j + 1) * k + c;
+            double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+            int i = 0;
+            for (; i + 8 <= n1; i += 8) {
+                double x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = wc[(size_t)(i + u) * k];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc[u] += x[u] * s_v[i + u];
+            }
+            for (; i < n1; ++i) acc[0] += wc[(size_t)i * k] * s_v[i];
+            const double y = beta * (((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7])));
+            i = 0;
+            for (; i + 8 <= n1; i += 8) {
+                double x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = wc[(size_t)(i + u) * k];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) wc[(size_t)(i + u) * k] = x[u] - s_v[i + u] * y;
+            }
+            for (; i < n1; ++i) wc[(size_t)i * k] -= s_v[i] * y;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (k >= 2) { s_d[k - 2] = T[(size_t)(k - 2) * k + k - 2]; s_e[k - 2] = T[(size_t)(k - 1) * k + k - 2]; }
+        s_d[k - 1] = T[(size_t)(k - 1) * k + k - 1];
+        s_e[k - 1] = 0.0;
+    }
+    __syncthreads();
+
+    // ---- implicit QL on (d, e); every rotation (c, s) of rows (i, i+1) is applied to W.
+    // Per QL sweep: all threads look for the first negligible sub-diagonal entry at or after l;
+    // thread 0 runs the scalar recurrences (operands prefetched one step ahead, the hypotenuse
+    // from a reciprocal square root) and records the rotations in s_v (c) and s_w (s); then
+    // every thread applies the recorded chain to its column of W.
+    for (int l = 0; l < k; ++l) {
+        for (int iter = 0; iter <= QL_MAX_ITER; ++iter) {
+            if (tid == 0) s_int[0] = k - 1;
+            __syncthreads();
+            for (int i = l + tid; i < k - 1; i += nt) {
+                const double dd = fabs(s_d[i]) + fabs(s_d[i + 1]);
+                if (fabs(s_e[i]) <= 2.3e-16 * dd) atomicMin(&s_int[0], i);
+            }
+            __syncthreads();
+            const int m = s_int[0];
+            if (m == l || iter >= QL_MAX_ITER) break;
+            if (tid == 0) {
+                int lo = m;                                   // rotations recorded for rows lo .. m-1
+                double g = (s_d[l + 1] - s_d[l]) / (2.0 * s_e[l]);
+                double rr = sqrt(g * g + 1.0);
+                g = s_d[m] - s_d[l] + s_e[l] / (g + ((g >= 0.0) ? fabs(rr) : -fabs(rr)));
+                double sn = 1.0, cs = 1.0, pp = 0.0;
+                double e_i = s_e[m - 1], d_i = s_d[m - 1], d_ip1 = s_d[m];
+                bool under = false;
+                for (int i = m - 1; i >= l; --i) {
+                    const double e_n = (i > l) ? s_e[i - 1] : 0.0;     // next step's operands
+                    const double d_n = (i > l) ? s_d[i - 1] : 0.0;
+                    const double f = sn * e_i;
+                    const double bb = cs * e_i;
+                    const double h2 = f * f + g * g;
+                    if (h2 == 0.0) { s_e[i + 1] = 0.0; s_d[i + 1] -= pp; s_e[m] = 0.0; under = true; break; }
+                    double rinv = __builtin_amdgcn_rsq(h2);
+                    const double hh = 0.5 * h2;
+                    rinv = rinv * (1.5 - hh * rinv * rinv);
+                    rinv = rinv * (1.5 - hh * rinv * rinv);
+                    s_e[i + 1] = h2 * rinv;
+                    sn = f * rinv; cs = g * rinv;
+                    g = d_ip1 - pp;
+                    rr = (d_i - g) * sn + 2.0 * cs * bb;
+                    pp = sn * rr;
+                    s_d[i + 1] = g + pp;
+                    g = cs * rr - bb;
+                    s_v[i] = cs; s_w[i] = sn;
+                    lo = i;
+                    d_ip1 = d_i; d_i = d_n; e_i = e_n;
+                }
+                if (!under) { s_d[l] -= pp; s_e[l] = g; s_e[m] = 0.0; }
+                s_int[1] = lo;
+            }
+            __syncthreads();
+            const int lo = s_int[1];
+            for (int c = tid; c < k; c += nt) {
+                double* wc = W + c;
+                double hi = wc[(size_t)m * k];                 // current row i+1, starting with i = m-1
+                int i = m - 1;
+                for (; i - 7 >= lo; i -= 8) {                  // eight rows fetched together
+                    double a[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) a[u] = wc[(size_t)(i - u) * k];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const double cs = s_v[i - u], sn = s_w[i - u];
+                        wc[(size_t)(i - u + 1) * k] = sn * a[u] + cs * hi;
+                        hi = cs * a[u] - sn * hi;
+                    }
+                }
+                for (; i >= lo; --i) {
+                    const double cs = s_v[i], sn = s_w[i];
+                    const double a = wc[(size_t)i * k];
+                    wc[(size_t)(i + 1) * k] = sn * a + cs * hi;
+                    hi = cs * a - sn * hi;
+                }
+                wc[(size_t)lo * k] = hi;
+            }
+            __syncthreads();
+        }
     }
 
-    // singular values = row norms; order descending (ties by index)
+    // ---- T <- W R  (rows of E^T R), 4 x 4 register tiles
+    {
+        const int tiles = (k + 3) >> 2;
+        for (int q = tid; q < tiles * tiles; q += nt) {
+            const int i0 = (q / tiles) * 4, c0 = (q % tiles) * 4;
+            double acc[4][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+            for (int j = 0; j < k; ++j) {
+                double a[4], b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    a[u] = (i0 + u < k) ? W[(size_t)(i0 + u) * k + j] : 0.0;
+                    b[u] = (c0 + u < k) ? R[(size_t)j * k + c0 + u] : 0.0;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[u][v] += a[u] * b[v];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (i0 + u < k && c0 + v < k) T[(size_t)(i0 + u) * k + c0 + v] = acc[u][v];
+        }
+    }
+    __syncthreads();
+
+    // singular values = row norms of E^T R; order descending (ties by index)
     for (int j = wave; j < k; j += nw) {
         double a = 0.0;
-        for (int c = lane; c < k; c += 64) { const double v = R[(size_t)j * k + c]; a += v * v; }
+        for (int c = lane; c < k; c += 64) { const double v = T[(size_t)j * k + c]; a += v * v; }
         a = wave_sum(a);
-        if (lane == 0) s_sig[j] = sqrt(a);
+        if (lane == 0) s_d[j] = sqrt(a);
     }
     __syncthreads();
     for (int j = tid; j < k; j += nt) {
-        const double sj = s_sig[j];
+        const double sj = s_d[j];
         int rank = 0;
         for (int i = 0; i < k; ++i) {
-            const double si = s_sig[i];
+            const double si = s_d[i];
             rank += (si > sj || (si == sj && i < j)) ? 1 : 0;
         }
         s_rank[j] = rank;
@@ -619,37 +733,22 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
     for (int j = wave; j < k; j += nw) {
         const int rank = s_rank[j];
         if (rank >= r) continue;
-        const double sj = s_sig[j];
+        const double sj = s_d[j];
         const double inv = (sj > 0.0) ? 1.0 / sj : 0.0;
         for (int c = lane; c < k; c += 64) {
-            blk->XrT[(size_t)rank * k + c] = (float)(R[(size_t)j * k + c] * inv);
-            blk->GrT[(size_t)rank * k + c] = (float)G[(size_t)j * k + c];
+            blk->XrT[(size_t)rank * k + c] = (float)(T[(size_t)j * k + c] * inv);
+            blk->GrT[(size_t)rank * k + c] = (float)W[(size_t)j * k + c];
         }
     }
 }
 
-// max_k: largest k of the launch (sizes the LDS row buffer)
 hipError_t launch_jacobi(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
                          hipStream_t stream) {
     if (blocks <= 0) return hipSuccess;
+    if (max_k > SMALL_MAXK) return hipErrorInvalidValue;
     JacobiBlock sb{};
     if (single) sb = *single;
-    typedef void (*fn_t)(const JacobiBlock*, const JacobiBlock);
-    // 32 rows per block pair while they fit in the 160 KB of LDS next to the static arrays
-    // (about 13 KB), else 16
-    const size_t budget = 160 * 1024 - 14 * 1024;
-    const bool big = (size_t)32 * max_k * 8 + 32 * 33 * 8 <= budget;
-    fn_t fn = big ? jacobi_kernel<32> : jacobi_kernel<16>;
-    const int b2 = big ? 32 : 16;
-    const int lds = b2 * max_k * 8 + b2 * (b2 + 1) * 8;
-    if ((size_t)lds > budget) return hipErrorInvalidValue;
-    static thread_local int configured[2] = {0, 0};       // largest dynamic LDS size set so far
-    if (configured[big ? 1 : 0] < lds) {
-        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured[big ? 1 : 0] = lds;
-    }
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(SMALL_THREADS), lds, stream, table_dev, sb);
+    hipLaunchKernelGGL(jacobi_kernel, dim3(blocks), dim3(SMALL_THREADS), 0, stream, table_dev, sb);
     return hipGetLastError();
 }
 
