@@ -168,6 +168,13 @@ void tsr_plan_destroy(tsr_plan* plan);
  * call this before the next step. */
 int tsr_plan_bases_changed(tsr_plan* plan);
 
+/* Which kernels the plan's per-step path runs: 1 = the k-contiguous bf16 family with the fused
+ * lift (precision TSR_PREC_BF16, every gradient with a 16-byte aligned base, row pitch and worker
+ * stride, n a multiple of 8, every operand addressable with 31-bit byte offsets), 0 = the
+ * general grouped kernels (every other case; same results to the precision's tolerance).
+ * A null plan gives -1. */
+int tsr_plan_kernel_path(const tsr_plan* plan);
+
 /* One TSR-Adam step (no refresh) for every block of the plan:
  * project all workers -> average -> Adam on the cores -> lift + apply.  t >= 1. */
 int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream);

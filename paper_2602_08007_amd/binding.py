@@ -65,6 +65,7 @@ _refresh_ws = _sig("tsr_refresh_workspace_bytes", _sz, _i, _i, _i, _i)
 _refresh = _sig("tsr_refresh_rsvd", _i, _vp, _i, _i, _i, _ll, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp)
 _plan_ws = _sig("tsr_plan_workspace_bytes", _sz, ctypes.POINTER(tsr_matrix_desc), _i, _i, _i, _i, _i)
 _bases_changed = _sig("tsr_plan_bases_changed", _i, _vp)
+_kernel_path = _sig("tsr_plan_kernel_path", _i, _vp)
 _plan_create = _sig("tsr_plan_create", _i, ctypes.POINTER(tsr_matrix_desc), _i, _i, _i, _i, _i, _vp, _sz, _vp,
                     ctypes.POINTER(_vp))
 _plan_destroy = _sig("tsr_plan_destroy", None, _vp)
@@ -240,6 +241,9 @@ class Plan:
     def tsr_step_batched(self, t, lr, wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0, stream=None):
         h = tsr_hyper(lr, wd, beta1, beta2, eps, scale)
         _check(_step_batched(self._handle, t, ctypes.byref(h), _stream(stream)))
+
+    def tsr_plan_kernel_path(self):
+        return _kernel_path(self._handle)
 
     def tsr_plan_bases_changed(self):
         _check(_bases_changed(self._handle))

@@ -369,6 +369,7 @@ struct tsr_plan {
     LiftProgram lift;
     FastStep fast;              // used instead of project / lift when precision == TSR_PREC_BF16
     bool use_fast = false;
+    bool force_generic = false;   // sizing only: measure the generic programs
     std::vector<CoreBlock> cores; const CoreBlock* d_cores = nullptr; long long max_core = 0;
     RefreshProgram refresh;
     char* ws = nullptr;
@@ -572,7 +573,7 @@ static void views_from_descs(std::vector<BlockView>& v, const tsr_matrix_desc* d
 
 // Builds every program of the plan into `ar`; with plan == nullptr only measures.
 static void build_plan(tsr_plan& pl, Arena& ar) {
-    pl.use_fast = (pl.precision == TSR_PREC_BF16);
+    pl.use_fast = (pl.precision == TSR_PREC_BF16) && !pl.force_generic && fast_step_eligible(pl.blocks, pl.n_workers);
     if (pl.use_fast) {
         build_fast_step(pl.fast, pl.blocks, pl.n_workers, ar);
     } else {
@@ -622,7 +623,18 @@ size_t tsr_plan_workspace_bytes(const tsr_matrix_desc* descs, int count, int n_w
     pl.n_workers = n_workers; pl.precision = precision; pl.with_refresh = with_refresh != 0; pl.p = p;
     Arena ar(nullptr);
     build_plan(pl, ar);
-    return ar.used();
+    size_t need = ar.used();
+    if (pl.use_fast) {
+        // the gradient pointers given at creation may turn out unaligned: size for either path
+        tsr_plan generic;
+        generic.blocks = pl.blocks;
+        generic.n_workers = n_workers; generic.precision = precision; generic.with_refresh = with_refresh != 0;
+        generic.p = p; generic.force_generic = true;
+        Arena ar2(nullptr);
+        build_plan(generic, ar2);
+        need = std::max(need, ar2.used());
+    }
+    return need;
 }
 
 int tsr_plan_create(const tsr_matrix_desc* descs, int count, int n_workers, int precision, int with_refresh, int p,
@@ -690,6 +702,8 @@ int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void*
     plan->fast.bases_dirty = true;
     return run_refresh(rp, true, q, cx);
 }
+
+int tsr_plan_kernel_path(const tsr_plan* plan) { return plan ? (plan->use_fast ? 1 : 0) : -1; }
 
 int tsr_plan_bases_changed(tsr_plan* plan) {
     if (!plan) return TSR_INVALID_ARG;

@@ -42,6 +42,7 @@ struct FastStep {
     bool bases_dirty = true;
 };
 
+bool fast_step_eligible(const std::vector<BlockView>& blocks, int n_workers);
 void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_workers, Arena& ar);
 void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up);
 int run_fast_step(FastStep& fs, int n_workers, const AdamScalars& s, float lr, float wd, float scale, Ctx& cx);

@@ -161,6 +161,24 @@ void upload_nt_stage(NtStageH& st, Arena& ar, Uploader& up) {
 
 }  // namespace
 
+// The NT kernels fetch 16-byte chunks through 32-bit buffer offsets: every gradient needs a
+// 16-byte aligned base, rows (and worker slices) that are multiples of 16 bytes, a column count
+// that is a multiple of 8, and tiles past the last row must still be addressable in 31 bits.
+bool fast_step_eligible(const std::vector<BlockView>& blocks, int n_workers) {
+    const long long lim = 1LL << 31;
+    for (const BlockView& b : blocks) {
+        const long long esz = (b.g_dtype == TSR_BF16) ? 2 : 4;
+        if (((uintptr_t)b.G) % 16 != 0 || (b.ldg * esz) % 16 != 0 || b.n % 8 != 0) return false;
+        if (n_workers > 1 && (b.g_stride * esz) % 16 != 0) return false;
+        const long long big = std::max(b.m, b.n);
+        if ((long long)(b.m + 256) * b.ldg * esz >= lim) return false;                  // G
+        if ((big + 256) * round8(b.r) * 2 >= lim) return false;                          // U, V, T shadows
+        if ((long long)(b.r + 256) * round8(big) * 2 >= lim) return false;               // U^T, V^T, P^T
+        if ((long long)(b.m + 256) * b.ldw * 4 >= lim) return false;                     // W
+    }
+    return true;
+}
+
 void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_workers, Arena& ar) {
     fs.shadows.clear(); fs.adam.clear(); fs.lifts.clear();
     fs.max_rows = 0; fs.max_r = 0;

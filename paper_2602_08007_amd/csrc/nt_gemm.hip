@@ -20,41 +20,55 @@ template <int CH, bool F32> struct NtStage;      // CH = 16-byte chunks per thre
 template <int CH> struct NtStage<CH, false> { u32x4 v[CH]; };
 template <int CH> struct NtStage<CH, true> { f32x4 v[CH][2]; };
 
+// Raw buffer loads: one descriptor (SGPRs) per operand, a 32-bit per-lane byte offset.  A
+// per-lane offset at or beyond the descriptor's size reads as zero, which is the row guard
+// (rows beyond the operand lie beyond its last byte); the k guard of the last, partial k-tile
+// is a mask applied to the loaded words.  No branches, no 64-bit address arithmetic.
+typedef __amdgpu_buffer_rsrc_t nt_rsrc_t;
+__device__ inline nt_rsrc_t nt_make_rsrc(const void* p, long long bytes) {
+    const int n = (bytes > 0x7fffffffLL) ? 0x7fffffff : (int)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), (short)0, n, 0x00020000);
+}
+
 // rows x K operand, k contiguous; tile rows row0.., k0..k0+BK-1.  Thread t owns chunks
-// c = t + 256*it: row c/(BK/8), k offset (c%(BK/8))*8.
+// c = t + 256*it: row c/(BK/8), k offset (c%(BK/8))*8.  `tail`: this k-tile crosses kend.
 template <int ROWS, int BK, bool F32>
-__device__ inline void nt_load(NtStage<ROWS * BK / 8 / NT_THREADS, F32>& s, const void* base, long long ld, int rows,
-                               int row0, int k0, int kend, bool vec_ok, int tid) {
+__device__ inline void nt_load(NtStage<ROWS * BK / 8 / NT_THREADS, F32>& s, nt_rsrc_t rs, unsigned ld_bytes, int row0,
+                               int k0, int kend, bool tail, int tid) {
     constexpr int CPR = BK / 8;
+    constexpr int ESZ = F32 ? 4 : 2;
+    constexpr int CH = ROWS * CPR / NT_THREADS;
 #pragma unroll
-    for (int it = 0; it < ROWS * CPR / NT_THREADS; ++it) {
+    for (int it = 0; it < CH; ++it) {
         const int c = tid + NT_THREADS * it;
-        const int grow = row0 + c / CPR;
+        const unsigned grow = row0 + c / CPR;
         const int gk = k0 + (c % CPR) * 8;
+        const unsigned voff = grow * ld_bytes + (unsigned)gk * ESZ;
         if constexpr (F32) {
-            const float* p = (const float*)base + (long long)grow * ld + gk;
-            if (grow < rows && vec_ok && gk + 8 <= kend) {
-                s.v[it][0] = *(const f32x4*)p;
-                s.v[it][1] = *(const f32x4*)(p + 4);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) s.v[it][j >> 2][j & 3] = (grow < rows && gk + j < kend) ? p[j] : 0.0f;
-            }
+            s.v[it][0] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, 0, 0));
+            s.v[it][1] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(voff + 16), 0, 0));
         } else {
-            const unsigned short* p = (const unsigned short*)base + (long long)grow * ld + gk;
-            u32x4 r = {0u, 0u, 0u, 0u};
-            if (grow < rows) {
-                if (vec_ok && gk + 8 <= kend) {
-                    r = *(const u32x4*)p;
-                } else {
-                    unsigned short e[8];
+            s.v[it] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, 0, 0));
+        }
+    }
+    if (tail) {                                             // wave-uniform: last k-tile only
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) e[j] = (gk + j < kend) ? p[j] : (unsigned short)0;
+        for (int it = 0; it < CH; ++it) {
+            const int c = tid + NT_THREADS * it;
+            const int valid = kend - (k0 + (c % CPR) * 8);  // elements of this chunk inside [.., kend)
+            if constexpr (F32) {
+                u32x4 m0, m1;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) r[j] = (unsigned int)e[2 * j] | ((unsigned int)e[2 * j + 1] << 16);
-                }
+                for (int j = 0; j < 4; ++j) { m0[j] = (j < valid) ? 0xffffffffu : 0u; m1[j] = (4 + j < valid) ? 0xffffffffu : 0u; }
+                s.v[it][0] = __builtin_bit_cast(f32x4, __builtin_bit_cast(u32x4, s.v[it][0]) & m0);
+                s.v[it][1] = __builtin_bit_cast(f32x4, __builtin_bit_cast(u32x4, s.v[it][1]) & m1);
+            } else {
+                u32x4 m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    m[j] = ((2 * j < valid) ? 0x0000ffffu : 0u) | ((2 * j + 1 < valid) ? 0xffff0000u : 0u);
+                s.v[it] = s.v[it] & m;
             }
-            s.v[it] = r;
         }
     }
 }
@@ -108,28 +122,38 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    const bool a_vec = (((unsigned long long)A) % 16 == 0) && ((lda * 2) % 16 == 0);
-    const bool b_vec = (((unsigned long long)B) % 16 == 0) && ((ldb * (B_F32 ? 4 : 2)) % 16 == 0);
+    // Operands have 16-byte aligned bases and rows, and K rounded up to 8 elements still lies
+    // inside every row (the host routes anything else to the generic kernels): a 16-byte chunk is
+    // then either wholly inside the operand's extent or wholly outside it.
+    const long long k8 = (K + 7) & ~7;
+    const nt_rsrc_t rA = nt_make_rsrc(A, ((long long)(M - 1) * lda + k8) * 2);
+    const nt_rsrc_t rB = nt_make_rsrc(B, ((long long)(N - 1) * ldb + k8) * (B_F32 ? 4 : 2));
+    const unsigned lda_b = (unsigned)lda * 2u, ldb_b = (unsigned)ldb * (B_F32 ? 4u : 2u);
 
     // For the read-modify-write epilogue the C tile is fetched into registers before the k-loop
     // and only consumed after it, so its HBM latency hides behind the whole loop.
     f32x16 cold[RMW ? FM : 1][RMW ? FN : 1];
     const float out_scale = alpha;
     const bool skip_products = RMW && alpha == 0.0f;
+    // output descriptor: guards poison the per-lane offset (the wave-uniform offset is not
+    // range-checked by the hardware)
+    constexpr int CSZ = OUT_BF16 ? 2 : 4;
+    const nt_rsrc_t rC = nt_make_rsrc((const char*)pp->C + (long long)t.ks * pp->c_split_stride * CSZ,
+                                      ((long long)(M - 1) * ldc + N) * CSZ);
+    const unsigned ldc_b = (unsigned)ldc * CSZ;
+    auto c_voff = [&](int i, int j, int e) -> unsigned {
+        const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
+        const int row = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4 + (e >> 2) * 8 + (e & 3);
+        return (row < M && col < N) ? (unsigned)row * ldc_b + (unsigned)col * CSZ : 0x80000000u;
+    };
     if constexpr (RMW) {
-        const float* C = (const float*)pp->C + (long long)t.ks * pp->c_split_stride;
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
-                const int rbase = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4;
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = rbase + (e >> 2) * 8 + (e & 3);
-                    cold[i][j][e] = (row < M && col < N) ? C[(long long)row * ldc + col] : 0.0f;
-                }
-            }
+                for (int e = 0; e < 16; ++e)
+                    cold[i][j][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rC, (int)c_voff(i, j, e), 0, 0));
     }
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -150,8 +174,9 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
 
     auto load = [&](int slot, int tile) {
         const int k0 = kbeg + tile * NT_BK;
-        nt_load<TM, NT_BK, false>(stA[slot], A, lda, M, row0, k0, kend, a_vec, tid);
-        nt_load<TN, NT_BK, B_F32>(stB[slot], B, ldb, N, col0, k0, kend, b_vec, tid);
+        const bool tail = k0 + NT_BK > kend;
+        nt_load<TM, NT_BK, false>(stA[slot], rA, lda_b, row0, k0, kend, tail, tid);
+        nt_load<TN, NT_BK, B_F32>(stB[slot], rB, ldb_b, col0, k0, kend, tail, tid);
     };
     auto store = [&](int slot, int buf) {
         unsigned short* d = lds + buf * BUF;
@@ -221,25 +246,18 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
-            const int rbase = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4;
-            if (col >= N) continue;
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = rbase + (e >> 2) * 8 + (e & 3);
-                if (row >= M) continue;
+                const unsigned vo = c_voff(i, j, e);
                 if constexpr (OUT_BF16) {
-                    unsigned short* C = (unsigned short*)pp->C;
-                    C[(long long)row * ldc + col] = f32_to_bf16_bits(out_scale * acc[i][j][e]);
+                    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_bits(out_scale * acc[i][j][e]), rC, (int)vo, 0, 0);
                 } else {
-                    float* C = (float*)pp->C + (long long)t.ks * pp->c_split_stride;
                     float v = out_scale * acc[i][j][e];
                     if constexpr (RMW) v += beta * cold[i][j][e];
-                    C[(long long)row * ldc + col] = v;
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rC, (int)vo, 0, 0);
                 }
             }
-        }
 }
 
 // ------------------------------------------------------------------ dispatch

@@ -346,11 +346,12 @@ def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3, guard_w=False):
                                                   (3, torch.bfloat16, "split"), (3, torch.bfloat16, "bf16"),
                                                   (1, torch.float32, "bf16")])
 def test_step_batched_matches_oracle(tsr, workers, g_dtype, prec):
-    shapes = [(256, 256), (256, 688), (688, 256), (200, 333), (256, 256)]
+    shapes = [(256, 256), (256, 688), (688, 256), (200, 336), (256, 256)]
     r = 32
     blocks, host = make_blocks(shapes, r, workers, g_dtype, si.stream_key(601, workers))
     precision = tsr.TSR_PREC_SPLIT if prec == "split" else tsr.TSR_PREC_BF16
     plan = tsr.Plan(blocks, n_workers=workers, precision=precision)
+    assert plan.tsr_plan_kernel_path() == (1 if prec == "bf16" else 0)
     tol = TOL_F32 if prec == "split" else TOL_BF16
     state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
     for t in (1, 2, 3):
@@ -368,12 +369,19 @@ def test_step_batched_matches_oracle(tsr, workers, g_dtype, prec):
 
 @pytest.mark.parametrize("r", [64, 128, 256])
 @pytest.mark.parametrize("workers", [1, 2])
-def test_bf16_plan_fused_lift_ranks(tsr, r, workers):
-    # ranks served by the fused lift kernel, on ragged shapes (partial row panels, partial
-    # column tiles, odd leading dimensions) and with weight decay
-    shapes = [(r + 37, 2 * r + 61), (3 * r + 5, r), (r, r), (2 * r, 5 * r + 130), (r + 1, 2 * r + 4)]
+@pytest.mark.parametrize("rows16", [True, False])
+def test_bf16_plan_fused_lift_ranks(tsr, r, workers, rows16):
+    # ragged shapes (partial row panels, partial column tiles) with weight decay.  With gradient
+    # rows that are multiples of 16 bytes the plan runs the k-contiguous bf16 kernels and, at
+    # these ranks, the fused lift kernel; with odd row lengths it must fall back to the general
+    # kernels and still meet the same bar.
+    if rows16:
+        shapes = [(r + 37, 2 * r + 64), (3 * r + 5, r), (r, r), (2 * r, 5 * r + 136), (r + 1, 2 * r + 8)]
+    else:
+        shapes = [(r + 37, 2 * r + 61), (3 * r + 5, r), (r, r), (2 * r, 5 * r + 130), (r + 1, 2 * r + 4)]
     blocks, host = make_blocks(shapes, r, workers, torch.bfloat16, si.stream_key(631, r), guard_w=True)
     plan = tsr.Plan(blocks, n_workers=workers, precision=tsr.TSR_PREC_BF16)
+    assert plan.tsr_plan_kernel_path() == (1 if rows16 else 0)
     state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
     for t in (1, 2):
         plan.tsr_step_batched(t, lr=1e-3, wd=0.05)
@@ -399,10 +407,11 @@ def test_bf16_plan_fused_lift_ranks(tsr, r, workers):
 def test_bf16_plan_follows_changed_bases(tsr):
     # the bf16 plan keeps bf16 copies of the bases: after the caller rewrites U, V and says
     # so, the next step must use the new ones
-    shapes = [(320, 448), (130, 257)]
+    shapes = [(320, 448), (130, 264)]
     r = 64
     blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, 611)
     plan = tsr.Plan(blocks, precision=tsr.TSR_PREC_BF16)
+    assert plan.tsr_plan_kernel_path() == 1
     plan.tsr_step_batched(1, lr=1e-3)
     for i, (b, h, (m, n)) in enumerate(zip(blocks, host, shapes)):
         U2, V2 = bases(m, n, r, si.stream_key(612, i))
