@@ -34,9 +34,9 @@ struct FastStep {
     struct LiftGroup {   // blocks of one rank handled by the fused lift kernel
         int r = 0;
         int mode = 0;        // kernel variant (panel height / prefetch), see lift.hip
-        bool vec4 = false;   // W rows 16-byte aligned and n % 4 == 0 for every block of the group
         std::vector<LiftBlock> blocks;  const LiftBlock* d_blocks = nullptr;
-        std::vector<LiftTile> tiles;    const LiftTile* d_tiles = nullptr;
+        std::vector<LiftTile> tiles;    const LiftTile* d_tiles = nullptr;     // work items, grouped by list
+        std::vector<LiftRange> ranges;  const LiftRange* d_ranges = nullptr;   // one list of items per workgroup
     };
     std::vector<LiftGroup> lifts;
     bool bases_dirty = true;

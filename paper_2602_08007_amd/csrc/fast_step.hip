@@ -183,11 +183,9 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
     fs.shadows.clear(); fs.adam.clear(); fs.lifts.clear();
     fs.max_rows = 0; fs.max_r = 0;
     const bool fused_lift = tune_int("TSR_TUNE_FUSED_LIFT", 1, 0, 1) != 0;
-    const int lift_chunk = tune_int("TSR_TUNE_LIFT_CHUNK", 6, 1, 64);
-    const int lift_mode = tune_int("TSR_TUNE_LIFT_MODE", 0, 0, 2);
-    const bool lift_vec4 = tune_int("TSR_TUNE_LIFT_VEC4", 0, 0, 1) != 0;
-    std::map<int, std::vector<int>> lift_tile_block;
-    std::map<int, std::vector<long long>> lift_tile_work;
+    const int lift_cus = tune_int("TSR_TUNE_LIFT_CUS", 256, 8, 4096);       // compute units of the target
+    const int lift_setup = tune_int("TSR_TUNE_LIFT_SETUP", 4, 0, 16);       // cost of an item's setup, in tiles
+    const int lift_mode = tune_int("TSR_TUNE_LIFT_MODE", 0, 0, 1);
     std::vector<NtLogical> gv[2], utp, ud, tvt;
     const int nb = (int)blocks.size();
     int r_max = 0;
@@ -201,8 +199,11 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
         bf* VTb = ar.take<bf>((size_t)b.r * ldn);
         bf* Tb = ar.take<bf>((size_t)b.m * ldr);
         bf* DTb = ar.take<bf>((size_t)b.r * ldr);
-        fs.shadows.push_back(ShadowBlock{b.U, Ub, UTb, b.m, b.r, ldr, ldm});
-        fs.shadows.push_back(ShadowBlock{b.V, Vb, VTb, b.n, b.r, ldr, ldn});
+        const bool fits32 = (long long)(b.m + 128) * b.ldw * 4 < (1LL << 31) && (long long)(std::max(b.m, b.n) + 128) * ldr * 2 < (1LL << 31);
+        const bool use_lift = fused_lift && lift_supports_rank(b.r) && fits32;
+        bf* Vf = use_lift ? ar.take<bf>((size_t)cdiv(b.n, 32) * 32 * b.r) : nullptr;
+        fs.shadows.push_back(ShadowBlock{b.U, Ub, UTb, nullptr, b.m, b.r, ldr, ldm});
+        fs.shadows.push_back(ShadowBlock{b.V, Vb, VTb, Vf, b.n, b.r, ldr, ldn});
         fs.max_rows = std::max(fs.max_rows, std::max(b.m, b.n));
         fs.max_r = std::max(fs.max_r, b.r);
         r_max = std::max(r_max, b.r);
@@ -213,33 +214,59 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
             gv[b.g_dtype].push_back(NtLogical{VTb, Gw, PT, ldn, b.ldg, ldm, b.r, b.m, b.n, bi, -1});
             utp.push_back(NtLogical{UTb, PT, b.C, ldm, ldm, b.r, b.r, b.r, b.m, bi, bi});
         }
-        fs.adam.push_back(AdamTBlock{b.C, b.M, b.Vm, b.D, DTb, b.r, ldr});
-        const bool fits32 = (long long)(b.m + 128) * b.ldw * 4 < (1LL << 31) && (long long)(std::max(b.m, b.n) + 128) * ldr * 2 < (1LL << 31);
-        if (fused_lift && lift_supports_rank(b.r) && fits32) {
-            const bool vec4 = lift_vec4 && (b.n % 4 == 0) && (b.ldw % 4 == 0) && (((uintptr_t)b.W) % 16 == 0);
+        bf* DTf = use_lift ? ar.take<bf>((size_t)b.r * b.r) : nullptr;
+        fs.adam.push_back(AdamTBlock{b.C, b.M, b.Vm, b.D, DTb, DTf, b.r, ldr});
+        if (use_lift) {
             FastStep::LiftGroup* grp = nullptr;
-            for (auto& g : fs.lifts) if (g.r == b.r && g.vec4 == vec4) grp = &g;
-            if (!grp) { fs.lifts.emplace_back(); grp = &fs.lifts.back(); grp->r = b.r; grp->vec4 = vec4; grp->mode = lift_mode; }
-            const int gkey = grp->r * 2 + (vec4 ? 1 : 0);
+            for (auto& g : fs.lifts) if (g.r == b.r) grp = &g;
+            if (!grp) { fs.lifts.emplace_back(); grp = &fs.lifts.back(); grp->r = b.r; grp->mode = lift_mode; }
             const int bidx = (int)grp->blocks.size();
-            grp->blocks.push_back(LiftBlock{Ub, DTb, Vb, b.W, ldr, b.ldw, b.m, b.n, b.r});
-            const int ntiles = cdiv(b.n, 128);
-            const int nchunks = cdiv(ntiles, lift_chunk);
-            const int per = cdiv(ntiles, nchunks);
-            for (int row0 = 0; row0 < b.m; row0 += lift_panel_rows(lift_mode))
-                for (int c0 = 0; c0 < ntiles; c0 += per) {
-                    grp->tiles.push_back(LiftTile{bidx, row0, c0, std::min(per, ntiles - c0)});
-                    lift_tile_block[gkey].push_back(bi);
-                    lift_tile_work[gkey].push_back(std::min(per, ntiles - c0) + 1);
-                }
+            grp->blocks.push_back(LiftBlock{Ub, DTf, Vf, b.W, ldr, b.ldw, b.m, b.n, b.r});
+            // whole row panels for now; cut into per-workgroup lists below
+            for (int row0 = 0; row0 < b.m; row0 += lift_panel_rows())
+                grp->tiles.push_back(LiftTile{bidx, row0, 0, cdiv(b.n, 128)});
         } else {
             ud.push_back(NtLogical{Ub, DTb, Tb, ldr, ldr, ldr, b.m, b.r, b.r, bi, -1});
             tvt.push_back(NtLogical{Tb, Vb, b.W, ldr, ldr, b.ldw, b.m, b.n, b.r, bi, -1});
         }
     }
-    for (auto& g : fs.lifts)
-        interleave_xcd(g.tiles, lift_tile_block[g.r * 2 + (g.vec4 ? 1 : 0)], lift_tile_work[g.r * 2 + (g.vec4 ? 1 : 0)], nb,
-                       LiftTile{-1, 0, 0, 0});
+    // Persistent launch: one list of work items per workgroup, all lists equally heavy (tiles
+    // plus the setup cost of every item).  The panels are walked in block order and cut where a
+    // list is full; list s goes to workgroup 8 (s mod L/8) + s / (L/8), so that the lists of
+    // neighbouring panels (which share V) run on one XCD and share its L2.
+    for (auto& g : fs.lifts) {
+        const int n_lists = lift_cus * lift_wgs_per_cu(g.mode);
+        std::vector<LiftTile> panels;
+        panels.swap(g.tiles);
+        long long total = 0;
+        for (const LiftTile& p : panels) total += p.nct + lift_setup;
+        // a cut adds one setup; `cap` is the smallest list weight that lets everything fit
+        long long cap = std::max<long long>(cdiv(total, n_lists), lift_setup + 1);
+        std::vector<std::vector<LiftTile>> lists;
+        for (;; ++cap) {
+            lists.assign(1, {});
+            long long w = 0;
+            for (const LiftTile& p : panels) {
+                int c0 = 0;
+                while (c0 < p.nct) {
+                    if (cap - w < lift_setup + 1) { lists.emplace_back(); w = 0; }
+                    const int take = (int)std::min<long long>(p.nct - c0, cap - w - lift_setup);
+                    lists.back().push_back(LiftTile{p.block, p.row0, c0, take});
+                    w += take + lift_setup;
+                    c0 += take;
+                }
+            }
+            if ((int)lists.size() <= n_lists) break;
+        }
+        g.ranges.assign(n_lists, LiftRange{0, 0});
+        const int per_xcd = n_lists / 8;
+        for (int s = 0; s < (int)lists.size(); ++s) {
+            const int wg = (n_lists % 8 == 0) ? 8 * (s % per_xcd) + s / per_xcd : s;
+            g.ranges[wg].begin = (int)g.tiles.size();
+            g.tiles.insert(g.tiles.end(), lists[s].begin(), lists[s].end());
+            g.ranges[wg].end = (int)g.tiles.size();
+        }
+    }
     const int s1_shape = tune("TSR_TUNE_GV", (r_max > 64) ? NT_128x128 : NT_64x256);
     build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1);
     build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1);
@@ -258,6 +285,7 @@ void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {
     for (auto& g : fs.lifts) {
         g.d_blocks = up.put(g.blocks, ar);
         g.d_tiles = up.put(g.tiles, ar);
+        g.d_ranges = up.put(g.ranges, ar);
     }
 }
 
@@ -273,11 +301,13 @@ int run_fast_step(FastStep& fs, int n_workers, const AdamScalars& s, float lr, f
         Timed timed(cx, TSR_PROF_ADAM);
         TSR_HIP(launch_adam_t(fs.d_adam, (int)fs.adam.size(), fs.max_r, s, cx.s));
     }
-    TSR_TRY(run_nt_stage(fs.ud, 1.0f, 0.0f, cx, TSR_PROF_UD));
-    TSR_TRY(run_nt_stage(fs.tvt, -lr * scale, 1.0f - lr * wd, cx, TSR_PROF_TVT));
+    // T = alpha U D carries the step size; the weight kernels then add T V^T to beta W
+    const float alpha = -lr * scale, beta = 1.0f - lr * wd;
+    TSR_TRY(run_nt_stage(fs.ud, alpha, 0.0f, cx, TSR_PROF_UD));
+    TSR_TRY(run_nt_stage(fs.tvt, 1.0f, beta, cx, TSR_PROF_TVT));
     for (const auto& g : fs.lifts) {
         Timed timed(cx, TSR_PROF_TVT);
-        TSR_HIP(launch_lift(g.d_blocks, g.d_tiles, (int)g.tiles.size(), g.r, g.vec4, g.mode, -lr * scale, 1.0f - lr * wd, cx.s));
+        TSR_HIP(launch_lift(g.d_blocks, g.d_tiles, g.d_ranges, (int)g.ranges.size(), g.r, g.mode, alpha, beta, cx.s));
     }
     return TSR_OK;
 }

@@ -53,9 +53,12 @@ struct NtVariant {
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream);
 
 // fp32 bases -> bf16 shadows: X (rows x r, contiguous fp32) -> Xb (rows x ldx bf16) and
-// XTb (r x ldt bf16, the transpose); padding columns are written as zeros.
+// XTb (r x ldt bf16, the transpose); padding columns are written as zeros.  XFb (optional,
+// r % 16 == 0) is the same matrix in MFMA-fragment order for the fused lift kernel: rows in
+// groups of 32 (zero rows up to the next multiple of 32), and for group g and 16-wide k step s
+// one contiguous 1 KiB record holding, for lane = 32 h + l, the 8 values X[32 g + l][16 s + 8 h ..].
 struct ShadowBlock {
-    const float* X; void* Xb; void* XTb;
+    const float* X; void* Xb; void* XTb; void* XFb;
     int rows, r; long long ldx, ldt;
 };
 hipError_t launch_shadows(const ShadowBlock* table_dev, int blocks, int max_rows, int max_r, hipStream_t stream);

@@ -314,12 +314,16 @@ __global__ __launch_bounds__(256) void shadow_kernel(const ShadowBlock* table) {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     unsigned short* Xb = (unsigned short*)b.Xb;
     unsigned short* XTb = (unsigned short*)b.XTb;
+    unsigned short* XFb = (unsigned short*)b.XFb;
+    const int rows32 = (rows + 31) / 32 * 32, ksteps = r / 16;
     for (int i = ty; i < 64; i += 4) {
         const int row = row0 + i, c = c0 + tx;
         const float v = (row < rows && c < r) ? b.X[(long long)row * r + c] : 0.0f;
         const unsigned short h = f32_to_bf16_bits(v);
         tile[i][tx] = h;
         if (row < rows && c < (int)b.ldx) Xb[(long long)row * b.ldx + c] = h;
+        if (XFb && row < rows32 && c < r)
+            XFb[(((long long)(row / 32) * ksteps + c / 16) * 64 + ((c % 16) / 8) * 32 + row % 32) * 8 + c % 8] = h;
     }
     __syncthreads();
     for (int i = ty; i < 64; i += 4) {

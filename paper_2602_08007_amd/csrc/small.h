@@ -16,10 +16,13 @@ struct AdamScalars { float beta1, beta2, eps, inv_c1, inv_c2; };
 hipError_t launch_adam(const CoreBlock* table_dev, const CoreBlock* single, int blocks,
                        long long max_count, const AdamScalars& s, hipStream_t stream);
 // Adam on square r x r cores that also writes D^T as bf16 (leading dimension ldt), the operand
-// layout the bf16 lift GEMM U D = U (D^T)^T consumes.
+// layout the bf16 lift GEMM U D = U (D^T)^T consumes.  DTf (optional, r % 32 == 0) receives D^T
+// in MFMA-fragment order for the fused lift kernel: for the group g of 32 columns of D and the
+// 16-wide k step s one contiguous 1 KiB record holding, for lane = 32 h + l, the 8 values
+// D[16 s + 8 h ..][32 g + l].
 struct AdamTBlock {
     const float* C; float* M; float* Vm; float* D;
-    void* DTb; int r; long long ldt;
+    void* DTb; void* DTf; int r; long long ldt;
 };
 hipError_t launch_adam_t(const AdamTBlock* table_dev, int blocks, int max_r, const AdamScalars& s,
                          hipStream_t stream);

@@ -65,9 +65,14 @@ __global__ __launch_bounds__(256) void adam_t_kernel(const AdamTBlock* table, co
     }
     __syncthreads();
     unsigned short* DT = (unsigned short*)b.DTb;
+    unsigned short* DF = (unsigned short*)b.DTf;
+    const int ksteps = r / 16;
     for (int i = ty; i < 32; i += 8) {
         const int trow = col0 + i, tcol = row0 + tx;     // D^T[col][row]
-        if (trow < r && tcol < r) DT[(long long)trow * b.ldt + tcol] = tile[tx][i];
+        if (trow < r && tcol < r) {
+            if (DF) DF[(((long long)(trow / 32) * ksteps + tcol / 16) * 64 + ((tcol % 16) / 8) * 32 + trow % 32) * 8 + tcol % 8] = tile[tx][i];
+            else DT[(long long)trow * b.ldt + tcol] = tile[tx][i];
+        }
     }
 }
 
