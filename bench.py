@@ -40,14 +40,14 @@ def step_flops(m, n, r):
 
 
 def tvt_bytes(m, n, r):
-    """Algorithmic bytes of the fused lift-and-apply kernel W <- bW + a T V^T for one block:
-    W read and written once, T (m x r) and V (n x r) read once."""
-    return 8 * m * n + 4 * r * (m + n)
+    """Algorithmic bytes of the fused lift-and-apply kernel W <- bW + a (U D) V^T for one block:
+    W (fp32) read and written once; the bf16 copies of U (m x r), V (n x r) and D (r x r) read once."""
+    return 8 * m * n + 2 * r * (m + n) + 2 * r * r
 
 
 def gv_bytes(m, n, r, g_bytes):
-    """G once, V once, P = G V written once."""
-    return m * n * g_bytes + 4 * n * r + 4 * m * r
+    """G once, the bf16 copy of V once, P = G V written once as bf16."""
+    return m * n * g_bytes + 2 * n * r + 2 * m * r
 
 
 def build_blocks(w: si.Workload, device):
@@ -69,26 +69,36 @@ def build_blocks(w: si.Workload, device):
     return blocks
 
 
-def cpu_baseline(w: si.Workload, blocks, n_sample):
-    """The fp64 oracle, as it stands, on the first n_sample blocks: one full step each."""
+def cpu_baseline(w: si.Workload, blocks, omegas, budget_s=12.0):
+    """The fp64 oracle, as it stands, on this host: whole steps of the whole workload (every
+    block: project, Adam on the core, lift + apply) repeated until about budget_s seconds have
+    passed, then the refresh of the first layer's blocks."""
     from oracle import tsr_oracle as orc
-    sample = []
-    for b in blocks[:n_sample]:
-        G = b["G"][0] if b["G"].dim() == 3 else b["G"]
-        sample.append((orc.f64(G), orc.f64(b["U"]), orc.f64(b["V"]), orc.f64(b["W"])))
     r = w.r
-    t0 = time.perf_counter()
-    for G, U, V, W in sample:
-        M = np.zeros((r, r)); Vm = np.zeros((r, r))
-        orc.tsr_adam_step(W, [G], U, V, M, Vm, 1, lr=1e-3)
-    dt = time.perf_counter() - t0
+    host = []
+    for b in blocks:
+        G = b["G"][0] if b["G"].dim() == 3 else b["G"]
+        host.append(dict(G=orc.f64(G), U=orc.f64(b["U"]), V=orc.f64(b["V"]), W=orc.f64(b["W"]),
+                         M=np.zeros((r, r)), Vm=np.zeros((r, r))))
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        for h in host:
+            orc.tsr_adam_step(h["W"], [h["G"]], h["U"], h["V"], h["M"], h["Vm"], steps + 1, lr=1e-3)
+        steps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or steps >= 20:
+            break
     g_bytes = 2 if w.g_dtype == torch.bfloat16 else 4
-    nbytes = sum(step_bytes(m, n, r, g_bytes) for m, n in w.shapes[:n_sample])
+    nbytes = steps * sum(step_bytes(m, n, r, g_bytes) for m, n in w.shapes)
+    n_refresh = min(7, len(host))
+    t1 = time.perf_counter()
+    for i in range(n_refresh):
+        orc.refresh_rsvd(host[i]["G"], orc.f64(omegas[i]), r, w.p, w.q)
+    dt_refresh = time.perf_counter() - t1
     return dict(value=nbytes / dt / 1e9, unit="GB/s", cores=orc.num_threads(), kind="oracle",
-                sample="one full step (project, Adam, lift+apply) of the first %d of %d blocks, %.2f s"
-                       % (n_sample, len(w.shapes), dt),
-                seconds_per_full_step_extrapolated=dt * sum(step_flops(m, n, r) for m, n in w.shapes)
-                / sum(step_flops(m, n, r) for m, n in w.shapes[:n_sample]))
+                sample="%d whole steps of all %d blocks in %.1f s (%.3f s per step); refresh of the first %d blocks "
+                       "in %.1f s" % (steps, len(w.shapes), dt, dt / steps, n_refresh, dt_refresh),
+                seconds_per_step=dt / steps, refresh_ms_per_matrix=dt_refresh / n_refresh * 1e3)
 
 
 def read_traffic(path):
@@ -152,6 +162,20 @@ def main():
                        stages_ms={kk: round(v[0], 3) for kk, v in prof.items() if v[1]},
                        p=w.p, q=w.q)
 
+    # ---- one plain copy of known size (256 MiB read + 256 MiB written): the measured HBM rate of
+    # this machine and the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters
+    n_copy = 64 * 1024 * 1024
+    src = torch.zeros(n_copy, device=dev); dst = torch.empty(n_copy, device=dev)
+    tsr.tsr_stream_scale(dst, src, 1.0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        tsr.tsr_stream_scale(dst, src, 1.0)
+    e1.record(); torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * n_copy * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
     # ---- the timed step loop
     hyper = dict(lr=float(os.environ.get("TSR_BENCH_LR", "1e-3")), wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0)
     t = 1
@@ -197,7 +221,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "blocks": len(w.shapes), "r": w.r, "g_dtype": str(w.g_dtype).replace("torch.", ""),
                    "workers": w.workers},
-        "hbm_frac": value / HBM_PEAK_GBPS,
+        "hbm_frac": value / HBM_PEAK_GBPS, "copy_kernel_gbps": copy_gbps, "frac_of_copy_kernel": value / copy_gbps,
         "step_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "stage_ms": {kk: round(v, 4) for kk, v in stage_ms.items()},
         "roofline": roofline,
@@ -205,7 +229,7 @@ def main():
         "payload": {"core_bytes": core_b, "dense_bytes_fp32": dense_b, "ratio": dense_b / core_b},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, blocks, min(7, len(w.shapes)))
+        out["cpu_baseline"] = cpu_baseline(w, blocks, omegas)
     plan.close()
     print(json.dumps(out))
 

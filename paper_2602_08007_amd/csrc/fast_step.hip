@@ -184,8 +184,8 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
     fs.max_rows = 0; fs.max_r = 0;
     const bool fused_lift = tune_int("TSR_TUNE_FUSED_LIFT", 1, 0, 1) != 0;
     const int lift_cus = tune_int("TSR_TUNE_LIFT_CUS", 256, 8, 4096);       // compute units of the target
-    const int lift_setup = tune_int("TSR_TUNE_LIFT_SETUP", 4, 0, 16);       // cost of an item's setup, in tiles
-    const int lift_mode = tune_int("TSR_TUNE_LIFT_MODE", 0, 0, 1);
+    const int lift_setup = tune_int("TSR_TUNE_LIFT_SETUP", 2, 0, 16);       // cost of an item's setup, in tiles
+    const int lift_mode = tune_int("TSR_TUNE_LIFT_MODE", 2, 0, 2);
     std::vector<NtLogical> gv[2], utp, ud, tvt;
     const int nb = (int)blocks.size();
     int r_max = 0;
@@ -223,7 +223,7 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
             const int bidx = (int)grp->blocks.size();
             grp->blocks.push_back(LiftBlock{Ub, DTf, Vf, b.W, ldr, b.ldw, b.m, b.n, b.r});
             // whole row panels for now; cut into per-workgroup lists below
-            for (int row0 = 0; row0 < b.m; row0 += lift_panel_rows())
+            for (int row0 = 0; row0 < b.m; row0 += lift_panel_rows(lift_mode))
                 grp->tiles.push_back(LiftTile{bidx, row0, 0, cdiv(b.n, 128)});
         } else {
             ud.push_back(NtLogical{Ub, DTb, Tb, ldr, ldr, ldr, b.m, b.r, b.r, bi, -1});

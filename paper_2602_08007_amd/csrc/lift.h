@@ -13,11 +13,11 @@ struct LiftBlock {
     int m, n, r;
 };
 
-struct LiftTile { int block, row0, ct0, nct; };   // work item: rows row0..row0+127, 128-column tiles ct0..ct0+nct-1
+struct LiftTile { int block, row0, ct0, nct; };   // work item: rows row0..row0+lift_panel_rows-1, 128-column tiles ct0..ct0+nct-1
 struct LiftRange { int begin, end; };              // the items [begin, end) of one workgroup
 
 bool lift_supports_rank(int r);
-int lift_panel_rows();
+int lift_panel_rows(int mode);   // rows of an item
 int lift_wgs_per_cu(int mode);
 hipError_t launch_lift(const LiftBlock* blocks_dev, const LiftTile* tiles_dev, const LiftRange* ranges_dev, int n_wgs,
                        int r, int mode, float alpha, float beta, hipStream_t stream);

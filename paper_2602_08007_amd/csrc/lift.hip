@@ -11,9 +11,10 @@
 //           streaming loop has no barriers.  W crosses HBM exactly once each way and neither T
 //           nor U D V^T is ever written to memory.
 // V and D^T are read from copies stored in fragment order (one contiguous 1 KiB record per
-// wave-level load, written by the shadow and Adam kernels).  Two workgroups share a CU, so that
-// the setup of one (a chain of memory latencies, microseconds each under a streaming load)
-// overlaps the other's stream.
+// wave-level load, written by the shadow and Adam kernels).  The default variant works on
+// 256-row items (two T panels in LDS, one workgroup per CU): V is re-read once per item, and
+// these re-reads rarely hit in L2 (the W stream has pushed them out), so taller items are what
+// cuts the traffic beyond W itself.
 #include "lift.h"
 
 namespace tsr {
@@ -40,17 +41,24 @@ __device__ inline rsrc_t make_rsrc(const void* p, long long bytes) {
 __device__ inline u32x4 buf_load128(rsrc_t r, unsigned voff, unsigned soff) {
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
 }
+// W is touched once per step: its loads and stores carry the non-temporal hint (aux bit 1) so that
+// the stream does not push the reused operands (V, D^T, U) out of L2.
+#ifndef LIFT_W_AUX
+#define LIFT_W_AUX 2
+#endif
 __device__ inline float buf_load32(rsrc_t r, unsigned voff, unsigned soff) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, LIFT_W_AUX));
 }
 __device__ inline void buf_store32(float v, rsrc_t r, unsigned voff, unsigned soff) {
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 0);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, LIFT_W_AUX);
 }
 
 // PIPE: 1 = prefetch the next tile's V fragments and W values while the current tile is
 // multiplied (one workgroup per CU); 2 = W one tile ahead, V fragments reloaded in place as soon
 // as the MFMAs of their k step are issued (fewer registers: two workgroups per CU).
-template <int KSTEPS, int PIPE, int MINB>
+// HALVES: 128-row panels per item (1 or 2).  With 2 the item is a 256-row panel: both T halves
+// sit in LDS and every V fragment, once in registers, serves both, which halves the V traffic.
+template <int KSTEPS, int PIPE, int HALVES, int MINB>
 __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBlock* blocks, const LiftTile* tiles,
                                                                   const LiftRange* ranges, const float alpha,
                                                                   const float beta) {
@@ -63,7 +71,7 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
     constexpr int CT_W = (NCT >= 4) ? NCT / 4 : 1;            // T column tiles per wave (setup)
     constexpr int WAVES_PER_CT = (NCT >= 4) ? 1 : 4 / NCT;
     constexpr int RT_W = RT / WAVES_PER_CT;                   // T row tiles per wave (setup)
-    extern __shared__ __attribute__((aligned(16))) unsigned short X[];   // [LIFT_TM][XP]
+    extern __shared__ __attribute__((aligned(16))) unsigned short X[];   // [HALVES][LIFT_TM][XP]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -92,7 +100,7 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
         unsigned row_soff[16];                  // byte offset of accumulator row e within a 32-row tile
 #pragma unroll
         for (int e = 0; e < 16; ++e) row_soff[e] = (unsigned)((e >> 2) * 8 + (e & 3)) * ldw_b;
-        const bool rows_full = row0 + LIFT_TM <= b.m;
+        constexpr int halves = HALVES;          // a lower half beyond the matrix is all guards: zero T, nothing stored
         auto v_voff = [&](int ct) -> unsigned {
             // one contiguous 1 KiB record per k step; column groups beyond n read as zero
             return (unsigned)((ct * 4 + wave) * KSTEPS * 64 + lane) * 16u;
@@ -102,12 +110,13 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
 #pragma unroll
             for (int s = 0; s < KSTEPS; ++s) f.v[s] = buf_load128(rV, voff + s * 1024, 0);
         };
-        auto w_voff = [&](int ct) -> unsigned {   // element (row0 + 4 h, col) of the tile
-            return (unsigned)(row0 + h * 4) * ldw_b + (unsigned)(ct * 128 + wave * 32 + l32) * 4u;
+        auto w_voff = [&](int ct, int half) -> unsigned {   // element (first row + 4 h, col) of the tile
+            return (unsigned)(row0 + half * LIFT_TM + h * 4) * ldw_b + (unsigned)(ct * 128 + wave * 32 + l32) * 4u;
         };
-        auto load_w = [&](Acc& w, int ct) {
-            const unsigned voff = w_voff(ct);
-            if (rows_full && (ct + 1) * 128 <= b.n) {
+        auto load_w = [&](Acc& w, int ct, int half) {
+            const unsigned voff = w_voff(ct, half);
+            const int r0 = row0 + half * LIFT_TM;
+            if (r0 + LIFT_TM <= b.m && (ct + 1) * 128 <= b.n) {
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
                     const unsigned vo = voff + (unsigned)(rt * 32) * ldw_b;
@@ -121,13 +130,15 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int dr = rt * 32 + (e >> 2) * 8 + (e & 3);
-                        const bool ok = col_ok && (row0 + h * 4 + dr < b.m);
+                        const bool ok = col_ok && (r0 + h * 4 + dr < b.m);
                         w.a[rt][e] = buf_load32(rW, ok ? voff + (unsigned)(rt * 32) * ldw_b : OOB_LANE, row_soff[e]);
                     }
             }
         };
         // next_ct >= 0 (PIPE == 2): reload each k step's V fragment for that tile once it is used
-        auto compute_store = [&](VFrag& f, Acc& w, int ct, int next_ct) {
+        auto compute_store = [&](VFrag& f, Acc& w, int ct, int half, int next_ct) {
+            const unsigned short* Xh = X + half * (LIFT_TM * XP);
+            const int r0 = row0 + half * LIFT_TM;
             if (beta != 1.0f) {
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt)
@@ -141,7 +152,7 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
                     const bf16x8 fv = __builtin_bit_cast(bf16x8, f.v[s]);
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
-                        const bf16x8 ft = *(const bf16x8*)(X + (rt * 32 + l32) * XP + kofs);
+                        const bf16x8 ft = *(const bf16x8*)(Xh + (rt * 32 + l32) * XP + kofs);
                         w.a[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ft, fv, w.a[rt], 0, 0, 0);
                     }
                     if constexpr (PIPE == 2) {
@@ -149,8 +160,8 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
                     }
                 }
             }
-            const unsigned voff = w_voff(ct);
-            if (rows_full && (ct + 1) * 128 <= b.n) {
+            const unsigned voff = w_voff(ct, half);
+            if (r0 + LIFT_TM <= b.m && (ct + 1) * 128 <= b.n) {
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
                     const unsigned vo = voff + (unsigned)(rt * 32) * ldw_b;
@@ -164,7 +175,7 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int dr = rt * 32 + (e >> 2) * 8 + (e & 3);
-                        const bool ok = col_ok && (row0 + h * 4 + dr < b.m);
+                        const bool ok = col_ok && (r0 + h * 4 + dr < b.m);
                         buf_store32(w.a[rt][e], rW, ok ? voff + (unsigned)(rt * 32) * ldw_b : OOB_LANE, row_soff[e]);
                     }
             }
@@ -173,6 +184,10 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
         Acc wa;
         if (item != range.begin) __syncthreads();             // the previous item's T panel is no longer read
 
+#pragma unroll
+        for (int half = 0; half < halves; ++half) {
+        unsigned short* Xh = X + half * (LIFT_TM * XP);
+        const int r0 = row0 + half * LIFT_TM;
         // ---- setup 1: U panel -> LDS (rows beyond m read as zero)
         {
             constexpr int GRP = PER_THREAD < 8 ? PER_THREAD : 8;
@@ -182,12 +197,12 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
 #pragma unroll
                 for (int u = 0; u < GRP; ++u) {
                     const int c = tid + LIFT_THREADS * (g + u);
-                    v[u] = buf_load128(rU, (unsigned)(row0 + c / CPR) * ldr_b + (c % CPR) * 16, 0);
+                    v[u] = buf_load128(rU, (unsigned)(r0 + c / CPR) * ldr_b + (c % CPR) * 16, 0);
                 }
 #pragma unroll
                 for (int u = 0; u < GRP; ++u) {
                     const int c = tid + LIFT_THREADS * (g + u);
-                    *(u32x4*)(X + (c / CPR) * XP + (c % CPR) * 8) = v[u];
+                    *(u32x4*)(Xh + (c / CPR) * XP + (c % CPR) * 8) = v[u];
                 }
             }
         }
@@ -212,15 +227,13 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
                 for (int i = 0; i < CT_W; ++i)
                     fd[i] = __builtin_bit_cast(bf16x8, buf_load128(rD, (unsigned)(((ct_base + i) * KSTEPS + s) * 64 + lane) * 16u, 0));
 #pragma unroll
-                for (int j = 0; j < RT_W; ++j) fu[j] = *(const bf16x8*)(X + ((rt_base + j) * 32 + l32) * XP + kofs);
+                for (int j = 0; j < RT_W; ++j) fu[j] = *(const bf16x8*)(Xh + ((rt_base + j) * 32 + l32) * XP + kofs);
 #pragma unroll
                 for (int i = 0; i < CT_W; ++i)
 #pragma unroll
                     for (int j = 0; j < RT_W; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[i], fu[j], acc[i][j], 0, 0, 0);
             }
-            // the first tile's V fragments and W values start travelling while T is parked
-            if constexpr (PIPE == 1) { load_v(va, ct0); load_w(wa, ct0); }
             __syncthreads();                                  // every wave is done reading U from X
             // acc element e of tile (ct, rt): T column c = ct*32 + 8*(e/4) + 4*h + e%4, T row = rt*32 + l32
 #pragma unroll
@@ -232,46 +245,68 @@ __global__ __launch_bounds__(LIFT_THREADS, MINB) void lift_kernel(const LiftBloc
                         bf16x4 q;
 #pragma unroll
                         for (int u = 0; u < 4; ++u) q[u] = (__bf16)(alpha * acc[i][j][4 * g + u]);
-                        *(bf16x4*)(X + ((rt_base + j) * 32 + l32) * XP + (ct_base + i) * 32 + 8 * g + 4 * h) = q;
+                        *(bf16x4*)(Xh + ((rt_base + j) * 32 + l32) * XP + (ct_base + i) * 32 + 8 * g + 4 * h) = q;
                     }
         }
-        if constexpr (PIPE == 2) { load_v(va, ct0); load_w(wa, ct0); }
         __syncthreads();
+        }   // halves
+        load_v(va, ct0);
+        load_w(wa, ct0, 0);
 
         // ---- stream
         if constexpr (PIPE == 1) {
             VFrag vb2;
             Acc wb2;
-            for (int i = 0; i < nct; i += 2) {
-                if (i + 1 < nct) { load_v(vb2, ct0 + i + 1); load_w(wb2, ct0 + i + 1); }
-                compute_store(va, wa, ct0 + i, -1);
-                if (i + 1 < nct) {
-                    if (i + 2 < nct) { load_v(va, ct0 + i + 2); load_w(wa, ct0 + i + 2); }
-                    compute_store(vb2, wb2, ct0 + i + 1, -1);
+            if constexpr (halves == 1) {
+                for (int i = 0; i < nct; i += 2) {
+                    if (i + 1 < nct) { load_v(vb2, ct0 + i + 1); load_w(wb2, ct0 + i + 1, 0); }
+                    compute_store(va, wa, ct0 + i, 0, -1);
+                    if (i + 1 < nct) {
+                        if (i + 2 < nct) { load_v(va, ct0 + i + 2); load_w(wa, ct0 + i + 2, 0); }
+                        compute_store(vb2, wb2, ct0 + i + 1, 0, -1);
+                    }
+                }
+            } else {
+                // sub-tiles (ct, upper half), (ct, lower half), (ct + 1, upper half), ...: W one
+                // sub-tile ahead, V one column tile ahead
+                for (int i = 0; i < nct; i += 2) {
+                    load_w(wb2, ct0 + i, 1);
+                    if (i + 1 < nct) load_v(vb2, ct0 + i + 1);
+                    compute_store(va, wa, ct0 + i, 0, -1);
+                    if (i + 1 < nct) load_w(wa, ct0 + i + 1, 0);
+                    compute_store(va, wb2, ct0 + i, 1, -1);
+                    if (i + 1 < nct) {
+                        load_w(wb2, ct0 + i + 1, 1);
+                        if (i + 2 < nct) load_v(va, ct0 + i + 2);
+                        compute_store(vb2, wa, ct0 + i + 1, 0, -1);
+                        if (i + 2 < nct) load_w(wa, ct0 + i + 2, 0);
+                        compute_store(vb2, wb2, ct0 + i + 1, 1, -1);
+                    }
                 }
             }
         } else {
             Acc wb2;
             for (int i = 0; i < nct; i += 2) {
-                if (i + 1 < nct) load_w(wb2, ct0 + i + 1);
-                compute_store(va, wa, ct0 + i, (i + 1 < nct && !skip) ? ct0 + i + 1 : -1);
+                if (i + 1 < nct) load_w(wb2, ct0 + i + 1, 0);
+                compute_store(va, wa, ct0 + i, 0, (i + 1 < nct && !skip) ? ct0 + i + 1 : -1);
                 if (i + 1 < nct) {
-                    if (i + 2 < nct) load_w(wa, ct0 + i + 2);
-                    compute_store(va, wb2, ct0 + i + 1, (i + 2 < nct && !skip) ? ct0 + i + 2 : -1);
+                    if (i + 2 < nct) load_w(wa, ct0 + i + 2, 0);
+                    compute_store(va, wb2, ct0 + i + 1, 0, (i + 2 < nct && !skip) ? ct0 + i + 2 : -1);
                 }
             }
         }
     }
 }
 
-// mode: 0 = in-place V prefetch, two workgroups per CU; 1 = software prefetch of whole tiles, one
-// workgroup per CU
+// mode: 0 = 128-row items, in-place V prefetch, two workgroups per CU; 1 = 128-row items, software
+// prefetch of whole tiles, one workgroup per CU; 2 = 256-row items, otherwise as 1
 template <int KSTEPS>
 static hipError_t launch_lift_r(const LiftBlock* blocks_dev, const LiftTile* tiles_dev, const LiftRange* ranges_dev,
                                 int n_wgs, int mode, float alpha, float beta, hipStream_t stream) {
     typedef void (*fn_t)(const LiftBlock*, const LiftTile*, const LiftRange*, float, float);
-    fn_t fn = (mode == 0) ? (fn_t)lift_kernel<KSTEPS, 2, 2> : (fn_t)lift_kernel<KSTEPS, 1, 1>;
-    const int lds = LIFT_TM * (KSTEPS * 16 + 8) * 2;
+    fn_t fn = (mode == 0) ? (fn_t)lift_kernel<KSTEPS, 2, 1, 2>
+              : (mode == 1) ? (fn_t)lift_kernel<KSTEPS, 1, 1, 1> : (fn_t)lift_kernel<KSTEPS, 1, 2, 1>;
+    const int lds = (mode == 2 ? 2 : 1) * LIFT_TM * (KSTEPS * 16 + 8) * 2;
     static thread_local const void* configured[16] = {nullptr};
     bool done = false;
     for (const void* c : configured) if (c == (const void*)fn) { done = true; break; }
@@ -296,7 +331,7 @@ hipError_t launch_lift(const LiftBlock* blocks_dev, const LiftTile* tiles_dev, c
 }
 
 bool lift_supports_rank(int r) { return r == 64 || r == 128 || r == 256; }
-int lift_panel_rows() { return LIFT_TM; }
+int lift_panel_rows(int mode) { return mode == 2 ? 2 * LIFT_TM : LIFT_TM; }
 int lift_wgs_per_cu(int mode) { return mode == 0 ? 2 : 1; }
 
 }  // namespace tsr
