@@ -470,6 +470,9 @@ __device__ inline double wave_sum(double v) {
 // of ~10 sweeps of k^2/2 rotations on 2k-vectors, and everything else is matrix products.
 // Outputs as before: R is overwritten by E^T R, Gacc = E^T.
 constexpr int QL_MAX_ITER = 60;
+constexpr int JAC_PARTS = 4;            // pieces a long sum is cut into (k <= JAC_SPLIT_MAXK)
+constexpr int JAC_SPLIT_MAXK = 544;
+#define JAC_SPLIT_MAXK_OR(k) JAC_SPLIT_MAXK
 
 __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock* table, const JacobiBlock single) {
     const JacobiBlock* blk = table ? table + blockIdx.x : &single;
@@ -483,8 +486,11 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
     __shared__ double s_e[SMALL_MAXK];      // sub-diagonal
     __shared__ double s_v[SMALL_MAXK];      // Householder vector / rotation cosines
     __shared__ double s_w[SMALL_MAXK];      // work vector / rotation sines
+    __shared__ double s_rc[SMALL_MAXK];     // second buffer of rotation cosines
+    __shared__ double s_rs[SMALL_MAXK];     // second buffer of rotation sines
+    __shared__ double s_part[JAC_PARTS * JAC_SPLIT_MAXK];   // partial sums of the split loops
     __shared__ double s_red[SMALL_THREADS / 64];
-    __shared__ int s_int[4];
+    __shared__ int s_job[2][4];
     __shared__ int s_rank[SMALL_MAXK];
 
     auto block_sum = [&](double v) -> double {      // sum over the workgroup, result to all
@@ -497,22 +503,26 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
         return t;
     };
 
-    // ---- T = R R^T (4 x 4 register tiles), W = I
+    // ---- T = R R^T (4 x 4 register tiles), W = I.  R is upper triangular: the sum for T[i][j]
+    // starts at column max(i, j).  R^T goes to W first so that the tiles read along rows.
     {
+        for (int idx = tid; idx < k * k; idx += nt) W[(size_t)(idx % k) * k + idx / k] = R[idx];
+        __syncthreads();
         const int tiles = (k + 3) >> 2;
         for (int q = tid; q < tiles * tiles; q += nt) {
             const int i0 = (q / tiles) * 4, j0 = (q % tiles) * 4;
+            if (j0 < i0) continue;                             // the mirror image is written below
             double acc[4][4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
-            for (int c = 0; c < k; ++c) {
+            for (int c = j0; c < k; ++c) {                     // columns before j0 hold zeros of rows j0..
                 double a[4], b[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    a[u] = (i0 + u < k) ? R[(size_t)(i0 + u) * k + c] : 0.0;
-                    b[u] = (j0 + u < k) ? R[(size_t)(j0 + u) * k + c] : 0.0;
+                    a[u] = (i0 + u < k) ? W[(size_t)c * k + i0 + u] : 0.0;
+                    b[u] = (j0 + u < k) ? W[(size_t)c * k + j0 + u] : 0.0;
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
@@ -523,19 +533,29 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (i0 + u < k && j0 + v < k) T[(size_t)(i0 + u) * k + j0 + v] = acc[u][v];
+                    if (i0 + u < k && j0 + v < k) {
+                        T[(size_t)(i0 + u) * k + j0 + v] = acc[u][v];
+                        T[(size_t)(j0 + v) * k + i0 + u] = acc[u][v];
+                    }
         }
+        __syncthreads();
         for (int idx = tid; idx < k * k; idx += nt) W[idx] = (idx / k == idx % k) ? 1.0 : 0.0;
     }
     __syncthreads();
 
-    // ---- Householder tridiagonalization of T (full symmetric storage), W <- H_j W as we go
+    // ---- Householder tridiagonalization of T (full symmetric storage), W <- H_j W as we go.
+    // The two long loops of a step (the product T22 v and the update of W) have only n1 or k
+    // independent outputs; each output's sum is cut into `parts` pieces so that all threads
+    // carry loads (the step is bound by memory latency, not by arithmetic).
+    const int parts = (k <= JAC_SPLIT_MAXK) ? JAC_PARTS : 1;
+    const int tpp = nt / parts;                          // threads per part
+    const int part = tid / tpp, li = tid % tpp;
     for (int j = 0; j + 2 < k; ++j) {
         const int n1 = k - j - 1;                       // length of the column below the diagonal
         // x = T[j+1.., j]; alpha = -sign(x0) |x|; v = x - alpha e1; H = I - beta v v^T
-        double part = 0.0;
-        for (int i = tid; i < n1; i += nt) { const double x = T[(size_t)(j + 1 + i) * k + j]; s_v[i] = x; part += x * x; }
-        const double xnorm2 = block_sum(part);
+        double psum = 0.0;
+        for (int i = tid; i < n1; i += nt) { const double x = T[(size_t)(j + 1 + i) * k + j]; s_v[i] = x; psum += x * x; }
+        const double xnorm2 = block_sum(psum);
         const double x0 = s_v[0];
         const double xn = sqrt(xnorm2);
         double alpha = (x0 >= 0.0) ? -xn : xn;
@@ -547,25 +567,33 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
         __syncthreads();
         if (skip) continue;
         const double beta = 2.0 / vnorm2;
+        const int seg = (n1 + parts - 1) / parts;
+        const int c_lo = min(n1, part * seg), c_hi = min(n1, c_lo + seg);
         // p = beta T22 v   (T22 symmetric: read columns as rows, coalesced over the output index)
-        for (int i = tid; i < n1; i += nt) {
+        for (int i = li; i < n1; i += tpp) {
             // eight independent partial sums keep eight loads in flight (the sum is a serial chain)
             double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
             const double* col = T + (size_t)(j + 1) * k + (j + 1 + i);
-            int c = 0;
-            for (; c + 8 <= n1; c += 8) {
+            int c = c_lo;
+            for (; c + 8 <= c_hi; c += 8) {
                 double x[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) x[u] = col[(size_t)(c + u) * k];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) acc[u] += x[u] * s_v[c + u];
             }
-            for (; c < n1; ++c) acc[0] += col[(size_t)c * k] * s_v[c];
-            s_w[i] = beta * (((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7])));
+            for (; c < c_hi; ++c) acc[0] += col[(size_t)c * k] * s_v[c];
+            s_part[part * JAC_SPLIT_MAXK_OR(k) + i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
         }
         __syncthreads();
         double pv = 0.0;
-        for (int i = tid; i < n1; i += nt) pv += s_w[i] * s_v[i];
+        for (int i = tid; i < n1; i += nt) {
+            double t = 0.0;
+            for (int q = 0; q < parts; ++q) t += s_part[q * JAC_SPLIT_MAXK_OR(k) + i];
+            t *= beta;
+            s_w[i] = t;
+            pv += t * s_v[i];
+        }
         const double kk2 = 0.5 * beta * block_sum(pv);
         for (int i = tid; i < n1; i += nt) s_w[i] -= kk2 * s_v[i];           // w = p - (beta/2)(p.v) v
         __syncthreads();
@@ -574,29 +602,37 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
             const int i = idx / n1, c = idx % n1;
             T[(size_t)(j + 1 + i) * k + j + 1 + c] -= s_v[i] * s_w[c] + s_w[i] * s_v[c];
         }
-        // W[j+1.., :] -= beta v (v^T W[j+1.., :])
-        for (int c = tid; c < k; c += nt) {
-            double* wc = W + (size_t)(j + 1) * k + c;
+        // W[j+1.., :] -= beta v (v^T W[j+1.., :]): partial column dots first ...
+        for (int c = li; c < k; c += tpp) {
+            const double* wc = W + (size_t)(j + 1) * k + c;
             double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-            int i = 0;
-            for (; i + 8 <= n1; i += 8) {
+            int i = c_lo;
+            for (; i + 8 <= c_hi; i += 8) {
                 double x[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) x[u] = wc[(size_t)(i + u) * k];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) acc[u] += x[u] * s_v[i + u];
             }
-            for (; i < n1; ++i) acc[0] += wc[(size_t)i * k] * s_v[i];
-            const double y = beta * (((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7])));
-            i = 0;
-            for (; i + 8 <= n1; i += 8) {
+            for (; i < c_hi; ++i) acc[0] += wc[(size_t)i * k] * s_v[i];
+            s_part[part * JAC_SPLIT_MAXK_OR(k) + c] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+        }
+        __syncthreads();
+        // ... then every part updates its own rows
+        for (int c = li; c < k; c += tpp) {
+            double* wc = W + (size_t)(j + 1) * k + c;
+            double y = 0.0;
+            for (int q = 0; q < parts; ++q) y += s_part[q * JAC_SPLIT_MAXK_OR(k) + c];
+            y *= beta;
+            int i = c_lo;
+            for (; i + 8 <= c_hi; i += 8) {
                 double x[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) x[u] = wc[(size_t)(i + u) * k];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) wc[(size_t)(i + u) * k] = x[u] - s_v[i + u] * y;
             }
-            for (; i < n1; ++i) wc[(size_t)i * k] -= s_v[i] * y;
+            for (; i < c_hi; ++i) wc[(size_t)i * k] -= s_v[i] * y;
         }
         __syncthreads();
     }
@@ -608,82 +644,108 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
     __syncthreads();
 
     // ---- implicit QL on (d, e); every rotation (c, s) of rows (i, i+1) is applied to W.
-    // Per QL sweep: all threads look for the first negligible sub-diagonal entry at or after l;
-    // thread 0 runs the scalar recurrences (operands prefetched one step ahead, the hypotenuse
-    // from a reciprocal square root) and records the rotations in s_v (c) and s_w (s); then
-    // every thread applies the recorded chain to its column of W.
-    for (int l = 0; l < k; ++l) {
-        for (int iter = 0; iter <= QL_MAX_ITER; ++iter) {
-            if (tid == 0) s_int[0] = k - 1;
-            __syncthreads();
-            for (int i = l + tid; i < k - 1; i += nt) {
-                const double dd = fabs(s_d[i]) + fabs(s_d[i + 1]);
-                if (fabs(s_e[i]) <= 2.3e-16 * dd) atomicMin(&s_int[0], i);
-            }
-            __syncthreads();
-            const int m = s_int[0];
-            if (m == l || iter >= QL_MAX_ITER) break;
-            if (tid == 0) {
-                int lo = m;                                   // rotations recorded for rows lo .. m-1
-                double g = (s_d[l + 1] - s_d[l]) / (2.0 * s_e[l]);
-                double rr = sqrt(g * g + 1.0);
-                g = s_d[m] - s_d[l] + s_e[l] / (g + ((g >= 0.0) ? fabs(rr) : -fabs(rr)));
-                double sn = 1.0, cs = 1.0, pp = 0.0;
-                double e_i = s_e[m - 1], d_i = s_d[m - 1], d_ip1 = s_d[m];
-                bool under = false;
-                for (int i = m - 1; i >= l; --i) {
-                    const double e_n = (i > l) ? s_e[i - 1] : 0.0;     // next step's operands
-                    const double d_n = (i > l) ? s_d[i - 1] : 0.0;
-                    const double f = sn * e_i;
-                    const double bb = cs * e_i;
-                    const double h2 = f * f + g * g;
-                    if (h2 == 0.0) { s_e[i + 1] = 0.0; s_d[i + 1] -= pp; s_e[m] = 0.0; under = true; break; }
-                    double rinv = __builtin_amdgcn_rsq(h2);
-                    const double hh = 0.5 * h2;
-                    rinv = rinv * (1.5 - hh * rinv * rinv);
-                    rinv = rinv * (1.5 - hh * rinv * rinv);
-                    s_e[i + 1] = h2 * rinv;
-                    sn = f * rinv; cs = g * rinv;
-                    g = d_ip1 - pp;
-                    rr = (d_i - g) * sn + 2.0 * cs * bb;
-                    pp = sn * rr;
-                    s_d[i + 1] = g + pp;
-                    g = cs * rr - bb;
-                    s_v[i] = cs; s_w[i] = sn;
-                    lo = i;
-                    d_ip1 = d_i; d_i = d_n; e_i = e_n;
+    // The scalar recurrences of a QL sweep are one serial chain and touch only (d, e); applying
+    // the sweep's rotations to W touches only W.  So wave 0 produces sweeps (its lanes look for
+    // the first negligible sub-diagonal entry at or after l, its lane 0 runs the recurrences,
+    // operands prefetched one step ahead, the hypotenuse from a reciprocal square root, and
+    // records the rotations) while the other waves apply the previous sweep to their columns of
+    // W; one barrier per sweep hands the buffers over.
+    {
+        int l = 0, iter = 0;                              // producer state (wave 0, uniform)
+        // job[b] = {m, lo, kind}; kind 1: apply rotations lo..m-1 from buffer b, 2: finished
+        auto produce = [&](int b) {
+            for (;;) {
+                if (l >= k) { if (lane == 0) { s_job[b][2] = 2; } return; }
+                int m = k - 1;
+                for (int i = l + lane; i < k - 1; i += 64) {
+                    const double dd = fabs(s_d[i]) + fabs(s_d[i + 1]);
+                    if (fabs(s_e[i]) <= 2.3e-16 * dd) { m = i; break; }
                 }
-                if (!under) { s_d[l] -= pp; s_e[l] = g; s_e[m] = 0.0; }
-                s_int[1] = lo;
-            }
-            __syncthreads();
-            const int lo = s_int[1];
-            for (int c = tid; c < k; c += nt) {
-                double* wc = W + c;
-                double hi = wc[(size_t)m * k];                 // current row i+1, starting with i = m-1
-                int i = m - 1;
-                for (; i - 7 >= lo; i -= 8) {                  // eight rows fetched together
-                    double a[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) a[u] = wc[(size_t)(i - u) * k];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const double cs = s_v[i - u], sn = s_w[i - u];
-                        wc[(size_t)(i - u + 1) * k] = sn * a[u] + cs * hi;
-                        hi = cs * a[u] - sn * hi;
+                for (int o = 32; o > 0; o >>= 1) m = min(m, __shfl_xor(m, o, 64));
+                if (m == l || iter >= QL_MAX_ITER) { ++l; iter = 0; continue; }
+                ++iter;
+                if (lane == 0) {
+                    double* rc = b ? s_rc : s_v;
+                    double* rs = b ? s_rs : s_w;
+                    int lo = m;                                   // rotations recorded for rows lo .. m-1
+                    double g = (s_d[l + 1] - s_d[l]) / (2.0 * s_e[l]);
+                    double rr = sqrt(g * g + 1.0);
+                    g = s_d[m] - s_d[l] + s_e[l] / (g + ((g >= 0.0) ? fabs(rr) : -fabs(rr)));
+                    double sn = 1.0, cs = 1.0, pp = 0.0;
+                    double e_i = s_e[m - 1], d_i = s_d[m - 1], d_ip1 = s_d[m];
+                    bool under = false;
+                    for (int i = m - 1; i >= l; --i) {
+                        const double e_n = (i > l) ? s_e[i - 1] : 0.0;     // next step's operands
+                        const double d_n = (i > l) ? s_d[i - 1] : 0.0;
+                        const double f = sn * e_i;
+                        const double bb = cs * e_i;
+                        const double h2 = f * f + g * g;
+                        if (h2 == 0.0) { s_e[i + 1] = 0.0; s_d[i + 1] -= pp; s_e[m] = 0.0; under = true; break; }
+                        double rinv = __builtin_amdgcn_rsq(h2);
+                        const double hh = 0.5 * h2;
+                        rinv = rinv * (1.5 - hh * rinv * rinv);
+                        rinv = rinv * (1.5 - hh * rinv * rinv);
+                        s_e[i + 1] = h2 * rinv;
+                        sn = f * rinv; cs = g * rinv;
+                        g = d_ip1 - pp;
+                        rr = (d_i - g) * sn + 2.0 * cs * bb;
+                        pp = sn * rr;
+                        s_d[i + 1] = g + pp;
+                        g = cs * rr - bb;
+                        rc[i] = cs; rs[i] = sn;
+                        lo = i;
+                        d_ip1 = d_i; d_i = d_n; e_i = e_n;
                     }
+                    if (!under) { s_d[l] -= pp; s_e[l] = g; s_e[m] = 0.0; }
+                    s_job[b][0] = m; s_job[b][1] = lo; s_job[b][2] = 1;
                 }
-                for (; i >= lo; --i) {
-                    const double cs = s_v[i], sn = s_w[i];
-                    const double a = wc[(size_t)i * k];
-                    wc[(size_t)(i + 1) * k] = sn * a + cs * hi;
-                    hi = cs * a - sn * hi;
+                // lane 0's updates of (d, e) must be visible to the whole wave's next search
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                return;
+            }
+        };
+        const int n_cons = nt - 64;                      // threads that apply rotations
+        if (wave == 0) produce(0);
+        __syncthreads();
+        for (int cur = 0;; cur ^= 1) {
+            const int kind = s_job[cur][2];
+            if (kind == 2) break;
+            if (wave == 0) {
+                produce(cur ^ 1);
+            } else {
+                const int m = s_job[cur][0], lo = s_job[cur][1];
+                const double* rc = cur ? s_rc : s_v;
+                const double* rs = cur ? s_rs : s_w;
+                for (int c = tid - 64; c < k; c += n_cons) {
+                    double* wc = W + c;
+                    double hi = wc[(size_t)m * k];                 // current row i+1, starting with i = m-1
+                    int i = m - 1;
+                    for (; i - 7 >= lo; i -= 8) {                  // eight rows fetched together
+                        double a[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) a[u] = wc[(size_t)(i - u) * k];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const double cs = rc[i - u], sn = rs[i - u];
+                            wc[(size_t)(i - u + 1) * k] = sn * a[u] + cs * hi;
+                            hi = cs * a[u] - sn * hi;
+                        }
+                    }
+                    for (; i >= lo; --i) {
+                        const double cs = rc[i], sn = rs[i];
+                        const double a = wc[(size_t)i * k];
+                        wc[(size_t)(i + 1) * k] = sn * a + cs * hi;
+                        hi = cs * a - sn * hi;
+                    }
+                    wc[(size_t)lo * k] = hi;
                 }
-                wc[(size_t)lo * k] = hi;
             }
             __syncthreads();
         }
     }
+    __syncthreads();
 
     // ---- T <- W R  (rows of E^T R), 4 x 4 register tiles
     {
@@ -695,7 +757,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
-            for (int j = 0; j < k; ++j) {
+            const int jend = min(k, c0 + 4);                   // R is upper triangular
+            for (int j = 0; j < jend; ++j) {
                 double a[4], b[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
