@@ -248,7 +248,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
     const int ti = tid >> 5, tc = tid & 31;    // 32 x 32 thread grid
     __shared__ double Ld[CHB][CHB_P];
     __shared__ double Li[CHB][CHB_P];
-    extern __shared__ double Pn[];             // [rows below the diagonal block][CHB_P]
+    extern __shared__ double Pn[];             // [(block rows - 1) * CHB][CHB_P]
 
     for (int idx = tid; idx < k * k; idx += SMALL_THREADS) { A[idx] = (double)S[idx]; X[idx] = 0.0; }
     __syncthreads();
@@ -258,29 +258,45 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
         // ---- diagonal block -> LDS (identity padding), unblocked factorization
         Ld[ti][tc] = (ti < jb && tc < jb) ? ((tc <= ti) ? A[(size_t)(J + ti) * k + J + tc] : 0.0) : (ti == tc ? 1.0 : 0.0);
         __syncthreads();
-        for (int j = 0; j < jb; ++j) {
-            const double a = Ld[j][j];
-            const double s0 = (double)S[(size_t)(J + j) * k + J + j];
-            const bool ok = (a > 0.0) && (a > tol * s0);
-            const double d = ok ? sqrt(a) : 0.0;
-            const double invd = ok ? 1.0 / d : 0.0;
-            __syncthreads();                                   // everyone has read the pivot
-            if (tc == j && ti > j) Ld[ti][j] *= invd;
-            if (tc == j && ti == j) Ld[j][j] = d;
-            __syncthreads();
-            if (tc > j && tc <= ti) Ld[ti][tc] -= Ld[ti][j] * Ld[tc][j];
-            __syncthreads();
+        // One wave factors the 32 x 32 block: lane i owns row i in registers, column j of L is
+        // final after step j and is published through LDS for the later steps (LDS operations of
+        // one wave complete in order, so no workgroup barrier is needed inside the loop).
+        if (tid < 64) {
+            const int i = tid & 31;
+            const bool act = tid < CHB;
+            double arow[CHB];
+#pragma unroll
+            for (int c = 0; c < CHB; ++c) arow[c] = Ld[i][c];
+            const double sdiag = (i < jb) ? (double)S[(size_t)(J + i) * k + J + i] : 1.0;
+#pragma unroll
+            for (int j = 0; j < CHB; ++j) {
+                double v = arow[j];
+#pragma unroll
+                for (int c = 0; c < j; ++c) v -= arow[c] * Ld[j][c];
+                const double piv = __shfl(v, j, 64);
+                const double s0 = __shfl(sdiag, j, 64);
+                const bool ok = (piv > 0.0) && (piv > tol * s0);
+                const double d = ok ? sqrt(piv) : 0.0;
+                const double invd = ok ? 1.0 / d : 0.0;
+                arow[j] = (i == j) ? d : v * invd;
+                if (act && i >= j) Ld[i][j] = arow[j];
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
         }
+        __syncthreads();
         // ---- inverse of the diagonal block (dropped pivots: zero row and column)
         if (tid < CHB) {
-            const int c = tid;                                // column c of the inverse, kept in Li[.][c]
-#pragma unroll 1
+            const int c = tid;                                // column c of the inverse, in registers
+            double xc[CHB];
+#pragma unroll
             for (int i = 0; i < CHB; ++i) {
                 double sacc = (i == c) ? 1.0 : 0.0;
-#pragma unroll 4
-                for (int j = 0; j < i; ++j) sacc -= Ld[i][j] * Li[j][c];
+#pragma unroll
+                for (int j = 0; j < i; ++j) sacc -= Ld[i][j] * xc[j];
                 const double d = Ld[i][i];
-                Li[i][c] = (d != 0.0) ? sacc / d : 0.0;
+                xc[i] = (d != 0.0) ? sacc / d : 0.0;
+                Li[i][c] = xc[i];
             }
         }
         __syncthreads();
@@ -361,20 +377,21 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
     }
 
     // ---- off-diagonal blocks of X = L^-1, block row by block row:
-    //      X[I][J] = -Li_I * sum_{K=J}^{I-1} L[I][K] X[K][J]
+    //      X[I][J] = -Li_I * sum_{K=J}^{I-1} L[I][K] X[K][J]   for all J < I at once.
+    // The sums (32 rows x 32 I columns) are parked in the panel buffer as Pn[col][row].
     const int nblk = (k + CHB - 1) / CHB;
     for (int I = 1; I < nblk; ++I) {
         const int ib = min(CHB, k - I * CHB);
+        const int ncol = I * CHB;
         Li[ti][tc] = (ti < ib && tc < ib) ? X[(size_t)(I * CHB + ti) * k + I * CHB + tc] : 0.0;
-        __syncthreads();
-        for (int J = 0; J < I; ++J) {
+        // thread (ti, tc): row ti of the block row, columns tc, tc + 32, ...
+        for (int col = tc; col < ncol; col += CHB) {
             double sacc = 0.0;
             if (ti < ib) {
                 const double* lrow = A + (size_t)(I * CHB + ti) * k;
-                // independent partial sums keep several loads in flight
+                const double* xcol = X + col;
                 double pa[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-                const double* xcol = X + J * CHB + tc;
-                for (int c = J * CHB; c < I * CHB; c += 8) {      // both bounds are multiples of 32
+                for (int c = (col / CHB) * CHB; c < ncol; c += 8) {      // both bounds are multiples of 32
                     double xv[8], lv[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) { xv[u] = xcol[(size_t)(c + u) * k]; lv[u] = lrow[c + u]; }
@@ -383,16 +400,18 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
                 }
                 sacc = ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pa[4] + pa[5]) + (pa[6] + pa[7]));
             }
-            Ld[ti][tc] = sacc;
-            __syncthreads();
+            Pn[col * CHB_P + ti] = sacc;
+        }
+        __syncthreads();
+        for (int col = tc; col < ncol; col += CHB) {
             if (ti < ib) {
                 double v = 0.0;
 #pragma unroll 8
-                for (int a2 = 0; a2 < CHB; ++a2) v += Li[ti][a2] * Ld[a2][tc];       // Li lower: zero for a2 > ti
-                X[(size_t)(I * CHB + ti) * k + J * CHB + tc] = -v;
+                for (int a2 = 0; a2 < CHB; ++a2) v += Li[ti][a2] * Pn[col * CHB_P + a2];     // Li lower: zero for a2 > ti
+                X[(size_t)(I * CHB + ti) * k + col] = -v;
             }
-            __syncthreads();
         }
+        __syncthreads();
     }
     __syncthreads();
 
@@ -402,31 +421,48 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
         const int a = idx / k, b = idx % k;
         Rinv[idx] = (a <= b) ? (float)X[(size_t)b * k + a] : 0.0f;
     }
-    // Rtot = R Rprev with R = L^T
+    // Rtot = R Rprev with R = L^T: both upper triangular, so entry (a, b) sums over a <= c <= b;
+    // 4 x 4 register tiles (rows of L^T are columns of A: four consecutive doubles per load)
     double* Rtot = blk->Rtot;
     if (Rtot != nullptr) {
         const double* Rp = blk->Rprev;
-        for (int idx = tid; idx < k * k; idx += SMALL_THREADS) {
-            const int a = idx / k, b = idx % k;
-            double sacc = 0.0;
-            if (a <= b) {
-                if (Rp == nullptr) {
-                    sacc = A[(size_t)b * k + a];
-                } else {
-                    double pa[4] = {0.0, 0.0, 0.0, 0.0};
-                    int c = a;
-                    for (; c + 3 <= b; c += 4) {
-                        double av[4], rv[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) { av[u] = A[(size_t)(c + u) * k + a]; rv[u] = Rp[(size_t)(c + u) * k + b]; }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) pa[u] += av[u] * rv[u];
-                    }
-                    for (; c <= b; ++c) pa[0] += A[(size_t)c * k + a] * Rp[(size_t)c * k + b];
-                    sacc = (pa[0] + pa[1]) + (pa[2] + pa[3]);
-                }
+        if (Rp == nullptr) {
+            for (int idx = tid; idx < k * k; idx += SMALL_THREADS) {
+                const int a = idx / k, b = idx % k;
+                Rtot[idx] = (a <= b) ? A[(size_t)b * k + a] : 0.0;
             }
-            Rtot[idx] = sacc;
+        } else {
+            const int tiles = (k + 3) >> 2;
+            for (int q = tid; q < tiles * tiles; q += SMALL_THREADS) {
+                const int a0 = (q / tiles) * 4, b0 = (q % tiles) * 4;
+                double acc[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+                if (b0 >= a0) {
+                    const int cend = min(k, b0 + 4);
+#pragma unroll 2
+                    for (int c = a0; c < cend; ++c) {
+                        double lv[4], rv[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            // A holds L in its lower triangle and zeros above it
+                            lv[u] = (a0 + u < k) ? A[(size_t)c * k + a0 + u] : 0.0;
+                            rv[u] = (b0 + u < k) ? Rp[(size_t)c * k + b0 + u] : 0.0;
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) acc[u][v] += lv[u] * rv[v];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (a0 + u < k && b0 + v < k) Rtot[(size_t)(a0 + u) * k + b0 + v] = (a0 + u <= b0 + v) ? acc[u][v] : 0.0;
+            }
         }
     }
 }
@@ -437,11 +473,14 @@ hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, 
     CholBlock sb{};
     if (single) sb = *single;
     if (max_k <= CHB_MAXK) {
-        const int lds = (max_k > CHB ? max_k - CHB : 1) * CHB_P * 8;
+        // panel rows below the first diagonal block, and (inverse phase) every column left of the
+        // last block row: both at most (number of block rows - 1) * CHB
+        const int pn_rows = (max_k > CHB) ? ((max_k + CHB - 1) / CHB - 1) * CHB : 1;
+        const int lds = pn_rows * CHB_P * 8;
         static thread_local bool configured = false;
         if (!configured) {
             hipError_t e = hipFuncSetAttribute((const void*)chol_inv_blocked_kernel,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (CHB_MAXK - CHB) * CHB_P * 8);
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, ((CHB_MAXK + CHB - 1) / CHB - 1) * CHB * CHB_P * 8);
             if (e != hipSuccess) return e;
             configured = true;
         }
@@ -517,6 +556,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+#pragma unroll 2
             for (int c = j0; c < k; ++c) {                     // columns before j0 hold zeros of rows j0..
                 double a[4], b[4];
 #pragma unroll
@@ -758,6 +798,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
             const int jend = min(k, c0 + 4);                   // R is upper triangular
+#pragma unroll 2
             for (int j = 0; j < jend; ++j) {
                 double a[4], b[4];
 #pragma unroll
