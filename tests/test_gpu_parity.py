@@ -172,7 +172,10 @@ def check_orthonormal(X, tol=1e-4):
     assert np.abs(X.T @ X - np.eye(X.shape[1])).max() < tol
 
 
-@pytest.mark.parametrize("m,n,r,p,q", [(96, 160, 8, 4, 1), (160, 96, 8, 4, 0), (300, 260, 24, 8, 2)])
+# the last case has k = r + p = 560: beyond the blocked Cholesky and the split sums of the
+# eigen-solver (both for k <= 544), so it runs their general variants
+@pytest.mark.parametrize("m,n,r,p,q", [(96, 160, 8, 4, 1), (160, 96, 8, 4, 0), (300, 260, 24, 8, 2),
+                                       (640, 600, 552, 8, 1)])
 def test_refresh_well_separated_spectrum(tsr, m, n, r, p, q):
     # singular values 2 .. 1 then a gap down to the noise: the top-r subspace is well conditioned
     G64, A, B = si.exact_lowrank(m, n, r, si.stream_key(501, m, n))
@@ -183,7 +186,12 @@ def test_refresh_well_separated_spectrum(tsr, m, n, r, p, q):
     check_orthonormal(U); check_orthonormal(V)
     assert projector_err(U, U_ref) < TOL_F32
     assert projector_err(V, V_ref) < TOL_F32
-    assert rel_fro(sigma, S_ref) < TOL_F32
+    # the r retained singular values carry the bar; of the p oversampling directions, those whose
+    # Cholesky pivot falls below the fp32 Gram matrix's resolution are dropped as dependent
+    # (zero singular value) where Householder QR keeps them -- they never enter U or V
+    assert rel_fro(sigma[:r], S_ref[:r]) < TOL_F32
+    tail = orc.f64(sigma[r:])
+    assert np.all((np.abs(tail - S_ref[r:]) < 1e-3 * S_ref[0]) | (tail < 1e-6 * S_ref[0]))
 
 
 def test_refresh_exact_rank_r_input(tsr):
