@@ -14,7 +14,9 @@ namespace tsr {
 struct NtStageH {
     NtVariant var{};
     std::vector<NtProblem> probs;
-    std::vector<NtTile> tiles;            // XCD-interleaved, idle entries have prob < 0
+    std::vector<NtTile> tiles;            // XCD-interleaved, idle entries have prob < 0; or grouped by list
+    std::vector<NtRange> ranges;          // persistent launch: one list of tiles per workgroup
+    const NtRange* d_ranges = nullptr;
     std::vector<ReduceProblem> reduces;   // empty when the GEMM writes its output directly
     int max_reduce_elems = 0;
     const NtProblem* d_probs = nullptr;

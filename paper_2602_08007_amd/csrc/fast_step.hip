@@ -65,8 +65,53 @@ void interleave_xcd(std::vector<TileT>& tiles, const std::vector<int>& tile_bloc
     tiles.swap(out);
 }
 
+// Persistent launch: the tiles of each XCD's blocks are dealt to that XCD's workgroups, heaviest
+// first onto the lightest list, and each list keeps the natural tile order (tiles that share an
+// operand stay neighbours).  List j of XCD x belongs to workgroup 8 j + x.
+void persistent_lists(std::vector<NtTile>& tiles, std::vector<NtRange>& ranges, const std::vector<int>& tile_block,
+                      const std::vector<long long>& tile_work, int n_blocks, int lists_per_xcd) {
+    std::vector<long long> work(n_blocks, 0);
+    for (size_t i = 0; i < tiles.size(); ++i) work[tile_block[i]] += tile_work[i];
+    std::vector<int> order(n_blocks);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return work[a] > work[b]; });
+    std::vector<int> xcd_of(n_blocks, 0);
+    long long load[N_XCD] = {0};
+    for (int b : order) {
+        int best = 0;
+        for (int x = 1; x < N_XCD; ++x) if (load[x] < load[best]) best = x;
+        xcd_of[b] = best;
+        load[best] += work[b];
+    }
+    std::vector<NtTile> out;
+    out.reserve(tiles.size());
+    ranges.assign((size_t)N_XCD * lists_per_xcd, NtRange{0, 0});
+    for (int x = 0; x < N_XCD; ++x) {
+        std::vector<int> mine;
+        for (size_t i = 0; i < tiles.size(); ++i) if (xcd_of[tile_block[i]] == x) mine.push_back((int)i);
+        std::vector<int> by_work = mine;
+        std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return tile_work[a] > tile_work[b]; });
+        std::vector<long long> lw(lists_per_xcd, 0);
+        std::vector<std::vector<int>> lists(lists_per_xcd);
+        for (int i : by_work) {
+            int best = 0;
+            for (int j = 1; j < lists_per_xcd; ++j) if (lw[j] < lw[best]) best = j;
+            lists[best].push_back(i);
+            lw[best] += tile_work[i];
+        }
+        for (int j = 0; j < lists_per_xcd; ++j) {
+            std::sort(lists[j].begin(), lists[j].end());
+            NtRange& r = ranges[(size_t)N_XCD * j + x];
+            r.begin = (int)out.size();
+            for (int i : lists[j]) out.push_back(tiles[i]);
+            r.end = (int)out.size();
+        }
+    }
+    tiles.swap(out);
+}
+
 void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogical>& gemms, int n_blocks, Arena& ar,
-                    int want_tiles) {
+                    int want_tiles, bool persistent = false) {
     st = NtStageH{};
     st.var = var;
     if (gemms.empty()) return;
@@ -132,7 +177,11 @@ void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogi
         }
         i = e;
     }
-    interleave_xcd(st.tiles, tile_block, tile_work, n_blocks, NtTile{-1, 0, 0, 0});
+    if (persistent)
+        persistent_lists(st.tiles, st.ranges, tile_block, tile_work, n_blocks,
+                         tune_int("TSR_TUNE_NT_CUS", 256, 8, 4096) / N_XCD * nt_wgs_per_cu(var.shape));
+    else
+        interleave_xcd(st.tiles, tile_block, tile_work, n_blocks, NtTile{-1, 0, 0, 0});
 }
 
 int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind) {
@@ -140,6 +189,7 @@ int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind)
     Timed timed(cx, kind);
     NtLaunch L{};
     L.probs = st.d_probs; L.tiles = st.d_tiles; L.n_tiles = (int)st.tiles.size();
+    if (!st.ranges.empty()) { L.ranges = st.d_ranges; L.n_tiles = (int)st.ranges.size(); }
     if (st.reduces.empty()) {
         L.alpha = alpha; L.beta = beta;
         TSR_HIP(launch_nt_gemm(L, st.var, cx.s));
@@ -157,6 +207,7 @@ void upload_nt_stage(NtStageH& st, Arena& ar, Uploader& up) {
     st.d_probs = up.put(st.probs, ar);
     st.d_tiles = up.put(st.tiles, ar);
     if (!st.reduces.empty()) st.d_reduces = up.put(st.reduces, ar);
+    if (!st.ranges.empty()) st.d_ranges = up.put(st.ranges, ar);
 }
 
 }  // namespace
@@ -268,9 +319,13 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
         }
     }
     const int s1_shape = tune("TSR_TUNE_GV", (r_max > 64) ? NT_128x128 : NT_64x256);
-    build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1);
-    build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1);
-    build_nt_stage(fs.utp, NtVariant{tune("TSR_TUNE_UTP", r_max > 64 ? NT_128x128 : NT_64x64), 0, 0}, utp, nb, ar, 512);
+    // persistent launches pay off for the many short tiles of U^T P, not for the G V stage
+    const bool gv_persist = tune_int("TSR_TUNE_GV_PERSIST", 0, 0, 1) != 0;
+    const bool utp_persist = tune_int("TSR_TUNE_UTP_PERSIST", 1, 0, 1) != 0;
+    build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1, gv_persist);
+    build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1, gv_persist);
+    build_nt_stage(fs.utp, NtVariant{tune("TSR_TUNE_UTP", NT_64x64), 0, 0}, utp, nb, ar,
+                   tune_int("TSR_TUNE_UTP_TILES", 2048, 1, 65536), utp_persist);
     build_nt_stage(fs.ud, NtVariant{tune("TSR_TUNE_UD", NT_128x128), 0, 1}, ud, nb, ar, 1);
     build_nt_stage(fs.tvt, NtVariant{tune("TSR_TUNE_TVT", NT_128x128), 0, 0}, tvt, nb, ar, 1);
 }

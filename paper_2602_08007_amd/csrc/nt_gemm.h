@@ -22,10 +22,16 @@ struct NtProblem {
 };
 
 struct NtTile { int prob, tm, tn, ks; };     // prob < 0: idle workgroup
+struct NtRange { int begin, end; };          // tiles [begin, end) of one persistent workgroup
 
+// With `ranges` set the launch is persistent: workgroup w walks tiles[ranges[w].begin ..
+// ranges[w].end) and keeps its load pipeline running across tile boundaries (the k-tiles of the
+// next tile are on their way while the current tile finishes and is written out); n_tiles is
+// then the number of workgroups.  Not available for the read-modify-write epilogue (beta != 0).
 struct NtLaunch {
     const NtProblem* probs;
     const NtTile* tiles;
+    const NtRange* ranges;
     int n_tiles;
     float alpha, beta;
 };
@@ -51,6 +57,7 @@ struct NtVariant {
 };
 
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream);
+int nt_wgs_per_cu(int shape);   // resident workgroups per CU the kernel of this shape is built for
 
 // fp32 bases -> bf16 shadows: X (rows x r, contiguous fp32) -> Xb (rows x ldx bf16) and
 // XTb (r x ldt bf16, the transpose); padding columns are written as zeros.  XFb (optional,

@@ -260,12 +260,169 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
             }
 }
 
+// ------------------------------------------------------------------ persistent variant
+// One workgroup walks a list of tiles.  The k-tiles of all its tiles form one stream that runs
+// through the same pipeline as above (two register stages, two LDS buffers) without draining at
+// tile boundaries: the loader cursor runs three k-tiles ahead of the compute cursor and moves on
+// to the next tile by itself.  A tile's accumulators are written out when the compute cursor
+// leaves it.  OUT: 0 = fp32 store, 1 = bf16 store.
+template <int TM, int TN, int WM, int WN, int NT_BK, bool B_F32, int OUT, int MINB>
+__global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(const NtLaunch L) {
+    constexpr bool OUT_BF16 = (OUT == 1);
+    static_assert(WM * WN == 4, "four waves");
+    static_assert(OUT == 0 || OUT == 1, "no read-modify-write epilogue here");
+    constexpr int NT_KP = NT_BK + 8;
+    constexpr int FM = TM / WM / 32, FN = TN / WN / 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+    constexpr int A_ELEMS = TM * NT_KP, B_ELEMS = TN * NT_KP, BUF = A_ELEMS + B_ELEMS;
+
+    const NtRange range = L.ranges[blockIdx.x];
+    if (range.begin >= range.end) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const float alpha = L.alpha;
+
+    auto tile_nk = [&](const NtTile& t) -> int {
+        const NtProblem* pp = L.probs + t.prob;
+        const int kbeg = t.ks * pp->kchunk;
+        const int kend = min(pp->K, kbeg + pp->kchunk);
+        return (kend - kbeg + NT_BK - 1) / NT_BK;
+    };
+    int total = 0;                                           // k-tiles of the whole list
+    for (int t = range.begin; t < range.end; ++t) total += tile_nk(L.tiles[t]);
+
+    // ---- loader cursor
+    int lt = range.begin, lk = 0;
+    nt_rsrc_t rA, rB;
+    unsigned lda_b, ldb_b;
+    int l_row0, l_col0, l_kbeg, l_kend, l_nk;
+    auto open_tile = [&](int t) {
+        const NtTile tl = L.tiles[t];
+        const NtProblem* pp = L.probs + tl.prob;
+        const long long k8 = (pp->K + 7) & ~7;
+        rA = nt_make_rsrc(pp->A, ((long long)(pp->M - 1) * pp->lda + k8) * 2);
+        rB = nt_make_rsrc(pp->B, ((long long)(pp->N - 1) * pp->ldb + k8) * (B_F32 ? 4 : 2));
+        lda_b = (unsigned)pp->lda * 2u;
+        ldb_b = (unsigned)pp->ldb * (B_F32 ? 4u : 2u);
+        l_row0 = tl.tm * TM; l_col0 = tl.tn * TN;
+        l_kbeg = tl.ks * pp->kchunk;
+        l_kend = min(pp->K, l_kbeg + pp->kchunk);
+        l_nk = (l_kend - l_kbeg + NT_BK - 1) / NT_BK;
+    };
+    open_tile(lt);
+    NtStage<TM * NT_BK / 8 / NT_THREADS, false> stA[2];
+    NtStage<TN * NT_BK / 8 / NT_THREADS, B_F32> stB[2];
+    auto load_next = [&](int slot) {
+        const int k0 = l_kbeg + lk * NT_BK;
+        const bool tail = k0 + NT_BK > l_kend;
+        nt_load<TM, NT_BK, false>(stA[slot], rA, lda_b, l_row0, k0, l_kend, tail, tid);
+        nt_load<TN, NT_BK, B_F32>(stB[slot], rB, ldb_b, l_col0, k0, l_kend, tail, tid);
+        if (++lk == l_nk) { lk = 0; if (++lt < range.end) open_tile(lt); }
+    };
+    auto store = [&](int slot, int buf) {
+        unsigned short* d = lds + buf * BUF;
+        nt_store<TM, NT_BK, false>(stA[slot], d, tid);
+        nt_store<TN, NT_BK, B_F32>(stB[slot], d + A_ELEMS, tid);
+    };
+
+    // ---- compute cursor
+    f32x16 acc[FM][FN];
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    };
+    zero_acc();
+    int ct = range.begin, ck = 0, c_nk = l_nk;
+    auto compute = [&](int buf) {
+        const unsigned short* sA = lds + buf * BUF;
+        const unsigned short* sB = sA + A_ELEMS;
+#pragma unroll
+        for (int kk = 0; kk < NT_BK / 16; ++kk) {
+            const int kofs = kk * 16 + (lane >> 5) * 8;
+            bf16x8 fa[FM], fb[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+                fa[i] = *(const bf16x8*)(sA + (wm * (FM * 32) + i * 32 + (lane & 31)) * NT_KP + kofs);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                fb[j] = *(const bf16x8*)(sB + (wn * (FN * 32) + j * 32 + (lane & 31)) * NT_KP + kofs);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    };
+    // after the last k-tile of a tile: write it out, start the next one
+    auto finish_step = [&]() {
+        if (++ck < c_nk) return;
+        const NtTile t = L.tiles[ct];
+        const NtProblem* pp = L.probs + t.prob;
+        const int M = pp->M, N = pp->N;
+        constexpr int CSZ = OUT_BF16 ? 2 : 4;
+        const nt_rsrc_t rC = nt_make_rsrc((const char*)pp->C + (long long)t.ks * pp->c_split_stride * CSZ,
+                                          ((long long)(M - 1) * pp->ldc + N) * CSZ);
+        const unsigned ldc_b = (unsigned)pp->ldc * CSZ;
+        const int row0 = t.tm * TM, col0 = t.tn * TN;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
+                    const int row = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4 + (e >> 2) * 8 + (e & 3);
+                    const unsigned vo = (row < M && col < N) ? (unsigned)row * ldc_b + (unsigned)col * CSZ : 0x80000000u;
+                    if constexpr (OUT_BF16)
+                        __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_bits(alpha * acc[i][j][e]), rC, (int)vo, 0, 0);
+                    else
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, alpha * acc[i][j][e]), rC, (int)vo, 0, 0);
+                }
+        zero_acc();
+        ck = 0;
+        if (++ct < range.end) c_nk = tile_nk(L.tiles[ct]);
+    };
+
+    // ---- the stream: step g multiplies LDS buffer g&1, moves step g+1 (register stage (g+1)&1)
+    // into the other buffer and refills that stage with step g+3
+    load_next(0);
+    store(0, 0);
+    __syncthreads();
+    if (total > 1) load_next(1);
+    if (total > 2) load_next(0);
+    for (int g = 0; g < total; g += 2) {
+        compute(0);
+        finish_step();
+        if (g + 1 < total) store(1, 1);
+        __syncthreads();
+        if (g + 3 < total) load_next(1);
+        if (g + 1 < total) {
+            compute(1);
+            finish_step();
+            if (g + 2 < total) store(0, 0);
+            __syncthreads();
+            if (g + 4 < total) load_next(0);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ dispatch
 typedef void (*nt_fn)(const NtLaunch);
-struct NtEntry { int shape, b_f32, out; nt_fn fn; int lds_bytes; };
+struct NtEntry { int shape, b_f32, out; nt_fn fn; nt_fn persistent; int lds_bytes; int minb; };
+
+template <int TM, int TN, int WM, int WN, int BK, bool BF32, int OUT, int MINB>
+constexpr nt_fn nt_persistent_fn() {
+    if constexpr (OUT == 2) return nullptr;
+    else return nt_gemm_persistent_kernel<TM, TN, WM, WN, BK, BF32, OUT, MINB>;
+}
 
 #define NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, bf32, out) \
-    { shape, bf32, out, nt_gemm_kernel<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>, 2 * (TM + TN) * (BK + 8) * 2 }
+    { shape, bf32, out, nt_gemm_kernel<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>, \
+      nt_persistent_fn<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>(), 2 * (TM + TN) * (BK + 8) * 2, MINB }
 // MINB / MINB_RMW: workgroups per CU the register allocation must allow (the read-modify-write
 // variant also holds the C tile in registers)
 #define NT_SHAPE(shape, TM, TN, WM, WN, BK, MINB, MINB_RMW)                                                   \
@@ -286,20 +443,27 @@ hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t str
     const int out = v.out_bf16 ? 1 : (L.beta != 0.0f ? 2 : 0);
     for (const NtEntry& e : kNt) {
         if (e.shape == v.shape && e.b_f32 == v.b_f32 && e.out == out) {
-            static thread_local const void* configured[128] = {nullptr};
+            const nt_fn fn = L.ranges ? e.persistent : e.fn;
+            if (fn == nullptr) return hipErrorInvalidValue;
+            static thread_local const void* configured[256] = {nullptr};
             bool done = false;
-            for (const void* c : configured) if (c == (const void*)e.fn) { done = true; break; }
+            for (const void* c : configured) if (c == (const void*)fn) { done = true; break; }
             if (!done) {
-                hipError_t er = hipFuncSetAttribute((const void*)e.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                hipError_t er = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                     e.lds_bytes);
                 if (er != hipSuccess) return er;
-                for (const void*& c : configured) if (c == nullptr) { c = (const void*)e.fn; break; }
+                for (const void*& c : configured) if (c == nullptr) { c = (const void*)fn; break; }
             }
-            hipLaunchKernelGGL(e.fn, dim3(L.n_tiles), dim3(NT_THREADS), e.lds_bytes, stream, L);
+            hipLaunchKernelGGL(fn, dim3(L.n_tiles), dim3(NT_THREADS), e.lds_bytes, stream, L);
             return hipGetLastError();
         }
     }
     return hipErrorInvalidValue;
+}
+
+int nt_wgs_per_cu(int shape) {
+    for (const NtEntry& e : kNt) if (e.shape == shape && e.out == 0) return e.minb;
+    return 1;
 }
 
 // ------------------------------------------------------------------ bf16 shadows of the bases
