@@ -28,7 +28,12 @@ struct NtStageH {
 struct FastStep {
     std::vector<ShadowBlock> shadows;  const ShadowBlock* d_shadows = nullptr;
     int max_rows = 0, max_r = 0;
-    NtStageH gv[2];      // P^T = V^T G^T   (index: dtype of G)
+    NtStageH gv[2];      // P^T = V^T G^T   (index: dtype of G), blocks the projection kernel cannot take
+    struct ProjGroup {   // bf16 gradients of one rank handled by the projection kernel
+        int r = 0, panel_rows = 128, variant = 0;
+        std::vector<ProjItem> items;  const ProjItem* d_items = nullptr;
+    };
+    std::vector<ProjGroup> projs;
     NtStageH utp;        // C = U^T P
     std::vector<AdamTBlock> adam;  const AdamTBlock* d_adam = nullptr;
     NtStageH ud;         // T = U D                      (blocks the fused kernel cannot take)

@@ -231,7 +231,13 @@ bool fast_step_eligible(const std::vector<BlockView>& blocks, int n_workers) {
 }
 
 void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_workers, Arena& ar) {
-    fs.shadows.clear(); fs.adam.clear(); fs.lifts.clear();
+    fs.shadows.clear(); fs.adam.clear(); fs.lifts.clear(); fs.projs.clear();
+    const bool use_proj_kernel = tune_int("TSR_TUNE_PROJ", 1, 0, 1) != 0;
+    const int proj_rows = tune_int("TSR_TUNE_PROJ_ROWS", 128, 64, 128) == 64 ? 64 : 128;
+    // 1 (measured best): two k-tiles in flight, two workgroups per CU; 0: four in flight, one per CU
+    const int proj_variant = tune_int("TSR_TUNE_PROJ_VARIANT", 1, 0, 1);
+    std::map<int, std::vector<int>> proj_block;
+    std::map<int, std::vector<long long>> proj_work;
     fs.max_rows = 0; fs.max_r = 0;
     const bool fused_lift = tune_int("TSR_TUNE_FUSED_LIFT", 1, 0, 1) != 0;
     const int lift_cus = tune_int("TSR_TUNE_LIFT_CUS", 256, 8, 4096);       // compute units of the target
@@ -253,8 +259,11 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
         const bool fits32 = (long long)(b.m + 128) * b.ldw * 4 < (1LL << 31) && (long long)(std::max(b.m, b.n) + 128) * ldr * 2 < (1LL << 31);
         const bool use_lift = fused_lift && lift_supports_rank(b.r) && fits32;
         bf* Vf = use_lift ? ar.take<bf>((size_t)cdiv(b.n, 32) * 32 * b.r) : nullptr;
-        fs.shadows.push_back(ShadowBlock{b.U, Ub, UTb, nullptr, b.m, b.r, ldr, ldm});
-        fs.shadows.push_back(ShadowBlock{b.V, Vb, VTb, Vf, b.n, b.r, ldr, ldn});
+        const bool use_proj = use_proj_kernel && b.g_dtype == TSR_BF16 && proj_supports_rank(b.r) &&
+                              (long long)b.r * (b.n + 16) * 2 < (1LL << 31);
+        bf* VTf = use_proj ? ar.take<bf>((size_t)b.r * ((b.n + 15) / 16 * 16)) : nullptr;
+        fs.shadows.push_back(ShadowBlock{b.U, Ub, UTb, nullptr, nullptr, b.m, b.r, ldr, ldm});
+        fs.shadows.push_back(ShadowBlock{b.V, Vb, VTb, Vf, VTf, b.n, b.r, ldr, ldn});
         fs.max_rows = std::max(fs.max_rows, std::max(b.m, b.n));
         fs.max_r = std::max(fs.max_r, b.r);
         r_max = std::max(r_max, b.r);
@@ -262,7 +271,18 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
         for (int w = 0; w < n_workers; ++w) {
             bf* PT = ar.take<bf>((size_t)b.r * ldm);
             const char* Gw = b.G ? (const char*)b.G + (size_t)w * b.g_stride * esz : nullptr;
-            gv[b.g_dtype].push_back(NtLogical{VTb, Gw, PT, ldn, b.ldg, ldm, b.r, b.m, b.n, bi, -1});
+            if (use_proj) {
+                FastStep::ProjGroup* pg = nullptr;
+                for (auto& g : fs.projs) if (g.r == b.r) pg = &g;
+                if (!pg) { fs.projs.emplace_back(); pg = &fs.projs.back(); pg->r = b.r; pg->panel_rows = proj_rows; pg->variant = (proj_rows == 128) ? proj_variant : 0; }
+                for (int row0 = 0; row0 < b.m; row0 += proj_rows) {
+                    pg->items.push_back(ProjItem{Gw, VTf, PT, b.ldg, ldm, b.m, b.n, row0});
+                    proj_block[b.r].push_back(bi);
+                    proj_work[b.r].push_back(b.n + 64);
+                }
+            } else {
+                gv[b.g_dtype].push_back(NtLogical{VTb, Gw, PT, ldn, b.ldg, ldm, b.r, b.m, b.n, bi, -1});
+            }
             utp.push_back(NtLogical{UTb, PT, b.C, ldm, ldm, b.r, b.r, b.r, b.m, bi, bi});
         }
         bf* DTf = use_lift ? ar.take<bf>((size_t)b.r * b.r) : nullptr;
@@ -318,6 +338,17 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
             g.ranges[wg].end = (int)g.tiles.size();
         }
     }
+    for (auto& g : fs.projs) {
+        // long contractions first: the hardware hands out panels in this order
+        std::vector<int> idx(g.items.size());
+        std::iota(idx.begin(), idx.end(), 0);
+        std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return g.items[a].n > g.items[b].n; });
+        std::vector<ProjItem> items; std::vector<int> blk; std::vector<long long> wk;
+        for (int i : idx) { items.push_back(g.items[i]); blk.push_back(proj_block[g.r][i]); wk.push_back(proj_work[g.r][i]); }
+        g.items.swap(items);
+        ProjItem idle{};
+        interleave_xcd(g.items, blk, wk, nb, idle);
+    }
     const int s1_shape = tune("TSR_TUNE_GV", (r_max > 64) ? NT_128x128 : NT_64x256);
     // persistent launches pay off for the many short tiles of U^T P, not for the G V stage
     const bool gv_persist = tune_int("TSR_TUNE_GV_PERSIST", 0, 0, 1) != 0;
@@ -334,6 +365,7 @@ void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {
     fs.d_shadows = up.put(fs.shadows, ar);
     fs.d_adam = up.put(fs.adam, ar);
     for (int d = 0; d < 2; ++d) upload_nt_stage(fs.gv[d], ar, up);
+    for (auto& g : fs.projs) g.d_items = up.put(g.items, ar);
     upload_nt_stage(fs.utp, ar, up);
     upload_nt_stage(fs.ud, ar, up);
     upload_nt_stage(fs.tvt, ar, up);
@@ -351,6 +383,10 @@ int run_fast_step(FastStep& fs, int n_workers, const AdamScalars& s, float lr, f
     }
     TSR_TRY(run_nt_stage(fs.gv[TSR_F32], 1.0f, 0.0f, cx, TSR_PROF_GV));
     TSR_TRY(run_nt_stage(fs.gv[TSR_BF16], 1.0f, 0.0f, cx, TSR_PROF_GV));
+    for (const auto& g : fs.projs) {
+        Timed timed(cx, TSR_PROF_GV);
+        TSR_HIP(launch_proj(g.d_items, (int)g.items.size(), g.r, g.panel_rows + g.variant, cx.s));
+    }
     TSR_TRY(run_nt_stage(fs.utp, 1.0f / (float)n_workers, 0.0f, cx, TSR_PROF_UTP));
     {
         Timed timed(cx, TSR_PROF_ADAM);

@@ -64,10 +64,26 @@ int nt_wgs_per_cu(int shape);   // resident workgroups per CU the kernel of this
 // r % 16 == 0) is the same matrix in MFMA-fragment order for the fused lift kernel: rows in
 // groups of 32 (zero rows up to the next multiple of 32), and for group g and 16-wide k step s
 // one contiguous 1 KiB record holding, for lane = 32 h + l, the 8 values X[32 g + l][16 s + 8 h ..].
+// XTFb (optional, r % 32 == 0) is X^T in fragment order for the projection kernel: for the
+// group g of 32 columns of X and the 16-wide step s over its rows one contiguous 1 KiB record
+// holding, for lane = 32 h + l, the 8 values X[16 s + 8 h ..][32 g + l] (zeros beyond the last row).
 struct ShadowBlock {
-    const float* X; void* Xb; void* XTb; void* XFb;
+    const float* X; void* Xb; void* XTb; void* XFb; void* XTFb;
     int rows, r; long long ldx, ldt;
 };
+// Projection P^T = V^T G^T for one 128- or 64-row panel of a bf16 gradient per workgroup (r = 128
+// or 256): the panel's accumulators (r x 128) stay in registers over the whole contraction, G goes
+// through LDS, V^T comes straight from its fragment-order copy.  G == nullptr: idle workgroup.
+struct ProjItem {
+    const void* G;       // bf16 m x n, leading dimension ldg (16-byte aligned rows, n % 8 == 0)
+    const void* VTf;     // ShadowBlock::XTFb of V
+    void* PT;            // bf16 r x m, leading dimension ldp
+    long long ldg, ldp;
+    int m, n, row0;
+};
+bool proj_supports_rank(int r);
+hipError_t launch_proj(const ProjItem* items_dev, int n_items, int r, int panel_rows, hipStream_t stream);   // panel_rows: 128 or 64
+
 hipError_t launch_shadows(const ShadowBlock* table_dev, int blocks, int max_rows, int max_r, hipStream_t stream);
 
 }  // namespace tsr

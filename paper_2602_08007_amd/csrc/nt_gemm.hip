@@ -410,6 +410,124 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
     }
 }
 
+// ------------------------------------------------------------------ projection kernel
+// RG: groups of 32 rows of V^T (r / 32); wave w owns groups w RG/4 .. and all TN gradient rows.
+// DEPTH: k-tiles in flight in registers (gradient tile stages and V^T fragment slots).  A
+// workgroup streams its own rows of G from HBM, so the loop runs at memory latency / DEPTH per
+// k-tile until DEPTH k-tiles of MFMAs cover that latency.
+template <int RG, int TN, int DEPTH, int MINB>
+__global__ __launch_bounds__(NT_THREADS, MINB) void proj_kernel(const ProjItem* items) {
+    constexpr int BK = 64, KP = BK + 8;
+    constexpr int FM = RG / 4, FN = TN / 32;
+    static_assert(RG % 4 == 0, "r must be a multiple of 128");
+    static_assert(DEPTH == 2 || DEPTH == 4, "ring sizes the loop is unrolled for");
+    __shared__ __attribute__((aligned(16))) unsigned short lds[2 * TN * KP];
+    const ProjItem it = items[blockIdx.x];
+    if (it.G == nullptr) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int m = it.m, n = it.n, row0 = it.row0;
+    const int nsteps = (n + 15) / 16, nk = (n + BK - 1) / BK;
+    const nt_rsrc_t rG = nt_make_rsrc(it.G, ((long long)(m - 1) * it.ldg + ((n + 7) & ~7)) * 2);
+    const nt_rsrc_t rV = nt_make_rsrc(it.VTf, (long long)RG * nsteps * 1024);
+    const unsigned ldg_b = (unsigned)it.ldg * 2u;
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    u32x4 af[DEPTH][FM][BK / 16];                            // V^T fragments of DEPTH k-tiles
+    auto load_a = [&](int slot, int kt) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                const int s = kt * (BK / 16) + kk;           // steps beyond the last read as zero
+                const unsigned voff = (s < nsteps) ? (unsigned)(((wave * FM + i) * nsteps + s) * 64 + lane) * 16u : 0x80000000u;
+                af[slot][i][kk] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, (int)voff, 0, 0));
+            }
+    };
+    NtStage<TN * BK / 8 / NT_THREADS, false> st[DEPTH];
+    auto load_g = [&](int slot, int kt) {
+        const int k0 = kt * BK;
+        nt_load<TN, BK, false>(st[slot], rG, ldg_b, row0, k0, n, k0 + BK > n, tid);
+    };
+    auto store_g = [&](int slot, int buf) { nt_store<TN, BK, false>(st[slot], lds + buf * (TN * KP), tid); };
+    auto compute = [&](int buf, int slot) {
+        const unsigned short* sB = lds + buf * (TN * KP);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int kofs = kk * 16 + h * 8;
+            bf16x8 fb[FN];
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8*)(sB + (j * 32 + l32) * KP + kofs);
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                const bf16x8 fa = __builtin_bit_cast(bf16x8, af[slot][i][kk]);
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+
+    // k-tile kt is multiplied from LDS buffer kt&1 with the fragments in af[kt % DEPTH]; gradient
+    // tiles kt+1 .. kt+DEPTH sit in the register stages (tile t in stage t % DEPTH); fragments
+    // and stages are refilled in place, DEPTH k-tiles ahead
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+        if (d < nk) { load_g(d, d); load_a(d, d); }
+    store_g(0, 0);
+    __syncthreads();
+    if (DEPTH < nk) load_g(0, DEPTH);
+    for (int kt = 0; kt < nk; kt += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            const int t = kt + u;                            // uniform; the whole group leaves together
+            if (t < nk) {
+                compute(u & 1, u);
+                if (t + DEPTH < nk) load_a(u, t + DEPTH);
+                if (t + 1 < nk) store_g((u + 1) % DEPTH, (u + 1) & 1);
+                __syncthreads();
+                if (t + 1 + DEPTH < nk) load_g((u + 1) % DEPTH, t + 1 + DEPTH);
+            }
+        }
+    }
+
+    // P^T[ri][row]: lane holds gradient row (lane & 31) of each 32-row group, registers run over ri
+    const nt_rsrc_t rP = nt_make_rsrc(it.PT, ((long long)(RG * 32 - 1) * it.ldp + m) * 2);
+    const unsigned ldp_b = (unsigned)it.ldp * 2u;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int row = row0 + j * 32 + l32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int ri = (wave * FM + i) * 32 + (e >> 2) * 8 + 4 * h + (e & 3);
+                const unsigned vo = (row < m) ? (unsigned)ri * ldp_b + (unsigned)row * 2u : 0x80000000u;
+                __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_bits(acc[i][j][e]), rP, (int)vo, 0, 0);
+            }
+        }
+}
+
+bool proj_supports_rank(int r) { return r == 128 || r == 256; }
+
+hipError_t launch_proj(const ProjItem* items_dev, int n_items, int r, int panel_rows, hipStream_t stream) {
+    if (n_items <= 0) return hipSuccess;
+    if (r == 256 && panel_rows == 128) hipLaunchKernelGGL((proj_kernel<8, 128, 4, 1>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    else if (r == 256 && panel_rows == 129) hipLaunchKernelGGL((proj_kernel<8, 128, 2, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    else if (r == 256 && panel_rows == 64) hipLaunchKernelGGL((proj_kernel<8, 64, 4, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    else if (r == 128 && panel_rows >= 128) hipLaunchKernelGGL((proj_kernel<4, 128, 4, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    else if (r == 128 && panel_rows == 64) hipLaunchKernelGGL((proj_kernel<4, 64, 4, 3>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ dispatch
 typedef void (*nt_fn)(const NtLaunch);
 struct NtEntry { int shape, b_f32, out; nt_fn fn; nt_fn persistent; int lds_bytes; int minb; };
@@ -479,7 +597,9 @@ __global__ __launch_bounds__(256) void shadow_kernel(const ShadowBlock* table) {
     unsigned short* Xb = (unsigned short*)b.Xb;
     unsigned short* XTb = (unsigned short*)b.XTb;
     unsigned short* XFb = (unsigned short*)b.XFb;
+    unsigned short* XTFb = (unsigned short*)b.XTFb;
     const int rows32 = (rows + 31) / 32 * 32, ksteps = r / 16;
+    const int rows16 = (rows + 15) / 16 * 16, nsteps = rows16 / 16;
     for (int i = ty; i < 64; i += 4) {
         const int row = row0 + i, c = c0 + tx;
         const float v = (row < rows && c < r) ? b.X[(long long)row * r + c] : 0.0f;
@@ -488,6 +608,8 @@ __global__ __launch_bounds__(256) void shadow_kernel(const ShadowBlock* table) {
         if (row < rows && c < (int)b.ldx) Xb[(long long)row * b.ldx + c] = h;
         if (XFb && row < rows32 && c < r)
             XFb[(((long long)(row / 32) * ksteps + c / 16) * 64 + ((c % 16) / 8) * 32 + row % 32) * 8 + c % 8] = h;
+        if (XTFb && row < rows16 && c < r)
+            XTFb[(((long long)(c / 32) * nsteps + row / 16) * 64 + ((row % 16) / 8) * 32 + c % 32) * 8 + row % 8] = h;
     }
     __syncthreads();
     for (int i = ty; i < 64; i += 4) {
