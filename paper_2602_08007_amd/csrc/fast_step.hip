@@ -25,10 +25,14 @@ struct NtLogical {
 // Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2:
 // give every block to one XCD (greedy by work) and interleave the per-XCD tile lists, so the
 // tiles that re-read a block's operands hit the L2 that already holds them.
-// Tuning knobs read from the environment at plan creation (integers): TSR_TUNE_GV, TSR_TUNE_UTP,
-// TSR_TUNE_UD, TSR_TUNE_TVT select the NtShape of a stage, TSR_TUNE_XCD=0 keeps the natural
-// tile order, TSR_TUNE_FUSED_LIFT=0 uses the two-GEMM lift, TSR_TUNE_LIFT_CHUNK sets the number
-// of column tiles one workgroup of the fused lift streams.  Unset = the built-in choice.
+// Tuning knobs read from the environment at plan creation (integers; unset = the built-in,
+// measured-best choice): TSR_TUNE_GV / UTP / UD / TVT select the NtShape of a stage,
+// TSR_TUNE_GV_PERSIST / UTP_PERSIST the persistent launch of that stage, TSR_TUNE_UTP_TILES the
+// tile count U^T P is split towards, TSR_TUNE_XCD=0 keeps the natural tile order,
+// TSR_TUNE_PROJ=0 routes G V through the NT family instead of the projection kernel
+// (TSR_TUNE_PROJ_ROWS, TSR_TUNE_PROJ_VARIANT: its panel height and pipeline depth),
+// TSR_TUNE_FUSED_LIFT=0 uses the two-GEMM lift, TSR_TUNE_LIFT_MODE / LIFT_SETUP / LIFT_CUS shape
+// the fused lift kernel's items and work lists.
 int tune_int(const char* name, int dflt, int lo, int hi) {
     const char* v = std::getenv(name);
     if (!v || !*v) return dflt;
