@@ -716,8 +716,12 @@ __global__ __launch_bounds__(SMALL_THREADS) void jacobi_kernel(const JacobiBlock
                     double e_i = s_e[m - 1], d_i = s_d[m - 1], d_ip1 = s_d[m];
                     bool under = false;
                     for (int i = m - 1; i >= l; --i) {
-                        const double e_n = (i > l) ? s_e[i - 1] : 0.0;     // next step's operands
-                        const double d_n = (i > l) ? s_d[i - 1] : 0.0;
+                        // next step's operands, fetched without a branch (the values read at the
+                        // last step, i == l, are not used) so that the wait for them can sit
+                        // at their first use, one step later
+                        const int ip = max(i - 1, 0);
+                        const double e_n = s_e[ip];
+                        const double d_n = s_d[ip];
                         const double f = sn * e_i;
                         const double bb = cs * e_i;
                         const double h2 = f * f + g * g;
