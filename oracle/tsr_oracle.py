@@ -152,6 +152,38 @@ def refresh_rsvd(G, Omega, r, p, q, return_q=False):
     return (U, V, S, Q) if return_q else (U, V, S)
 
 
+def refresh_rsvd_workers(G_workers, Omega, r, p, q):
+    """Refresh branch of Algorithm 1 with N workers (Section 3.5): every worker i runs the sketch
+    chain on its own gradient with the shared Omega (Y_i = G_i Omega, Q_i = orth(Y_i), q rounds of
+    Yrow = G_i^T Q_i, Qrow = orth(Yrow), Y_i = G_i Qrow, Q_i = orth(Y_i)) and forms B_i = Q_i^T G_i;
+    the sketches are averaged, Bbar = AR(B_i), Qbar = AR(Q_i); Bbar = Ut S Vt^T;
+    U = Qbar Ut[:, :r], V = Vt[:, :r].  U is orthonormal only when the Q_i coincide.
+    Returns (U m x r, V n x r, sigma k, Qbar m x k, Bbar k x n)."""
+    Omega = f64(Omega)
+    n, k = Omega.shape
+    assert k == r + p
+    Qs, Bs = [], []
+    for G in G_workers:
+        G = f64(G)
+        m = G.shape[0]
+        assert G.shape[1] == n and k <= min(m, n)
+        Q, _ = householder_qr(matmul(G, Omega))
+        for _ in range(q):
+            Qrow, _ = householder_qr(matmul(G, Q, ta=True))
+            Q, _ = householder_qr(matmul(G, Qrow))
+        Qs.append(Q)
+        Bs.append(matmul(Q, G, ta=True))
+    N = len(Qs)
+    Qbar = np.zeros_like(Qs[0]); Bbar = np.zeros_like(Bs[0])
+    for Q, B in zip(Qs, Bs):
+        Qbar += Q; Bbar += B
+    Qbar /= N; Bbar /= N
+    Ut, S, Vt, _ = jacobi_svd(Bbar)
+    U = matmul(Qbar, np.ascontiguousarray(Ut[:, :r]))
+    V = np.ascontiguousarray(Vt[:, :r])
+    return U, V, S, Qbar, Bbar
+
+
 def tsr_adam_step(W, G_workers, U, V, M, Vm, t, lr, wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0):
     """One non-refresh iteration of Algorithm 1 for one matrix block: project every
     worker's gradient, average the cores, Adam on the core, lift and apply.

@@ -6,6 +6,7 @@ routines on tiny inputs, or numbers printed in the paper.
 """
 import numpy as np
 import pytest
+import torch
 
 import synth_inputs as si
 from oracle import tsr_oracle as orc
@@ -347,3 +348,59 @@ def test_rsvd_returns_final_q():
     # U lies in range(Q); S are the singular values of Q^T G
     assert rel(Q @ (Q.T @ U), U) < 1e-12
     assert np.allclose(S, np.linalg.svd(Q.T @ G, compute_uv=False), rtol=1e-11)
+
+
+# ------------------------------------------------------------------ multi-worker refresh (Algorithm 1, N > 1)
+def _sign_fix(U, V):
+    s = np.sign(V[np.abs(V).argmax(axis=0), np.arange(V.shape[1])])
+    return U * s, V * s
+
+
+def test_workers_refresh_single_worker_is_the_plain_refresh():
+    m, n, r, p, q = 40, 30, 4, 3, 1
+    G64, _, _ = si.exact_lowrank(m, n, r, 901)
+    G = orc.f64(G64) + 1e-3 * orc.f64(si.normal((m, n), 902, dtype=torch.float64))
+    Om = si.omega(n, r + p, 903)
+    U1, V1, S1 = orc.refresh_rsvd(G, Om, r, p, q)
+    U2, V2, S2, Qbar, Bbar = orc.refresh_rsvd_workers([G], Om, r, p, q)
+    assert np.allclose(S1, S2, atol=1e-12)
+    U1, V1 = _sign_fix(U1, V1); U2, V2 = _sign_fix(U2, V2)
+    assert np.allclose(U1, U2, atol=1e-10) and np.allclose(V1, V2, atol=1e-10)
+    assert np.allclose(Qbar.T @ Qbar, np.eye(r + p), atol=1e-12)
+
+
+def test_workers_refresh_identical_workers_change_nothing():
+    # averaging N copies of the same sketches is the identity: the result equals one worker's
+    m, n, r, p, q = 36, 44, 5, 2, 1
+    G64, _, _ = si.exact_lowrank(m, n, r, 911)
+    G = orc.f64(G64) + 1e-3 * orc.f64(si.normal((m, n), 912, dtype=torch.float64))
+    Om = si.omega(n, r + p, 913)
+    U1, V1, S1, _, _ = orc.refresh_rsvd_workers([G], Om, r, p, q)
+    U3, V3, S3, _, _ = orc.refresh_rsvd_workers([G, G.copy(), G.copy()], Om, r, p, q)
+    assert np.allclose(S1, S3, atol=1e-12)
+    U1, V1 = _sign_fix(U1, V1); U3, V3 = _sign_fix(U3, V3)
+    assert np.allclose(U1, U3, atol=1e-10) and np.allclose(V1, V3, atol=1e-10)
+
+
+def test_workers_refresh_structure_of_the_averaged_sketches():
+    # what the definition fixes for N > 1: Bbar and Qbar are the plain means of the workers'
+    # sketches (recomputed here from each worker's own refresh), sigma are Bbar's singular values
+    # (numpy), V is orthonormal, U = Qbar Ut_r so U^T U = Ut_r^T (Qbar^T Qbar) Ut_r, and
+    # Qbar^T Qbar <= I (a mean of orthonormal bases is a contraction).
+    m, n, r, p, q, N = 48, 40, 4, 4, 1, 3
+    G64, _, _ = si.exact_lowrank(m, n, r, 921)
+    Gs = [orc.f64(G64) + 5e-2 * orc.f64(si.normal((m, n), 922 + w, dtype=torch.float64)) for w in range(N)]
+    Om = si.omega(n, r + p, 929)
+    U, V, S, Qbar, Bbar = orc.refresh_rsvd_workers(Gs, Om, r, p, q)
+    Qi = [orc.refresh_rsvd(G, Om, r, p, q, return_q=True)[3] for G in Gs]
+    assert np.allclose(Qbar, sum(Qi) / N, atol=1e-12)
+    assert np.allclose(Bbar, sum(Q.T @ G for Q, G in zip(Qi, Gs)) / N, atol=1e-10)
+    assert np.allclose(S, np.linalg.svd(Bbar, compute_uv=False), atol=1e-10)
+    assert np.allclose(V.T @ V, np.eye(r), atol=1e-10)
+    # U Sigma_r V^T is the best rank-r approximation of Bbar lifted by Qbar
+    Ub, Sb, Vbt = np.linalg.svd(Bbar, full_matrices=False)
+    lifted = Qbar @ (Ub[:, :r] * Sb[:r]) @ Vbt[:r]
+    assert np.allclose((U * S[:r]) @ V.T, lifted, atol=1e-9)
+    gram = Qbar.T @ Qbar
+    assert np.linalg.eigvalsh(gram).max() <= 1.0 + 1e-12
+    assert np.linalg.norm(U.T @ U - np.eye(r)) > 1e-6          # the workers differ: U is not orthonormal
