@@ -158,19 +158,29 @@ def refresh_rsvd_workers(G_workers, Omega, r, p, q):
     Yrow = G_i^T Q_i, Qrow = orth(Yrow), Y_i = G_i Qrow, Q_i = orth(Y_i)) and forms B_i = Q_i^T G_i;
     the sketches are averaged, Bbar = AR(B_i), Qbar = AR(Q_i); Bbar = Ut S Vt^T;
     U = Qbar Ut[:, :r], V = Vt[:, :r].  U is orthonormal only when the Q_i coincide.
+    orth is the thin QR factor with diag(R) > 0 (see `orth` below).
     Returns (U m x r, V n x r, sigma k, Qbar m x k, Bbar k x n)."""
     Omega = f64(Omega)
     n, k = Omega.shape
     assert k == r + p
+
+    def orth(Y):
+        # Averaging the workers' Q_i only means something if every worker orients the columns of
+        # its basis the same way: orth is the unique thin QR factor, the one whose R has a
+        # positive diagonal (the Householder routine leaves the signs of diag(R) arbitrary).
+        Q, R = householder_qr(Y)
+        s = np.where(np.diag(R) < 0.0, -1.0, 1.0)
+        return Q * s
+
     Qs, Bs = [], []
     for G in G_workers:
         G = f64(G)
         m = G.shape[0]
         assert G.shape[1] == n and k <= min(m, n)
-        Q, _ = householder_qr(matmul(G, Omega))
+        Q = orth(matmul(G, Omega))
         for _ in range(q):
-            Qrow, _ = householder_qr(matmul(G, Q, ta=True))
-            Q, _ = householder_qr(matmul(G, Qrow))
+            Qrow = orth(matmul(G, Q, ta=True))
+            Q = orth(matmul(G, Qrow))
         Qs.append(Q)
         Bs.append(matmul(Q, G, ta=True))
     N = len(Qs)
