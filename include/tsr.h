@@ -147,6 +147,20 @@ int tsr_refresh_rsvd(const void* G, int g_dtype, int m, int n, long long ldg,
                      float* U, float* V, float* sigma,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* Refresh with N workers on one GPU (refresh branch of Algorithm 1, Section 3.5): every worker
+ * runs the sketch chain above on its own gradient G_i with the shared Omega and forms
+ * B_i = Q_i^T G_i; the sketches are averaged in device memory (the stand-in for the two
+ * all-reduces), Bbar = mean B_i, Qbar = mean Q_i; Bbar = Ut S Vt^T; U = Qbar Ut[:, :r],
+ * V = Vt[:, :r].  V is orthonormal; U is orthonormal only as far as the workers' Q_i agree.
+ * G holds the n_workers gradients g_stride elements apart (g_stride >= (m-1) ldg + n).
+ * The communicated sketch payload this stands in for is k (m + n) values per worker, k = r + p.
+ * n_workers = 1 is tsr_refresh_rsvd.  Workspace: tsr_refresh_workers_workspace_bytes. */
+size_t tsr_refresh_workers_workspace_bytes(int m, int n, int r, int p, int n_workers);
+int tsr_refresh_rsvd_workers(const void* G, int g_dtype, int m, int n, long long ldg, long long g_stride,
+                             int n_workers, const float* Omega, int r, int p, int q,
+                             float* U, float* V, float* sigma,
+                             void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------- batched all-layers calls
  * A plan holds, in caller-provided device workspace, the grouped-launch tables for a fixed
  * list of blocks, so that every phase of the step (and of the refresh) is a handful of

@@ -16,7 +16,7 @@ __all__ = [
     "tsr_status_string", "tsr_device_count",
     "tsr_stream_scale", "tsr_project_workspace_bytes", "tsr_project_core", "tsr_core_average", "tsr_adam_core", "tsr_sgd_core",
     "tsr_backproject_workspace_bytes", "tsr_backproject_apply",
-    "tsr_refresh_workspace_bytes", "tsr_refresh_rsvd",
+    "tsr_refresh_workspace_bytes", "tsr_refresh_rsvd", "tsr_refresh_workers_workspace_bytes", "tsr_refresh_rsvd_workers",
     "tsr_matrix_desc", "tsr_hyper", "Plan", "workspace",
 ]
 
@@ -63,6 +63,9 @@ _lift_ws = _sig("tsr_backproject_workspace_bytes", _sz, _i, _i, _i)
 _lift = _sig("tsr_backproject_apply", _i, _vp, _i, _i, _ll, _vp, _vp, _vp, _i, _f, _f, _f, _i, _vp, _sz, _vp)
 _refresh_ws = _sig("tsr_refresh_workspace_bytes", _sz, _i, _i, _i, _i)
 _refresh = _sig("tsr_refresh_rsvd", _i, _vp, _i, _i, _i, _ll, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp)
+_refresh_workers_ws = _sig("tsr_refresh_workers_workspace_bytes", _sz, _i, _i, _i, _i, _i)
+_refresh_workers = _sig("tsr_refresh_rsvd_workers", _i, _vp, _i, _i, _i, _ll, _ll, _i, _vp, _i, _i, _i, _vp, _vp, _vp, _vp,
+                        _sz, _vp)
 _plan_ws = _sig("tsr_plan_workspace_bytes", _sz, ctypes.POINTER(tsr_matrix_desc), _i, _i, _i, _i, _i)
 _bases_changed = _sig("tsr_plan_bases_changed", _i, _vp)
 _kernel_path = _sig("tsr_plan_kernel_path", _i, _vp)
@@ -203,6 +206,25 @@ def tsr_refresh_rsvd(G, Omega, r, p, q, U, V, sigma=None, ws=None, stream=None):
         ws = workspace(tsr_refresh_workspace_bytes(m, n, r, p), G.device)
     _check(_refresh(_ptr(G), _gdtype(G), m, n, _ld(G), _ptr(Omega), r, p, q, _ptr(U), _ptr(V), _ptr(sigma), _ptr(ws),
                     ws.numel(), _stream(stream)))
+    return U, V
+
+
+def tsr_refresh_workers_workspace_bytes(m: int, n: int, r: int, p: int, n_workers: int) -> int:
+    return int(_refresh_workers_ws(m, n, r, p, n_workers))
+
+
+def tsr_refresh_rsvd_workers(G, Omega, r, p, q, U, V, sigma=None, ws=None, stream=None):
+    """G: the workers' gradients stacked as [workers, m, n] (contiguous)."""
+    if G.dim() != 3 or not G.is_contiguous():
+        raise ValueError("G must be a contiguous [workers, m, n] tensor")
+    K, m, n = G.shape
+    _f32c(Omega, U, V, sigma)
+    if tuple(Omega.shape) != (n, r + p):
+        raise ValueError("Omega must be n x (r+p)")
+    if ws is None:
+        ws = workspace(tsr_refresh_workers_workspace_bytes(m, n, r, p, K), G.device)
+    _check(_refresh_workers(_ptr(G), _gdtype(G), m, n, n, m * n, K, _ptr(Omega), r, p, q, _ptr(U), _ptr(V), _ptr(sigma),
+                            _ptr(ws), ws.numel(), _stream(stream)))
     return U, V
 
 

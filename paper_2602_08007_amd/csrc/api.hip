@@ -328,7 +328,8 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
     build_stage(rp.vout, variant(0, 0, 0, 3, 3), vo, ar, 1);
 }
 
-int run_refresh(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
+// Sketch chain of one worker: leaves the final Q in Y and B^T = G^T Q in Z.
+int run_refresh_front(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.sketch[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     TSR_TRY(run_orth(rp.orthY, grouped, cx));
     for (int it = 0; it < q; ++it) {
@@ -337,8 +338,12 @@ int run_refresh(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
         for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
         TSR_TRY(run_orth(rp.orthY, grouped, cx));
     }
-    // B^T = G^T Q = Q_B R ; SVD of R ; U = Q X_r ; V = Q_B Gacc_r^T
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
+    return TSR_OK;
+}
+
+// From Q (in Y) and B^T (in Z):  B^T = Q_B R ; SVD of R ; U = Q X_r ; V = Q_B Gacc_r^T
+int run_refresh_back(const RefreshProgram& rp, bool grouped, Ctx& cx) {
     TSR_TRY(run_orth(rp.orthZ, grouped, cx));
     {
         Timed timed(cx, TSR_PROF_JACOBI);
@@ -348,6 +353,11 @@ int run_refresh(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
     }
     TSR_TRY(run_stage(rp.uout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
     return run_stage(rp.vout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM);
+}
+
+int run_refresh(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
+    TSR_TRY(run_refresh_front(rp, grouped, q, cx));
+    return run_refresh_back(rp, grouped, cx);
 }
 
 int check_refresh_shape(int m, int n, int r, int p) {
@@ -542,6 +552,55 @@ int tsr_refresh_rsvd(const void* G, int g_dtype, int m, int n, long long ldg, co
     build_refresh(rp, v, oms, p, sigs, ar);
     Ctx cx{(hipStream_t)stream, nullptr};
     return run_refresh(rp, false, q, cx);
+}
+
+size_t tsr_refresh_workers_workspace_bytes(int m, int n, int r, int p, int n_workers) {
+    if (check_refresh_shape(m, n, r, p) != TSR_OK || n_workers <= 0) return 0;
+    Arena ar(nullptr);
+    const size_t k = (size_t)r + p;
+    (void)ar.take<float>((size_t)n_workers * m * k);
+    (void)ar.take<float>((size_t)n_workers * n * k);
+    return ar.used() + tsr_refresh_workspace_bytes(m, n, r, p);
+}
+
+int tsr_refresh_rsvd_workers(const void* G, int g_dtype, int m, int n, long long ldg, long long g_stride,
+                             int n_workers, const float* Omega, int r, int p, int q, float* U, float* V,
+                             float* sigma, void* ws, size_t ws_bytes, void* stream) {
+    TSR_TRY(check_refresh_shape(m, n, r, p));
+    TSR_TRY(check_dtype(g_dtype));
+    if (q < 0 || n_workers <= 0) return TSR_INVALID_ARG;
+    if (!G || !Omega || !U || !V || !ws) return TSR_INVALID_ARG;
+    if (ldg < n) return TSR_BAD_SHAPE;
+    if (n_workers > 1 && g_stride < (long long)(m - 1) * ldg + n) return TSR_BAD_SHAPE;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_refresh_workers_workspace_bytes(m, n, r, p, n_workers)) return TSR_WORKSPACE_TOO_SMALL;
+    const size_t k = (size_t)r + p;
+    const size_t esz = (g_dtype == TSR_BF16) ? 2 : 4;
+    Arena ar(ws);
+    float* Qs = ar.take<float>((size_t)n_workers * m * k);     // the workers' Q_i, stacked
+    float* Bs = ar.take<float>((size_t)n_workers * n * k);     // the workers' B_i^T, stacked
+    const size_t mark = ar.used();
+    Ctx cx{(hipStream_t)stream, nullptr};
+    const float* oms[1] = {Omega};
+    float* sigs[1] = {sigma};
+    RefreshProgram rp;
+    for (int w = 0; w < n_workers; ++w) {
+        // the same buffers for every worker: only the gradient pointer differs
+        std::vector<BlockView> v;
+        one_block_view(v, (const char*)G + (size_t)w * g_stride * esz, g_dtype, m, n, r, ldg, nullptr, n, U, V, nullptr,
+                       nullptr);
+        Arena sub(ws);
+        sub.off = mark;
+        build_refresh(rp, v, oms, p, sigs, sub);
+        TSR_TRY(run_refresh_front(rp, false, q, cx));
+        const RefreshBlock& b = rp.blocks[0];
+        TSR_HIP(hipMemcpyAsync(Qs + (size_t)w * m * k, b.Y, (size_t)m * k * sizeof(float), hipMemcpyDeviceToDevice, cx.s));
+        TSR_HIP(hipMemcpyAsync(Bs + (size_t)w * n * k, b.Z, (size_t)n * k * sizeof(float), hipMemcpyDeviceToDevice, cx.s));
+    }
+    const RefreshBlock& b = rp.blocks[0];
+    TSR_HIP(launch_average(Qs, n_workers, (long long)m * (long long)k, b.Y, cx.s));      // Qbar
+    TSR_HIP(launch_average(Bs, n_workers, (long long)n * (long long)k, b.Z, cx.s));      // Bbar^T
+    return run_refresh_back(rp, false, cx);
 }
 
 // ---------------------------------------------------------------- plan

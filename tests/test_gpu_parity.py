@@ -243,6 +243,42 @@ def test_refresh_bf16_gradient(tsr):
     assert rel_fro(sigma, S_ref) < TOL_F32
 
 
+# ------------------------------------------------------------------ refresh with several workers
+def _sign_fix(U, V):
+    U, V = orc.f64(U).copy(), orc.f64(V).copy()
+    s = np.sign(V[np.abs(V).argmax(axis=0), np.arange(V.shape[1])])
+    return U * s, V * s
+
+
+@pytest.mark.parametrize("workers,g_dtype,q", [(1, torch.float32, 1), (3, torch.float32, 1), (4, torch.bfloat16, 0),
+                                               (2, torch.float32, 2)])
+def test_refresh_workers_matches_oracle(tsr, workers, g_dtype, q):
+    # shared well-separated signal (singular values 2 .. 1), independent noise per worker: the
+    # averaged sketches, hence sigma, V and the (non-orthonormal) U = Qbar Ut_r, are well conditioned
+    m, n, r, p = 300, 260, 24, 8
+    G64, _, _ = si.exact_lowrank(m, n, r, si.stream_key(801, workers))
+    Gs = torch.stack([(G64 + 2e-2 * si.normal((m, n), si.stream_key(802, w), dtype=torch.float64)).float().to(g_dtype)
+                      for w in range(workers)])
+    Om = si.omega(n, r + p, si.stream_key(803, workers))
+    U_ref, V_ref, S_ref, Qbar, Bbar = orc.refresh_rsvd_workers([g for g in Gs], Om, r, p, q)
+    U = torch.empty(m, r, device="cuda"); V = torch.empty(n, r, device="cuda"); sigma = torch.empty(r + p, device="cuda")
+    tsr.tsr_refresh_rsvd_workers(dev(Gs), dev(Om), r, p, q, U, V, sigma)
+    torch.cuda.synchronize()
+    assert rel_fro(sigma[:r], S_ref[:r]) < TOL_F32
+    check_orthonormal(V)
+    Ug, Vg = _sign_fix(U, V)
+    Ur, Vr = _sign_fix(U_ref, V_ref)
+    assert np.linalg.norm(Vg - Vr) / np.linalg.norm(Vr) < 5e-4, np.linalg.norm(Vg - Vr) / np.linalg.norm(Vr)
+    assert np.linalg.norm(Ug - Ur) / np.linalg.norm(Ur) < 5e-4, np.linalg.norm(Ug - Ur) / np.linalg.norm(Ur)
+    # sign-free: the lifted rank-r matrix U diag(sigma_r) V^T; then the Gram matrix of U
+    lift_ref = (U_ref * S_ref[:r]) @ V_ref.T
+    lift_gpu = (orc.f64(U) * orc.f64(sigma[:r])) @ orc.f64(V).T
+    assert rel_fro(lift_gpu, lift_ref) < TOL_F32
+    assert np.abs(Ug.T @ Ug - Ur.T @ Ur).max() < 5e-4          # columns oriented alike first
+    if workers > 1:
+        assert np.linalg.norm(U_ref.T @ U_ref - np.eye(r)) > 1e-4       # the defect is real and reproduced above
+
+
 # ------------------------------------------------------------------ configuration 1 end to end
 def test_config1_refresh_then_ten_steps(tsr):
     """Refresh on G_1, then steps 1..10 on G_1..G_10 (the initial refresh and step 1 share a
