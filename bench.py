@@ -125,6 +125,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="use fewer layers (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-refresh", action="store_true")
+    ap.add_argument("--refresh-workers", type=int, default=0,
+                    help="also time the N-worker refresh (averaged sketches) on one block of each distinct shape")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives are built); --gpus %d is not supported"
@@ -212,6 +214,30 @@ def main():
                     frac=achieved / HBM_PEAK_GBPS, ms_per_launch=stage_ms[dom],
                     traffic=read_traffic(os.path.join(ROOT, "profiles", "step_%s_traffic.txt" % w.name)))
 
+    # ---- optional: refresh with N workers (per-worker sketch chains, averaged Q and B)
+    refresh_workers = None
+    if args.refresh_workers > 0:
+        K = args.refresh_workers
+        k = w.r + w.p
+        per_shape = []
+        for (m, n) in sorted(set(w.shapes)):
+            key = si.stream_key(si.BASE_SEED, 5, m, n)
+            sig = si.make_signal(m, n, w.signal_rank, w.spectrum, key, device=dev)
+            Gs = torch.stack([si.gradient(sig, w.noise, si.stream_key(key, 100 + i), dtype=w.g_dtype) for i in range(K)])
+            Om = si.omega(n, k, si.stream_key(key, 3), device=dev)
+            U = torch.empty(m, w.r, device=dev); V = torch.empty(n, w.r, device=dev)
+            ws = tsr.workspace(tsr.tsr_refresh_workers_workspace_bytes(m, n, w.r, w.p, K), dev)
+            tsr.tsr_refresh_rsvd_workers(Gs, Om, w.r, w.p, w.q, U, V, None, ws)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            tsr.tsr_refresh_rsvd_workers(Gs, Om, w.r, w.p, w.q, U, V, None, ws)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3
+            defect = float(torch.linalg.norm(U.double().T @ U.double() - torch.eye(w.r, device=dev, dtype=torch.float64)))
+            per_shape.append({"shape": [m, n], "ms": round(ms, 3), "orthonormality_defect_U": defect,
+                              "sketch_payload_bytes_per_worker": 4 * k * (m + n), "dense_bytes_fp32": 4 * m * n})
+        refresh_workers = {"workers": K, "per_shape": per_shape}
+
     core_b, dense_b = plan.payload_bytes(4)
     out = {
         "metric": "Projected-Adam step GB/s + % HBM roofline; rSVD refresh ms/matrix + MFMA %",
@@ -226,6 +252,7 @@ def main():
         "stage_ms": {kk: round(v, 4) for kk, v in stage_ms.items()},
         "roofline": roofline,
         "refresh": refresh,
+        "refresh_workers": refresh_workers,
         "payload": {"core_bytes": core_b, "dense_bytes_fp32": dense_b, "ratio": dense_b / core_b},
     }
     if not args.no_cpu_baseline:
