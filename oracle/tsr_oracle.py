@@ -194,6 +194,16 @@ def refresh_rsvd_workers(G_workers, Omega, r, p, q):
     return U, V, S, Qbar, Bbar
 
 
+def realign_moment(M, U_old, V_old, U_new, V_new):
+    """First moment re-expressed in refreshed bases (refresh-alignment assumption of the
+    convergence analysis, Appendix B): the core M' whose lifted matrix U_new M' V_new^T is the
+    old lifted matrix U_old M V_old^T projected onto the new subspaces,
+        M' = (U_new^T U_old) M (V_old^T V_new)."""
+    A = matmul(U_new, U_old, ta=True)           # r x r
+    B = matmul(V_old, V_new, ta=True)           # r x r
+    return matmul(matmul(A, f64(M)), B)
+
+
 def tsr_adam_step(W, G_workers, U, V, M, Vm, t, lr, wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0):
     """One non-refresh iteration of Algorithm 1 for one matrix block: project every
     worker's gradient, average the cores, Adam on the core, lift and apply.

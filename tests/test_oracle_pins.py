@@ -422,3 +422,37 @@ def test_workers_refresh_nearby_workers_keep_the_mean_basis_nearly_orthonormal()
     assert np.abs(Qbar.T @ Qbar - np.eye(r)).max() < 1e-4
     assert np.abs(U.T @ U - np.eye(r)).max() < 1e-4
     assert np.allclose(S, np.linspace(2.0, 1.0, r), atol=1e-4)
+
+
+# ------------------------------------------------------------------ moment re-alignment (Appendix B)
+def test_realign_moment_is_the_doubly_projected_lifted_moment():
+    # the defining equation of the assumption, with the projectors formed explicitly by numpy
+    m, n, r = 30, 24, 5
+    Uo, Vo = orthonormal(m, r, 941), orthonormal(n, r, 942)
+    Un, Vn = orthonormal(m, r, 943), orthonormal(n, r, 944)
+    M = RNG.standard_normal((r, r))
+    M2 = orc.realign_moment(M, Uo, Vo, Un, Vn)
+    lifted_old = Uo @ M @ Vo.T
+    assert np.allclose(Un @ M2 @ Vn.T, (Un @ Un.T) @ lifted_old @ (Vn @ Vn.T), atol=1e-12)
+
+
+def test_realign_moment_unchanged_bases_and_rotated_bases():
+    m, n, r = 28, 33, 6
+    U, V = orthonormal(m, r, 951), orthonormal(n, r, 952)
+    M = RNG.standard_normal((r, r))
+    assert np.allclose(orc.realign_moment(M, U, V, U, V), M, atol=1e-12)
+    # same subspaces, rotated coordinates: the lifted moment does not move at all
+    Ru, _ = np.linalg.qr(RNG.standard_normal((r, r))); Rv, _ = np.linalg.qr(RNG.standard_normal((r, r)))
+    U2, V2 = U @ Ru, V @ Rv
+    M2 = orc.realign_moment(M, U, V, U2, V2)
+    assert np.allclose(M2, Ru.T @ M @ Rv, atol=1e-12)
+    assert np.allclose(U2 @ M2 @ V2.T, U @ M @ V.T, atol=1e-12)
+
+
+def test_realign_moment_orthogonal_subspace_loses_everything():
+    m, n, r = 20, 20, 4
+    Q = orthonormal(m, 2 * r, 961)
+    U_old, U_new = Q[:, :r].copy(), Q[:, r:].copy()          # orthogonal column spaces
+    V = orthonormal(n, r, 962)
+    M = RNG.standard_normal((r, r))
+    assert np.abs(orc.realign_moment(M, U_old, V, U_new, V)).max() < 1e-13
