@@ -161,6 +161,18 @@ int tsr_refresh_rsvd_workers(const void* G, int g_dtype, int m, int n, long long
                              float* U, float* V, float* sigma,
                              void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------- moment re-alignment (Appendix B)
+ * First moment re-expressed in refreshed bases, the refresh-alignment assumption of the
+ * convergence analysis: the core whose lifted matrix is the old lifted moment projected onto
+ * the new subspaces,  M <- (U_new^T U_old) M (V_old^T V_new)   (r x r, in place, fp32).
+ * Algorithm 1 as printed does not do this (moments are kept as they are across a refresh);
+ * a caller that wants it keeps copies of the old bases, refreshes, then calls this once per
+ * block.  The second moment is not touched (the paper defines no re-expression of it).
+ * Workspace: tsr_realign_workspace_bytes(m, n, r). */
+size_t tsr_realign_workspace_bytes(int m, int n, int r);
+int tsr_realign_moment(const float* U_old, const float* V_old, const float* U_new, const float* V_new,
+                       int m, int n, int r, float* M, void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------- batched all-layers calls
  * A plan holds, in caller-provided device workspace, the grouped-launch tables for a fixed
  * list of blocks, so that every phase of the step (and of the refresh) is a handful of

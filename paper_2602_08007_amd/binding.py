@@ -17,6 +17,7 @@ __all__ = [
     "tsr_stream_scale", "tsr_project_workspace_bytes", "tsr_project_core", "tsr_core_average", "tsr_adam_core", "tsr_sgd_core",
     "tsr_backproject_workspace_bytes", "tsr_backproject_apply",
     "tsr_refresh_workspace_bytes", "tsr_refresh_rsvd", "tsr_refresh_workers_workspace_bytes", "tsr_refresh_rsvd_workers",
+    "tsr_realign_workspace_bytes", "tsr_realign_moment",
     "tsr_matrix_desc", "tsr_hyper", "Plan", "workspace",
 ]
 
@@ -63,6 +64,8 @@ _lift_ws = _sig("tsr_backproject_workspace_bytes", _sz, _i, _i, _i)
 _lift = _sig("tsr_backproject_apply", _i, _vp, _i, _i, _ll, _vp, _vp, _vp, _i, _f, _f, _f, _i, _vp, _sz, _vp)
 _refresh_ws = _sig("tsr_refresh_workspace_bytes", _sz, _i, _i, _i, _i)
 _refresh = _sig("tsr_refresh_rsvd", _i, _vp, _i, _i, _i, _ll, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp)
+_realign_ws = _sig("tsr_realign_workspace_bytes", _sz, _i, _i, _i)
+_realign = _sig("tsr_realign_moment", _i, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp)
 _refresh_workers_ws = _sig("tsr_refresh_workers_workspace_bytes", _sz, _i, _i, _i, _i, _i)
 _refresh_workers = _sig("tsr_refresh_rsvd_workers", _i, _vp, _i, _i, _i, _ll, _ll, _i, _vp, _i, _i, _i, _vp, _vp, _vp, _vp,
                         _sz, _vp)
@@ -226,6 +229,23 @@ def tsr_refresh_rsvd_workers(G, Omega, r, p, q, U, V, sigma=None, ws=None, strea
     _check(_refresh_workers(_ptr(G), _gdtype(G), m, n, n, m * n, K, _ptr(Omega), r, p, q, _ptr(U), _ptr(V), _ptr(sigma),
                             _ptr(ws), ws.numel(), _stream(stream)))
     return U, V
+
+
+def tsr_realign_workspace_bytes(m: int, n: int, r: int) -> int:
+    return int(_realign_ws(m, n, r))
+
+
+def tsr_realign_moment(U_old, V_old, U_new, V_new, M, ws=None, stream=None):
+    m, r = U_old.shape
+    n = V_old.shape[0]
+    _f32c(U_old, V_old, U_new, V_new, M)
+    if tuple(U_new.shape) != (m, r) or tuple(V_old.shape) != (n, r) or tuple(V_new.shape) != (n, r) or tuple(M.shape) != (r, r):
+        raise ValueError("shape mismatch")
+    if ws is None:
+        ws = workspace(tsr_realign_workspace_bytes(m, n, r), M.device)
+    _check(_realign(_ptr(U_old), _ptr(V_old), _ptr(U_new), _ptr(V_new), m, n, r, _ptr(M), _ptr(ws), ws.numel(),
+                    _stream(stream)))
+    return M
 
 
 class Plan:

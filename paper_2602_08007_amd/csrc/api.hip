@@ -603,6 +603,53 @@ int tsr_refresh_rsvd_workers(const void* G, int g_dtype, int m, int n, long long
     return run_refresh_back(rp, false, cx);
 }
 
+// ---------------------------------------------------------------- moment re-alignment
+}  // extern "C"
+
+namespace {
+struct RealignProgram { GemmStage a, b, am, out; };
+void build_realign(RealignProgram& rp, const float* U_old, const float* V_old, const float* U_new, const float* V_new,
+                   int m, int n, int r, float* M, Arena& ar) {
+    float* A = ar.take<float>((size_t)r * r);       // U_new^T U_old
+    float* B = ar.take<float>((size_t)r * r);       // V_old^T V_new
+    float* AM = ar.take<float>((size_t)r * r);
+    std::vector<LogicalGemm> ga{LogicalGemm{U_new, U_old, r, r, r, r, m, A, r}};
+    std::vector<LogicalGemm> gb{LogicalGemm{V_old, V_new, r, r, r, r, n, B, r}};
+    std::vector<LogicalGemm> gam{LogicalGemm{A, M, r, r, r, r, r, AM, r}};
+    std::vector<LogicalGemm> gout{LogicalGemm{AM, B, r, r, r, r, r, M, r}};
+    build_stage(rp.a, variant(1, 1, 0, 3, 3), ga, ar);
+    build_stage(rp.b, variant(1, 1, 0, 3, 3), gb, ar);
+    build_stage(rp.am, variant(0, 1, 0, 3, 3), gam, ar, 1);
+    build_stage(rp.out, variant(0, 1, 0, 3, 3), gout, ar, 1);
+}
+}  // namespace
+
+extern "C" {
+
+size_t tsr_realign_workspace_bytes(int m, int n, int r) {
+    if (check_block(m, n, r) != TSR_OK) return 0;
+    Arena ar(nullptr);
+    RealignProgram rp;
+    build_realign(rp, nullptr, nullptr, nullptr, nullptr, m, n, r, nullptr, ar);
+    return ar.used();
+}
+
+int tsr_realign_moment(const float* U_old, const float* V_old, const float* U_new, const float* V_new, int m, int n,
+                       int r, float* M, void* ws, size_t ws_bytes, void* stream) {
+    TSR_TRY(check_block(m, n, r));
+    if (!U_old || !V_old || !U_new || !V_new || !M || !ws) return TSR_INVALID_ARG;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_realign_workspace_bytes(m, n, r)) return TSR_WORKSPACE_TOO_SMALL;
+    Arena ar(ws);
+    RealignProgram rp;
+    build_realign(rp, U_old, V_old, U_new, V_new, m, n, r, M, ar);
+    Ctx cx{(hipStream_t)stream, nullptr};
+    TSR_TRY(run_stage(rp.a, false, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
+    TSR_TRY(run_stage(rp.b, false, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
+    TSR_TRY(run_stage(rp.am, false, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
+    return run_stage(rp.out, false, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM);
+}
+
 // ---------------------------------------------------------------- plan
 static int check_descs(const tsr_matrix_desc* descs, int count, int n_workers, int with_refresh, int p,
                        bool need_ptrs) {

@@ -279,6 +279,24 @@ def test_refresh_workers_matches_oracle(tsr, workers, g_dtype, q):
         assert np.linalg.norm(U_ref.T @ U_ref - np.eye(r)) > 1e-4       # the defect is real and reproduced above
 
 
+# ------------------------------------------------------------------ moment re-alignment
+@pytest.mark.parametrize("m,n,r", [(300, 260, 24), (768, 2048, 256), (130, 75, 33)])
+def test_realign_moment_matches_oracle(tsr, m, n, r):
+    # new bases = old bases turned by a small random rotation of the whole space plus noise, as a
+    # refresh produces; also checks that in-place use leaves nothing else touched
+    Uo, Vo = bases(m, n, r, si.stream_key(851, m))
+    Un, Vn = bases(m, n, r, si.stream_key(852, m))
+    # not orthonormal on purpose: the formula does not need it
+    Un = (si.orthonormal(m, r, si.stream_key(853, m)) * 0.2 + Uo).float().contiguous()
+    Vn = (si.orthonormal(n, r, si.stream_key(854, m)) * 0.2 + Vo).float().contiguous()
+    M0 = si.normal((r, r), si.stream_key(855, m))
+    M_ref = orc.realign_moment(M0, Uo, Vo, Un, Vn)
+    M = dev(M0)
+    tsr.tsr_realign_moment(dev(Uo), dev(Vo), dev(Un), dev(Vn), M)
+    torch.cuda.synchronize()
+    assert rel_fro(M, M_ref) < TOL_F32
+
+
 # ------------------------------------------------------------------ configuration 1 end to end
 def test_config1_refresh_then_ten_steps(tsr):
     """Refresh on G_1, then steps 1..10 on G_1..G_10 (the initial refresh and step 1 share a
