@@ -243,7 +243,9 @@ def main():
         "metric": "Projected-Adam step GB/s + % HBM roofline; rSVD refresh ms/matrix + MFMA %",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 operands, f32 accumulate" if precision == tsr.TSR_PREC_BF16 else "f32 (split bf16x2), f32 accumulate",
+        "dtype": "bf16" if precision == tsr.TSR_PREC_BF16 else "f32",
+        "dtype_detail": "bf16 MFMA operands, f32 accumulation, f32 weights and moments" if precision == tsr.TSR_PREC_BF16
+                        else "f32 operands as 2-3 bf16 pieces, f32 accumulation",
         "data": "synthetic",
         "config": {"workload": w.name, "blocks": len(w.shapes), "r": w.r, "g_dtype": str(w.g_dtype).replace("torch.", ""),
                    "workers": w.workers},

@@ -12,6 +12,8 @@
  *   lift + apply               W <- W - lr (scale U D V^T + wd W)             tsr_backproject_apply
  *   all blocks of a model in grouped launches                                 tsr_plan_* / tsr_step_batched /
  *                                                                             tsr_refresh_batched
+ *   refresh with N workers (averaged sketches, one GPU)                       tsr_refresh_rsvd_workers
+ *   first moment re-expressed in refreshed bases (Appendix B)                 tsr_realign_moment
  *
  * Conventions
  *   - Every matrix is dense row-major.  G and W take an explicit leading dimension
