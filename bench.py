@@ -60,6 +60,13 @@ def build_blocks(w: si.Workload, device):
                              for k in range(w.workers)])
         else:
             G = si.gradient(sig, w.noise, si.stream_key(key, 100), dtype=w.g_dtype)
+        if n % 8 != 0:
+            # odd widths (5461 in the 1B shapes): row pitch padded to 8 elements, which the bf16
+            # kernels' 16-byte loads need; the matrix itself stays m x n (a strided view)
+            ld = (n + 7) // 8 * 8
+            Gp = torch.zeros(*G.shape[:-1], ld, dtype=G.dtype, device=G.device)
+            Gp[..., :n] = G
+            G = Gp[..., :n]
         r = w.r
         blocks.append(dict(
             G=G, W=si.weights(m, n, si.stream_key(key, 7), device=device),

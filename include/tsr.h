@@ -198,7 +198,8 @@ int tsr_plan_bases_changed(tsr_plan* plan);
 
 /* Which kernels the plan's per-step path runs: 1 = the k-contiguous bf16 family with the fused
  * lift (precision TSR_PREC_BF16, every gradient with a 16-byte aligned base, row pitch and worker
- * stride, n a multiple of 8, every operand addressable with 31-bit byte offsets), 0 = the
+ * stride, a row pitch of at least n rounded up to 8 elements, every operand addressable with
+ * 31-bit byte offsets), 0 = the
  * general grouped kernels (every other case; same results to the precision's tolerance).
  * A null plan gives -1. */
 int tsr_plan_kernel_path(const tsr_plan* plan);

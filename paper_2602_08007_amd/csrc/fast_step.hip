@@ -217,13 +217,15 @@ void upload_nt_stage(NtStageH& st, Arena& ar, Uploader& up) {
 }  // namespace
 
 // The NT kernels fetch 16-byte chunks through 32-bit buffer offsets: every gradient needs a
-// 16-byte aligned base, rows (and worker slices) that are multiples of 16 bytes, a column count
-// that is a multiple of 8, and tiles past the last row must still be addressable in 31 bits.
+// 16-byte aligned base, a row pitch (and worker stride) that is a multiple of 16 bytes and covers
+// the column count rounded up to 8 elements, and tiles past the last row must still be
+// addressable in 31 bits.
 bool fast_step_eligible(const std::vector<BlockView>& blocks, int n_workers) {
     const long long lim = 1LL << 31;
     for (const BlockView& b : blocks) {
         const long long esz = (b.g_dtype == TSR_BF16) ? 2 : 4;
-        if (((uintptr_t)b.G) % 16 != 0 || (b.ldg * esz) % 16 != 0 || b.n % 8 != 0) return false;
+        // a 16-byte chunk that starts inside a row must end inside that row's pitch
+        if (((uintptr_t)b.G) % 16 != 0 || (b.ldg * esz) % 16 != 0 || b.ldg < round8(b.n)) return false;
         if (n_workers > 1 && (b.g_stride * esz) % 16 != 0) return false;
         const long long big = std::max(b.m, b.n);
         if ((long long)(b.m + 256) * b.ldg * esz >= lim) return false;                  // G

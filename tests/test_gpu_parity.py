@@ -387,7 +387,7 @@ def guards_intact(full: torch.Tensor, m: int, n: int) -> bool:
     return bool((full[m:, :] == SENTINEL).all() and (full[:m, n:] == SENTINEL).all())
 
 
-def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3, guard_w=False):
+def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3, guard_w=False, pad_g=False):
     blocks, host = [], []
     for i, (m, n) in enumerate(shapes):
         k = si.stream_key(key, i)
@@ -398,7 +398,14 @@ def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3, guard_w=False):
         host.append(dict(G=Gs, U=U, V=V, W=W0))
         Wd, Wfull = guarded(W0) if guard_w else (dev(W0), None)
         host[-1]["W_full"] = Wfull
-        blocks.append(dict(G=dev(Gs) if workers > 1 else dev(Gs[0]), W=Wd, U=dev(U), V=dev(V),
+        Gd = dev(Gs) if workers > 1 else dev(Gs[0])
+        if pad_g:
+            # row pitch rounded up to 8 elements; the padding holds NaN, which no kernel may let through
+            ld = (n + 7) // 8 * 8
+            Gp = torch.full((*Gd.shape[:-1], ld), float("nan"), dtype=Gd.dtype, device="cuda")
+            Gp[..., :n] = Gd
+            Gd = Gp[..., :n]
+        blocks.append(dict(G=Gd, W=Wd, U=dev(U), V=dev(V),
                            M=torch.zeros(r, r, device="cuda"), Vm=torch.zeros(r, r, device="cuda"),
                            C=torch.empty(r, r, device="cuda"), D=torch.empty(r, r, device="cuda")))
     return blocks, host
@@ -431,17 +438,19 @@ def test_step_batched_matches_oracle(tsr, workers, g_dtype, prec):
 
 @pytest.mark.parametrize("r", [64, 128, 256])
 @pytest.mark.parametrize("workers", [1, 2])
-@pytest.mark.parametrize("rows16", [True, False])
+@pytest.mark.parametrize("rows16", [True, False, "padded"])
 def test_bf16_plan_fused_lift_ranks(tsr, r, workers, rows16):
     # ragged shapes (partial row panels, partial column tiles) with weight decay.  With gradient
     # rows that are multiples of 16 bytes the plan runs the k-contiguous bf16 kernels and, at
     # these ranks, the fused lift kernel; with odd row lengths it must fall back to the general
-    # kernels and still meet the same bar.
-    if rows16:
+    # kernels and still meet the same bar -- unless the caller pads the row pitch to 8 elements
+    # ("padded": odd n, NaN in the padding), which is all the bf16 kernels need.
+    if rows16 is True:
         shapes = [(r + 37, 2 * r + 64), (3 * r + 5, r), (r, r), (2 * r, 5 * r + 136), (r + 1, 2 * r + 8)]
     else:
         shapes = [(r + 37, 2 * r + 61), (3 * r + 5, r), (r, r), (2 * r, 5 * r + 130), (r + 1, 2 * r + 4)]
-    blocks, host = make_blocks(shapes, r, workers, torch.bfloat16, si.stream_key(631, r), guard_w=True)
+    blocks, host = make_blocks(shapes, r, workers, torch.bfloat16, si.stream_key(631, r), guard_w=True,
+                               pad_g=(rows16 == "padded"))
     plan = tsr.Plan(blocks, n_workers=workers, precision=tsr.TSR_PREC_BF16)
     assert plan.tsr_plan_kernel_path() == (1 if rows16 else 0)
     state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
