@@ -361,7 +361,9 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
     const bool utp_persist = tune_int("TSR_TUNE_UTP_PERSIST", 1, 0, 1) != 0;
     build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1, gv_persist);
     build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1, gv_persist);
-    build_nt_stage(fs.utp, NtVariant{tune("TSR_TUNE_UTP", NT_64x64), 0, 0}, utp, nb, ar,
+    // cores up to 256 x 256 are cut into 64 x 64 tiles (enough of them to fill the chip without
+    // splitting k); larger cores have enough 128 x 128 tiles
+    build_nt_stage(fs.utp, NtVariant{tune("TSR_TUNE_UTP", r_max >= 512 ? NT_128x128 : NT_64x64), 0, 0}, utp, nb, ar,
                    tune_int("TSR_TUNE_UTP_TILES", 2048, 1, 65536), utp_persist);
     build_nt_stage(fs.ud, NtVariant{tune("TSR_TUNE_UD", NT_128x128), 0, 1}, ud, nb, ar, 1);
     build_nt_stage(fs.tvt, NtVariant{tune("TSR_TUNE_TVT", NT_128x128), 0, 0}, tvt, nb, ar, 1);
