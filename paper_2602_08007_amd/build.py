@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtsr.so")
-SOURCES = ["gemm.hip", "nt_gemm.hip", "lift.hip", "small.hip", "fast_step.hip", "api.hip"]
+SOURCES = ["gemm.hip", "nt_gemm.hip", "lift.hip", "small.hip", "eig.hip", "fast_step.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -228,7 +229,7 @@ struct RefreshBlock {
     float* U; float* V; float* sigma;
     // workspace
     float *Y, *Yalt, *Z, *Zalt, *S, *Rinv, *XrT, *GrT;
-    double *work, *R1, *Rtot, *Gacc;
+    double *work, *R1, *Rtot, *Gacc, *eig;
 };
 
 struct OrthProgram {        // X (rows x k) -> orthonormal basis, in place, Xalt as scratch
@@ -301,8 +302,9 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         b.Z = ar.take<float>((size_t)b.n * k); b.Zalt = ar.take<float>((size_t)b.n * k);
         b.S = ar.take<float>(k * k); b.Rinv = ar.take<float>(k * k);
         b.XrT = ar.take<float>((size_t)b.r * k); b.GrT = ar.take<float>((size_t)b.r * k);
-        b.work = ar.take<double>(2 * k * k); b.R1 = ar.take<double>(k * k);
+        b.work = ar.take<double>(2 * k * k + 64); b.R1 = ar.take<double>(k * k);
         b.Rtot = ar.take<double>(k * k); b.Gacc = ar.take<double>(k * k);
+        b.eig = (b.k <= EIG_MAXK) ? ar.take<double>(3 * k * k) : nullptr;
         rp.blocks.push_back(b);
     }
     std::vector<LogicalGemm> sk[2], gtq[2], gq[2], uo, vo;
@@ -315,7 +317,7 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Z, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
         uo.push_back(LogicalGemm{b.Y, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
         vo.push_back(LogicalGemm{b.Z, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
-        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r});
+        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r, b.eig});
     }
     for (int d = 0; d < 2; ++d) {
         build_stage(rp.sketch[d], variant(0, 1, d, 2, 2), sk[d], ar);
@@ -349,7 +351,11 @@ int run_refresh_back(const RefreshProgram& rp, bool grouped, Ctx& cx) {
         Timed timed(cx, TSR_PROF_JACOBI);
         int max_k = 0;
         for (const JacobiBlock& jb : rp.jac) max_k = std::max(max_k, jb.k);
-        TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
+        static const bool chain = [] { const char* e = getenv("TSR_TUNE_EIG_CHAIN"); return !(e && e[0] == '0'); }();
+        if (chain && max_k <= EIG_MAXK)
+            TSR_HIP(launch_eig_svd(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
+        else
+            TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
     }
     TSR_TRY(run_stage(rp.uout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
     return run_stage(rp.vout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM);

@@ -1,0 +1,569 @@
+// SVD of the k x k triangular factor R of the refresh (the "small SVD" of the randomized SVD,
+// Algorithm 1's refresh step) as a chain of launches, for k <= EIG_MAXK:
+//   1. T = R R^T                        fp64 MFMA GEMM, 64 x 64 tiles over the whole chip
+//   2. per matrix, one workgroup:       Householder tridiagonalization of T (reflectors parked in
+//      the rows of T they cleared), eigenvalues by bisection (one per thread), eigenvectors of
+//      the tridiagonal matrix by inverse iteration (one per thread, pivoted LU of T - lambda I),
+//      Gram-Schmidt inside groups of numerically equal eigenvalues
+//   3. E = H_0 H_1 ... Z                reflectors applied to 64 eigenvectors per workgroup, the
+//      vectors held in registers
+//   4. E^T R                            fp64 MFMA GEMM
+//   5. singular values = row norms of E^T R, ordering, fp32 outputs
+// Nothing here is a serial chain longer than k steps, which is what separates it from the QL
+// sweeps of the single-kernel variant (about k^2 dependent rotations per matrix).
+#include <hip/hip_runtime.h>
+
+#include "small.h"
+
+namespace tsr {
+namespace {
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+constexpr int EIG_THREADS = 1024;
+constexpr int EIG_PARTS = 4;
+constexpr double EIG_EPS = 2.220446049250313e-16;
+
+__device__ inline double eig_wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// 1 / x to full precision for finite non-zero x of ordinary size (no scaling, no fix-up)
+__device__ inline double eig_rcp(double x) {
+    double r = __builtin_amdgcn_rcp(x);
+    r = fma(fma(-x, r, 1.0), r, r);
+    r = fma(fma(-x, r, 1.0), r, r);
+    return r;
+}
+
+// ------------------------------------------------------------------ fp64 MFMA GEMMs
+// v_mfma_f64_16x16x4: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16] and receives
+// D[4 v + l / 16][l % 16] in element v.  One wave owns a 32 x 32 patch (2 x 2 MFMA tiles), a
+// workgroup of four waves a 64 x 64 tile; operands come straight from L2 (the matrices are a
+// few hundred KB), 16 k-values per round.
+// WHICH = 0: T = R R^T (R upper triangular: the sum for T[i][j] starts at max(i, j));
+// WHICH = 1: E^T R into the second half of tmp (the sum for column c ends at c).
+template <int WHICH>
+__global__ __launch_bounds__(256) void eig_gemm_kernel(const JacobiBlock* table, const JacobiBlock single) {
+    JacobiBlock jb = single;
+    if (table) jb = table[blockIdx.y];
+    const JacobiBlock* blk = &jb;
+    const int k = blk->k;
+    const int tiles = (k + 63) >> 6;
+    if ((int)blockIdx.x >= tiles * tiles) return;
+    const int tm = blockIdx.x / tiles, tn = blockIdx.x % tiles;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m0 = tm * 64 + (wave >> 1) * 32, n0 = tn * 64 + (wave & 1) * 32;
+    if (m0 >= k || n0 >= k) return;
+    const double* __restrict__ A;
+    const double* __restrict__ B = blk->R;
+    double* __restrict__ C;
+    long long sam, sak, sbk, sbn;
+    int k_lo = 0, k_hi = k;
+    if (WHICH == 0) { A = blk->R; sam = k; sak = 1; sbk = 1; sbn = k; C = blk->tmp; k_lo = max(m0, n0) & ~3; }
+    else { A = blk->Gacc; sam = 1; sak = k; sbk = k; sbn = 1; C = blk->tmp + (size_t)k * k; k_hi = min(k, n0 + 32); }
+    const int li = lane & 15, lk = lane >> 4;
+    d4 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = d4{0.0, 0.0, 0.0, 0.0};
+    long long arow[2], bcol[2];
+    bool aok[2], bok[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = m0 + 16 * i + li, col = n0 + 16 * i + li;
+        aok[i] = row < k; bok[i] = col < k;
+        arow[i] = (long long)min(row, k - 1) * sam;
+        bcol[i] = (long long)min(col, k - 1) * sbn;
+    }
+    for (int kk = k_lo; kk < k_hi; kk += 16) {
+        double a[4][2], b[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int kc = kk + 4 * u + lk;
+            const bool kok = kc < k_hi;
+            const long long kcc = min(kc, k - 1);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const double av = A[arow[i] + kcc * sak];
+                const double bv = B[kcc * sbk + bcol[i]];
+                a[u][i] = (kok && aok[i]) ? av : 0.0;
+                b[u][i] = (kok && bok[i]) ? bv : 0.0;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u][i], b[u][j], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = m0 + 16 * i + 4 * v + lk, col = n0 + 16 * j + li;
+                if (row < k && col < k) C[(size_t)row * k + col] = acc[i][j][v];
+            }
+}
+
+// ------------------------------------------------------------------ tridiagonal eigenproblem
+// Start vector of the inverse iteration: a fixed pseudo-random value in (-0.5, 0.5) per entry
+// (integer finalizer of the published MurmurHash3).
+__device__ inline double eig_start_value(unsigned i, unsigned j) {
+    unsigned h = i * 2654435761u ^ (j * 40503u + 0x9E3779B9u);
+    h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
+    return (double)h * (1.0 / 4294967296.0) - 0.5 + 1.0 / 8589934592.0;
+}
+
+__global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBlock* table, const JacobiBlock single) {
+    JacobiBlock jb = single;
+    if (table) jb = table[blockIdx.x];
+    const JacobiBlock* blk = &jb;
+    const int k = blk->k;
+    double* T = blk->tmp;                       // symmetric, full storage; afterwards the reflectors
+    double* Z = blk->tmp + (size_t)k * k;       // eigenvectors of the tridiagonal matrix, Z[i][j] = j-th vector
+    double* U0 = blk->scratch;                  // per thread j: reciprocal pivots, first and second
+    double* U1 = U0 + (size_t)k * k;            //   super-diagonal of the LU factor, entry [i][j]
+    double* U2 = U1 + (size_t)k * k;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+    __shared__ double s_d[EIG_MAXK];            // diagonal
+    __shared__ double s_e[EIG_MAXK];            // sub-diagonal, s_e[i] couples i and i + 1
+    __shared__ double s_v[EIG_MAXK];            // Householder vector; later the eigenvalues
+    __shared__ double s_w[EIG_MAXK];            // work vector; later the squared sub-diagonal
+    __shared__ double s_part[EIG_PARTS * EIG_MAXK];
+    __shared__ double s_red[EIG_THREADS / 64];
+    __shared__ int s_first[EIG_MAXK];           // first member of the group an eigenvalue belongs to
+
+    auto block_sum = [&](double v) -> double {
+        v = eig_wave_sum(v);
+        __syncthreads();
+        if (lane == 0) s_red[wave] = v;
+        __syncthreads();
+        double t = 0.0;
+        for (int i = 0; i < nw; ++i) t += s_red[i];
+        return t;
+    };
+    auto block_max = [&](double v) -> double {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+        __syncthreads();
+        if (lane == 0) s_red[wave] = v;
+        __syncthreads();
+        double t = s_red[0];
+        for (int i = 1; i < nw; ++i) t = fmax(t, s_red[i]);
+        return t;
+    };
+
+    // ---- Householder tridiagonalization.  Step j clears column j below the sub-diagonal with
+    // H_j = I - beta v v^T on indices j+1..k-1; v goes to row j of T (columns j+1..), beta to
+    // T[j][j].  The product T22 v has only n1 outputs: each output's sum is cut into pieces so
+    // that all threads carry loads (the step is bound by memory latency, not by arithmetic).
+    const int parts = EIG_PARTS;
+    const int tpp = nt / parts;
+    const int part = tid / tpp, li = tid % tpp;
+    for (int j = 0; j + 2 < k; ++j) {
+        const int n1 = k - j - 1;
+        double psum = 0.0;
+        for (int i = tid; i < n1; i += nt) { const double x = T[(size_t)(j + 1 + i) * k + j]; s_v[i] = x; psum += x * x; }
+        const double xnorm2 = block_sum(psum);
+        const double x0 = s_v[0];
+        const double xn = sqrt(xnorm2);
+        double alpha = (x0 >= 0.0) ? -xn : xn;
+        const double vnorm2 = xnorm2 - 2.0 * alpha * x0 + alpha * alpha;
+        const bool skip = (xnorm2 - x0 * x0 <= 0.0) || vnorm2 <= 0.0;        // already tridiagonal here
+        if (skip) alpha = x0;
+        __syncthreads();
+        const double beta = skip ? 0.0 : 2.0 / vnorm2;
+        if (tid == 0) { s_d[j] = T[(size_t)j * k + j]; s_e[j] = alpha; T[(size_t)j * k + j] = beta; if (!skip) s_v[0] = x0 - alpha; }
+        __syncthreads();
+        if (skip) continue;
+        for (int i = tid; i < n1; i += nt) T[(size_t)j * k + j + 1 + i] = s_v[i];
+        const int seg = (n1 + parts - 1) / parts;
+        const int c_lo = min(n1, part * seg), c_hi = min(n1, c_lo + seg);
+        for (int i = li; i < n1; i += tpp) {
+            double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+            const double* col = T + (size_t)(j + 1) * k + (j + 1 + i);
+            int c = c_lo;
+            for (; c + 8 <= c_hi; c += 8) {
+                double x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = col[(size_t)(c + u) * k];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc[u] += x[u] * s_v[c + u];
+            }
+            for (; c < c_hi; ++c) acc[0] += col[(size_t)c * k] * s_v[c];
+            s_part[part * EIG_MAXK + i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+        }
+        __syncthreads();
+        double pv = 0.0;
+        for (int i = tid; i < n1; i += nt) {
+            double t = 0.0;
+            for (int q = 0; q < parts; ++q) t += s_part[q * EIG_MAXK + i];
+            t *= beta;
+            s_w[i] = t;
+            pv += t * s_v[i];
+        }
+        const double kk2 = 0.5 * beta * block_sum(pv);
+        for (int i = tid; i < n1; i += nt) s_w[i] -= kk2 * s_v[i];           // w = p - (beta/2)(p.v) v
+        __syncthreads();
+        // T22 -= v w^T + w v^T
+        for (int idx = tid; idx < n1 * n1; idx += nt) {
+            const int i = idx / n1, c = idx % n1;
+            T[(size_t)(j + 1 + i) * k + j + 1 + c] -= s_v[i] * s_w[c] + s_w[i] * s_v[c];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (k >= 2) { s_d[k - 2] = T[(size_t)(k - 2) * k + k - 2]; s_e[k - 2] = T[(size_t)(k - 1) * k + k - 2]; }
+        s_d[k - 1] = T[(size_t)(k - 1) * k + k - 1];
+        s_e[k - 1] = 0.0;
+    }
+    __syncthreads();
+
+    // ---- eigenvalues by bisection on the Sturm count, eigenvalue j (ascending) on thread j
+    double gl = 0.0, gu = 0.0;
+    {
+        double lo = 1e300, hi = -1e300;
+        for (int i = tid; i < k; i += nt) {
+            const double rad = ((i > 0) ? fabs(s_e[i - 1]) : 0.0) + ((i < k - 1) ? fabs(s_e[i]) : 0.0);
+            lo = fmin(lo, s_d[i] - rad);
+            hi = fmax(hi, s_d[i] + rad);
+            s_w[i] = s_e[i] * s_e[i];
+        }
+        gu = block_max(hi);
+        gl = -block_max(-lo);
+    }
+    const double tnorm = fmax(fabs(gl), fabs(gu));
+    if (!(tnorm > 0.0) || !(tnorm < 1e300)) {
+        // zero (or non-finite) matrix: every orthonormal basis is one of eigenvectors
+        for (int idx = tid; idx < k * k; idx += nt) Z[idx] = (idx / k == idx % k) ? 1.0 : 0.0;
+        return;
+    }
+    const double pivmin = fmax(1e-290, 1e-32 * tnorm);
+    const double tiny = EIG_EPS * tnorm;                 // floor of an LU pivot
+    {
+        const double margin = 2.0 * EIG_EPS * tnorm * (double)k + 2.0 * pivmin;
+        gl -= margin; gu += margin;
+    }
+    __syncthreads();
+    if (tid < k) {
+        double lo = gl, hi = gu;
+        const double atol = EIG_EPS * tnorm;
+        for (int it = 0; it < 100; ++it) {
+            const double mid = 0.5 * (lo + hi);
+            if (hi - lo <= atol || !(mid > lo) || !(mid < hi)) break;
+            double q = s_d[0] - mid;
+            if (fabs(q) < pivmin) q = -pivmin;
+            int cnt = (q < 0.0) ? 1 : 0;
+            for (int i = 1; i < k; ++i) {
+                q = (s_d[i] - mid) - s_w[i - 1] * eig_rcp(q);
+                if (fabs(q) < pivmin) q = -pivmin;
+                cnt += (q < 0.0) ? 1 : 0;
+            }
+            if (cnt > tid) hi = mid; else lo = mid;
+        }
+        s_v[tid] = 0.5 * (lo + hi);
+    }
+    __syncthreads();
+
+    // ---- eigenvectors by inverse iteration, vector j on thread j.  T - lambda I = P L U with
+    // partial pivoting; U (three diagonals, pivots as reciprocals) is kept, L is applied to the
+    // right-hand side while it is formed and formed again in every round.
+    if (tid < k) {
+        const int j = tid;
+        const double lam = s_v[j];
+        double* zc = Z + j;
+        double* u0 = U0 + j; double* u1 = U1 + j; double* u2 = U2 + j;
+        double scale = 1.0;
+        for (int round = 0; round < 3; ++round) {
+            // forward: eliminate, apply to y (round 0: the start vector, later scale * previous x)
+            auto yval = [&](int i) -> double {
+                return (round == 0) ? eig_start_value((unsigned)i, (unsigned)j) : scale * zc[(size_t)i * k];
+            };
+            double a = s_d[0] - lam, b = (k > 1) ? s_e[0] : 0.0;
+            double ycur = yval(0);
+            auto step = [&](int i, double ynext) {
+                const double c = s_e[i];
+                const double dn = s_d[i + 1] - lam;
+                const double en = (i + 2 < k) ? s_e[i + 1] : 0.0;
+                const size_t o = (size_t)i * k;
+                if (fabs(a) >= fabs(c)) {
+                    double piv = a;
+                    if (fabs(piv) < tiny) piv = (piv < 0.0) ? -tiny : tiny;
+                    const double inv = eig_rcp(piv);
+                    const double mult = c * inv;
+                    if (round == 0) { u0[o] = inv; u1[o] = b; u2[o] = 0.0; }
+                    zc[o] = ycur;
+                    a = dn - mult * b; b = en;
+                    ycur = ynext - mult * ycur;
+                } else {
+                    double piv = c;
+                    if (fabs(piv) < tiny) piv = (piv < 0.0) ? -tiny : tiny;
+                    const double inv = eig_rcp(piv);
+                    const double mult = a * inv;
+                    if (round == 0) { u0[o] = inv; u1[o] = dn; u2[o] = en; }
+                    zc[o] = ynext;
+                    a = b - mult * dn; b = -mult * en;
+                    ycur = ycur - mult * ynext;
+                }
+            };
+            {
+                int i = 0;
+                for (; i + 4 < k; i += 4) {                  // rows i+1 .. i+4 fetched together
+                    double yn[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) yn[u] = yval(i + 1 + u);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) step(i + u, yn[u]);
+                }
+                for (; i + 1 < k; ++i) step(i, yval(i + 1));
+            }
+            {
+                double piv = a;
+                if (fabs(piv) < tiny) piv = (piv < 0.0) ? -tiny : tiny;
+                if (round == 0) { u0[(size_t)(k - 1) * k] = eig_rcp(piv); u1[(size_t)(k - 1) * k] = 0.0; u2[(size_t)(k - 1) * k] = 0.0; }
+                zc[(size_t)(k - 1) * k] = ycur;
+            }
+            // backward: U x = y, four rows fetched together
+            double x1 = 0.0, x2 = 0.0, amax = 0.0;      // x[i+1], x[i+2]
+            bool bad = false;
+            int i = k - 1;
+            for (; i >= 3; i -= 4) {
+                double y[4], p0[4], p1[4], p2[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const size_t o = (size_t)(i - u) * k;
+                    y[u] = zc[o]; p0[u] = u0[o]; p1[u] = u1[o]; p2[u] = u2[o];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const double x = (y[u] - p1[u] * x1 - p2[u] * x2) * p0[u];
+                    zc[(size_t)(i - u) * k] = x;
+                    amax = fmax(amax, fabs(x));
+                    bad = bad || !(fabs(x) <= 1e300);
+                    x2 = x1; x1 = x;
+                }
+            }
+            for (; i >= 0; --i) {
+                const size_t o = (size_t)i * k;
+                const double x = (zc[o] - u1[o] * x1 - u2[o] * x2) * u0[o];
+                zc[o] = x;
+                amax = fmax(amax, fabs(x));
+                bad = bad || !(fabs(x) <= 1e300);
+                x2 = x1; x1 = x;
+            }
+            if (bad || !(amax > 0.0)) {
+                // overflow or a vanished vector (the floored pivots are meant to rule both out):
+                // go on from the unit vector rather than carry a non-finite value
+                for (int q = 0; q < k; ++q) zc[(size_t)q * k] = (q == j) ? 1.0 : 0.0;
+                amax = 1.0;
+            }
+            scale = 1.0 / amax;
+        }
+        double ss = 0.0;
+        for (int i = 0; i < k; ++i) { const double x = scale * zc[(size_t)i * k]; ss += x * x; }
+        const double nrm = scale / sqrt(ss);
+        for (int i = 0; i < k; ++i) zc[(size_t)i * k] *= nrm;
+    }
+    __syncthreads();
+
+    // ---- eigenvalues closer than ortol form a group; inside a group the vectors found above
+    // span the right subspace but need not be orthogonal: Gram-Schmidt (two passes) in order.
+    {
+        const double ortol = 1e-9 * tnorm;
+        if (tid == 0) {
+            s_first[0] = 0;
+            for (int j = 1; j < k; ++j) s_first[j] = (s_v[j] - s_v[j - 1] <= ortol) ? s_first[j - 1] : j;
+        }
+        __syncthreads();
+        double* coef = s_part;
+        for (int j = 1; j < k; ++j) {
+            const int cs = s_first[j];
+            if (cs == j) continue;                       // uniform
+            for (int pass = 0; pass < 2; ++pass) {
+                for (int i = cs + wave; i < j; i += nw) {
+                    double a = 0.0;
+                    for (int t = lane; t < k; t += 64) a += Z[(size_t)t * k + i] * Z[(size_t)t * k + j];
+                    a = eig_wave_sum(a);
+                    if (lane == 0) coef[i - cs] = a;
+                }
+                __syncthreads();
+                for (int t = tid; t < k; t += nt) {
+                    double a = 0.0;
+                    for (int i = cs; i < j; ++i) a += coef[i - cs] * Z[(size_t)t * k + i];
+                    Z[(size_t)t * k + j] -= a;
+                }
+                __syncthreads();
+            }
+            double ss = 0.0;
+            for (int t = tid; t < k; t += nt) { const double x = Z[(size_t)t * k + j]; ss += x * x; }
+            ss = block_sum(ss);
+            const double inv = (ss > 0.0) ? 1.0 / sqrt(ss) : 0.0;
+            for (int t = tid; t < k; t += nt) Z[(size_t)t * k + j] *= inv;
+            __syncthreads();
+        }
+    }
+}
+
+// ------------------------------------------------------------------ back-transformation
+// E = H_0 H_1 ... H_{k-3} Z for 64 columns of Z per workgroup: lane = column, each of the WAVES
+// waves owns EPT consecutive rows (in registers); the reflector entries are uniform over a
+// wave.  One barrier per reflector (the dot product spans the waves).
+template <int EPT, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void eig_backtransform_kernel(const JacobiBlock* table, const JacobiBlock single) {
+    JacobiBlock jb = single;
+    if (table) jb = table[blockIdx.y];
+    const JacobiBlock* blk = &jb;
+    const int k = blk->k;
+    const int c0 = blockIdx.x * 64;
+    if (c0 >= k) return;
+    // the reflectors (written by the previous launch, constant here) are read through a
+    // constant-address-space pointer: their addresses are uniform over a wave, which lets them
+    // travel through the scalar data path
+    typedef const double __attribute__((address_space(4))) gdouble;
+    typedef double d8 __attribute__((ext_vector_type(8)));
+    typedef d8 __attribute__((aligned(8))) d8u;
+    typedef const d8u __attribute__((address_space(4))) cd8u;
+    static_assert(EPT % 8 == 0, "rows per wave come in chunks of eight");
+    const gdouble* __restrict__ T = (const gdouble*)blk->tmp;
+    const double* __restrict__ Z = blk->tmp + (size_t)k * k;
+    double* __restrict__ E = blk->Gacc;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = c0 + lane;
+    const bool colok = col < k;
+    const int i0 = wave * EPT;
+    __shared__ double s_dot[2][WAVES][64];
+    double x[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int i = i0 + e;
+        x[e] = (colok && i < k) ? Z[(size_t)min(i, k - 1) * k + min(col, k - 1)] : 0.0;
+    }
+    int par = 0;
+    for (int j = k - 3; j >= 0; --j) {
+        const double beta = T[(size_t)j * k + j];
+        if (beta == 0.0) continue;                          // uniform: no reflector at this step
+        const gdouble* __restrict__ vrow = T + (size_t)j * k;
+        const bool active = i0 + EPT > j + 1 && i0 < k;     // uniform over the wave
+        // eight reflector entries per fetch; chunks that end at or before j hold no entry of v.
+        // (A chunk may reach past column k-1: what it reads there is still inside tmp, which
+        // carries 64 doubles of padding for the smallest k, and is masked out.)
+        double part = 0.0;
+        if (active) {
+#pragma unroll
+            for (int c = 0; c < EPT / 8; ++c) {
+                const int ib = i0 + 8 * c;
+                if (ib + 7 > j && ib < k) {
+                    const d8u v8 = *(const cd8u*)(vrow + ib);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const double v = (ib + u > j && ib + u < k) ? v8[u] : 0.0;
+                        part += v * x[8 * c + u];
+                    }
+                }
+            }
+        }
+        s_dot[par][wave][lane] = part;
+        __syncthreads();
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) tot += s_dot[par][w][lane];
+        const double s = beta * tot;
+        if (active) {
+#pragma unroll
+            for (int c = 0; c < EPT / 8; ++c) {
+                const int ib = i0 + 8 * c;
+                if (ib + 7 > j && ib < k) {
+                    const d8u v8 = *(const cd8u*)(vrow + ib);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const double v = (ib + u > j && ib + u < k) ? v8[u] : 0.0;
+                        x[8 * c + u] -= s * v;
+                    }
+                }
+            }
+        }
+        par ^= 1;
+    }
+    if (colok) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int i = i0 + e;
+            if (i < k) E[(size_t)i * k + col] = x[e];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ ordering and outputs
+// Rows of E^T R (second half of tmp) are mutually orthogonal with norms sigma_i.
+__global__ __launch_bounds__(EIG_THREADS) void eig_finish_kernel(const JacobiBlock* table, const JacobiBlock single) {
+    JacobiBlock jb = single;
+    if (table) jb = table[blockIdx.x];
+    const JacobiBlock* blk = &jb;
+    const int k = blk->k, r = blk->r;
+    const double* __restrict__ ER = blk->tmp + (size_t)k * k;
+    const double* __restrict__ E = blk->Gacc;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+    __shared__ double s_sig[EIG_MAXK];
+    __shared__ int s_rank[EIG_MAXK];
+    for (int j = wave; j < k; j += nw) {
+        double a = 0.0;
+        for (int c = lane; c < k; c += 64) { const double v = ER[(size_t)j * k + c]; a += v * v; }
+        a = eig_wave_sum(a);
+        if (lane == 0) s_sig[j] = sqrt(a);
+    }
+    __syncthreads();
+    for (int j = tid; j < k; j += nt) {
+        const double sj = s_sig[j];
+        int rank = 0;
+        for (int i = 0; i < k; ++i) {
+            const double si = s_sig[i];
+            rank += (si > sj || (si == sj && i < j)) ? 1 : 0;
+        }
+        s_rank[j] = rank;
+        if (blk->sigma) blk->sigma[rank] = (float)sj;
+    }
+    __syncthreads();
+    for (int j = wave; j < k; j += nw) {
+        const int rank = s_rank[j];
+        if (rank >= r) continue;
+        const double sj = s_sig[j];
+        const double inv = (sj > 0.0) ? 1.0 / sj : 0.0;
+        for (int c = lane; c < k; c += 64) {
+            blk->XrT[(size_t)rank * k + c] = (float)(ER[(size_t)j * k + c] * inv);
+            blk->GrT[(size_t)rank * k + c] = (float)E[(size_t)c * k + j];
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_eig_svd(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
+                          hipStream_t stream) {
+    if (blocks <= 0) return hipSuccess;
+    if (max_k > EIG_MAXK || max_k < 1) return hipErrorInvalidValue;
+    JacobiBlock sb{};
+    if (single) sb = *single;
+    const int tiles = (max_k + 63) / 64;
+    hipLaunchKernelGGL(eig_gemm_kernel<0>, dim3(tiles * tiles, blocks), dim3(256), 0, stream, table_dev, sb);
+    hipLaunchKernelGGL(eig_tridiag_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
+    const dim3 bt_grid(tiles, blocks);
+    if (max_k <= 32) hipLaunchKernelGGL((eig_backtransform_kernel<8, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);
+    else if (max_k <= 96) hipLaunchKernelGGL((eig_backtransform_kernel<24, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);
+    else if (max_k <= 160) hipLaunchKernelGGL((eig_backtransform_kernel<40, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);
+    else if (max_k <= 320) hipLaunchKernelGGL((eig_backtransform_kernel<40, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb);
+    else hipLaunchKernelGGL((eig_backtransform_kernel<72, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb);
+    hipLaunchKernelGGL(eig_gemm_kernel<1>, dim3(tiles * tiles, blocks), dim3(256), 0, stream, table_dev, sb);
+    hipLaunchKernelGGL(eig_finish_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
+    return hipGetLastError();
+}
+
+}  // namespace tsr

@@ -46,6 +46,7 @@ struct FastStep {
         std::vector<LiftRange> ranges;  const LiftRange* d_ranges = nullptr;   // one list of items per workgroup
     };
     std::vector<LiftGroup> lifts;
+    bool adam_fused = false;   // the U^T P launch also runs Adam on each core (no separate Adam kernel)
     bool bases_dirty = true;
 };
 

@@ -188,10 +188,11 @@ void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogi
         interleave_xcd(st.tiles, tile_block, tile_work, n_blocks, NtTile{-1, 0, 0, 0});
 }
 
-int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind) {
+int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind, const AdamScalars* adam = nullptr) {
     if (st.empty()) return TSR_OK;
     Timed timed(cx, kind);
     NtLaunch L{};
+    if (adam) L.adam = *adam;
     L.probs = st.d_probs; L.tiles = st.d_tiles; L.n_tiles = (int)st.tiles.size();
     if (!st.ranges.empty()) { L.ranges = st.d_ranges; L.n_tiles = (int)st.ranges.size(); }
     if (st.reduces.empty()) {
@@ -372,6 +373,23 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
 void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {
     fs.d_shadows = up.put(fs.shadows, ar);
     fs.d_adam = up.put(fs.adam, ar);
+    // Adam rides in the epilogue of U^T P when every core is written whole by that GEMM: one
+    // worker, no k split, persistent launch, one problem per block in block order
+    fs.adam_fused = false;
+    if (tune_int("TSR_TUNE_ADAM_FUSED", 1, 0, 1) != 0 && fs.utp.reduces.empty() && !fs.utp.ranges.empty() &&
+        (fs.utp.var.shape == NT_64x64 || fs.utp.var.shape == NT_128x128) && fs.utp.probs.size() == fs.adam.size()) {
+        bool ok = true;
+        for (size_t j = 0; j < fs.adam.size(); ++j) {
+            const NtProblem& p = fs.utp.probs[j];
+            const AdamTBlock& a = fs.adam[j];
+            ok = ok && p.C == (void*)a.C && p.M == a.r && p.N == a.r && p.ldc == a.r && (a.DTf == nullptr || a.r % 32 == 0);
+        }
+        if (ok) {
+            for (size_t j = 0; j < fs.adam.size(); ++j) fs.utp.probs[j].adam = fs.d_adam + j;
+            fs.utp.var.fused_adam = 1;
+            fs.adam_fused = true;
+        }
+    }
     for (int d = 0; d < 2; ++d) upload_nt_stage(fs.gv[d], ar, up);
     for (auto& g : fs.projs) g.d_items = up.put(g.items, ar);
     upload_nt_stage(fs.utp, ar, up);
@@ -395,8 +413,8 @@ int run_fast_step(FastStep& fs, int n_workers, const AdamScalars& s, float lr, f
         Timed timed(cx, TSR_PROF_GV);
         TSR_HIP(launch_proj(g.d_items, (int)g.items.size(), g.r, g.panel_rows + g.variant, cx.s));
     }
-    TSR_TRY(run_nt_stage(fs.utp, 1.0f / (float)n_workers, 0.0f, cx, TSR_PROF_UTP));
-    {
+    TSR_TRY(run_nt_stage(fs.utp, 1.0f / (float)n_workers, 0.0f, cx, TSR_PROF_UTP, fs.adam_fused ? &s : nullptr));
+    if (!fs.adam_fused) {
         Timed timed(cx, TSR_PROF_ADAM);
         TSR_HIP(launch_adam_t(fs.d_adam, (int)fs.adam.size(), fs.max_r, s, cx.s));
     }

@@ -9,6 +9,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include "small.h"
+
 namespace tsr {
 
 struct NtProblem {
@@ -19,6 +21,7 @@ struct NtProblem {
     long long c_split_stride;
     int M, N, K;
     int kchunk;             // multiple of 64
+    const AdamTBlock* adam; // fused Adam epilogue (NtVariant::fused_adam): this core's moment arrays
 };
 
 struct NtTile { int prob, tm, tn, ks; };     // prob < 0: idle workgroup
@@ -34,6 +37,7 @@ struct NtLaunch {
     const NtRange* ranges;
     int n_tiles;
     float alpha, beta;
+    AdamScalars adam;       // fused Adam epilogue only
 };
 
 enum NtShape {
@@ -54,6 +58,8 @@ struct NtVariant {
     int shape;      // NtShape
     int b_f32;      // B operand stored as fp32
     int out_bf16;   // C stored as bf16 (beta ignored)
+    int fused_adam; // persistent launches only: C (an r x r core, ldc = r) is final after this GEMM and
+                    // the epilogue runs Adam on it (C, M, Vm, D and the bf16 D^T written there)
 };
 
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream);

@@ -265,12 +265,12 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
 // through the same pipeline as above (two register stages, two LDS buffers) without draining at
 // tile boundaries: the loader cursor runs three k-tiles ahead of the compute cursor and moves on
 // to the next tile by itself.  A tile's accumulators are written out when the compute cursor
-// leaves it.  OUT: 0 = fp32 store, 1 = bf16 store.
+// leaves it.  OUT: 0 = fp32 store, 1 = bf16 store, 3 = fp32 store of a core followed by Adam on it.
 template <int TM, int TN, int WM, int WN, int NT_BK, bool B_F32, int OUT, int MINB>
 __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(const NtLaunch L) {
     constexpr bool OUT_BF16 = (OUT == 1);
     static_assert(WM * WN == 4, "four waves");
-    static_assert(OUT == 0 || OUT == 1, "no read-modify-write epilogue here");
+    static_assert(OUT == 0 || OUT == 1 || OUT == 3, "no read-modify-write epilogue here");
     constexpr int NT_KP = NT_BK + 8;
     constexpr int FM = TM / WM / 32, FN = TN / WN / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
@@ -368,6 +368,10 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
                                           ((long long)(M - 1) * pp->ldc + N) * CSZ);
         const unsigned ldc_b = (unsigned)pp->ldc * CSZ;
         const int row0 = t.tm * TM, col0 = t.tn * TN;
+        AdamTBlock ab = {};
+        const AdamScalars sc = L.adam;
+        unsigned short dq[4] = {0, 0, 0, 0};
+        if constexpr (OUT == 3) ab = *pp->adam;
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -377,10 +381,38 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
                     const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
                     const int row = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4 + (e >> 2) * 8 + (e & 3);
                     const unsigned vo = (row < M && col < N) ? (unsigned)row * ldc_b + (unsigned)col * CSZ : 0x80000000u;
-                    if constexpr (OUT_BF16)
+                    if constexpr (OUT_BF16) {
                         __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_bits(alpha * acc[i][j][e]), rC, (int)vo, 0, 0);
-                    else
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, alpha * acc[i][j][e]), rC, (int)vo, 0, 0);
+                    } else {
+                        const float cv = alpha * acc[i][j][e];
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, cv), rC, (int)vo, 0, 0);
+                        if constexpr (OUT == 3) {
+                            // Adam on the finished core entry (Algorithm 1: moments, bias correction, D)
+                            float d = 0.0f;
+                            if (row < M && col < N) {
+                                const long long idx = (long long)row * ab.r + col;
+                                const float mm = sc.beta1 * ab.M[idx] + (1.0f - sc.beta1) * cv;
+                                const float vv = sc.beta2 * ab.Vm[idx] + (1.0f - sc.beta2) * (cv * cv);
+                                ab.M[idx] = mm;
+                                ab.Vm[idx] = vv;
+                                d = (mm * sc.inv_c1) / (sqrtf(vv * sc.inv_c2) + sc.eps);
+                                ab.D[idx] = d;
+                                if (!ab.DTf) ((unsigned short*)ab.DTb)[(long long)col * ab.ldt + row] = f32_to_bf16_bits(d);
+                            }
+                            dq[e & 3] = f32_to_bf16_bits(d);
+                            // D^T in fragment order: the four rows e & 3 = 0..3 of this lane are four
+                            // neighbouring bf16 of one record (r % 32 == 0, so they are all inside D)
+                            if ((e & 3) == 3 && ab.DTf && row < M && col < N) {
+                                const int rw = row - 3;
+                                const int ksteps = ab.r / 16;
+                                uint2 pk;
+                                pk.x = dq[0] | ((unsigned)dq[1] << 16);
+                                pk.y = dq[2] | ((unsigned)dq[3] << 16);
+                                *(uint2*)((unsigned short*)ab.DTf + (((long long)(col / 32) * ksteps + rw / 16) * 64 +
+                                                                     ((rw % 16) / 8) * 32 + col % 32) * 8 + rw % 8) = pk;
+                            }
+                        }
+                    }
                 }
         zero_acc();
         ck = 0;
@@ -537,6 +569,9 @@ constexpr nt_fn nt_persistent_fn() {
     if constexpr (OUT == 2) return nullptr;
     else return nt_gemm_persistent_kernel<TM, TN, WM, WN, BK, BF32, OUT, MINB>;
 }
+// out = 3 (fused Adam) exists as a persistent kernel only, for bf16 operands
+#define NT_ENTRY_ADAM(shape, TM, TN, WM, WN, BK, MINB) \
+    { shape, 0, 3, nullptr, nt_gemm_persistent_kernel<TM, TN, WM, WN, BK, false, 3, MINB>, 2 * (TM + TN) * (BK + 8) * 2, MINB }
 
 #define NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, bf32, out) \
     { shape, bf32, out, nt_gemm_kernel<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>, \
@@ -554,11 +589,12 @@ static const NtEntry kNt[] = {
     NT_SHAPE(NT_128x128_K32, 128, 128, 2, 2, 32, 3, 2), NT_SHAPE(NT_256x64_K32, 256, 64, 4, 1, 32, 3, 2),
     NT_SHAPE(NT_256x128_K32, 256, 128, 2, 2, 32, 2, 1), NT_SHAPE(NT_128x256_K32, 128, 256, 2, 2, 32, 2, 1),
     NT_SHAPE(NT_256x128, 256, 128, 2, 2, 64, 1, 1),
+    NT_ENTRY_ADAM(NT_64x64, 64, 64, 2, 2, 64, 4), NT_ENTRY_ADAM(NT_128x128, 128, 128, 2, 2, 64, 2),
 };
 
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream) {
     if (L.n_tiles <= 0) return hipSuccess;
-    const int out = v.out_bf16 ? 1 : (L.beta != 0.0f ? 2 : 0);
+    const int out = v.fused_adam ? 3 : (v.out_bf16 ? 1 : (L.beta != 0.0f ? 2 : 0));
     for (const NtEntry& e : kNt) {
         if (e.shape == v.shape && e.b_f32 == v.b_f32 && e.out == out) {
             const nt_fn fn = L.ranges ? e.persistent : e.fn;

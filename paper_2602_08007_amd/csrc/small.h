@@ -52,13 +52,20 @@ hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, 
 // Gacc R = diag(sigma) X^T (rows mutually orthogonal), from the symmetric eigenproblem of R R^T.
 // Outputs, for the r largest sigma in descending order: XrT (r x k fp32) rows x_j^T, GrT
 // (r x k fp32) rows of Gacc, and sigma (k fp32, optional, all k values descending).
-// Gacc and tmp are k x k doubles of work each.
+// Work: Gacc k x k doubles, tmp 2 k x k + 64 doubles, scratch 3 k x k doubles (launch_eig_svd only).
 struct JacobiBlock {
     double* R; double* Gacc; double* tmp;
     float* XrT; float* GrT; float* sigma;
     int k, r;
+    double* scratch;
 };
+// single kernel per matrix: tridiagonalization and implicit QL sweeps (any k up to 1024)
 hipError_t launch_jacobi(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
                          hipStream_t stream);
+// the same result as a chain of launches without long serial recurrences (bisection and
+// inverse iteration instead of QL, chip-wide fp64 MFMA products), k <= EIG_MAXK
+constexpr int EIG_MAXK = 544;
+hipError_t launch_eig_svd(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
+                          hipStream_t stream);
 
 }  // namespace tsr

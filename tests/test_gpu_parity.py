@@ -475,6 +475,40 @@ def test_bf16_plan_fused_lift_ranks(tsr, r, workers, rows16):
     plan.close()
 
 
+@pytest.mark.parametrize("r", [64, 96, 256])
+def test_bf16_plan_adam_in_core_epilogue(tsr, r, monkeypatch):
+    # With one worker and cores that U^T P writes whole (no k split), Adam runs in the epilogue
+    # of that GEMM.  A model-sized batch gets there by itself; these few ragged blocks are kept
+    # from splitting k by the tile-count knob.  r = 96 takes the unfused lift (row-major D^T).
+    monkeypatch.setenv("TSR_TUNE_UTP_TILES", "1")
+    shapes = [(r + 37, 2 * r + 64), (3 * r + 5, r), (r, r), (2 * r, 5 * r + 136)]
+    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, si.stream_key(641, r), guard_w=True)
+    plan = tsr.Plan(blocks, n_workers=1, precision=tsr.TSR_PREC_BF16)
+    assert plan.tsr_plan_kernel_path() == 1
+    state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
+    for t in (1, 2, 3):
+        plan.tsr_step_batched(t, lr=1e-3, wd=0.05)
+        torch.cuda.synchronize()
+        for b, h, s in zip(blocks, host, state):
+            W_before = s["W"].copy()
+            M_before, Vm_before = s["M"].copy(), s["Vm"].copy()
+            Cbar, D = orc.tsr_adam_step(s["W"], [g for g in h["G"]], h["U"], h["V"], s["M"], s["Vm"], t, lr=f32(1e-3),
+                                        wd=f32(0.05), beta1=B1, beta2=B2, eps=EPS)
+            assert rel_fro(b["C"], Cbar) < TOL_BF16
+            assert rel_fro(b["M"], s["M"]) < TOL_BF16 and rel_fro(b["Vm"], s["Vm"]) < 2 * TOL_BF16
+            # Adam itself, from the GPU's own core: moments and direction to fp32 accuracy
+            Mk, Vk = M_before.copy(), Vm_before.copy()
+            Dk = orc.adam_core(orc.f64(b["C"]), Mk, Vk, t, B1, B2, EPS)
+            assert rel_fro(b["M"], Mk) < 1e-5 and rel_fro(b["Vm"], Vk) < 1e-5 and rel_fro(b["D"], Dk) < 1e-4
+            W_k = orc.backproject_apply(W_before.copy(), h["U"], h["V"], orc.f64(b["D"]), f32(1e-3), f32(0.05))
+            assert rel_fro(b["W"], W_k) < TOL_BF16
+            assert rel_fro(orc.f64(b["W"]) - W_before, W_k - W_before) < 3e-2
+            s["W"][...] = orc.f64(b["W"])
+            s["M"][...] = orc.f64(b["M"]); s["Vm"][...] = orc.f64(b["Vm"])
+            assert guards_intact(h["W_full"], *b["W"].shape)
+    plan.close()
+
+
 def test_bf16_plan_follows_changed_bases(tsr):
     # the bf16 plan keeps bf16 copies of the bases: after the caller rewrites U, V and says
     # so, the next step must use the new ones
