@@ -261,7 +261,9 @@ void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool o
         g2.push_back(LogicalGemm{Xalt, Xalt, k, k, k, k, rows, b.S, k});
         q2.push_back(LogicalGemm{Xalt, b.Rinv, k, k, rows, k, k, X, k});
         op.chol1.push_back(CholBlock{b.S, b.Rinv, nullptr, b.R1, b.work, k});
-        op.chol2.push_back(CholBlock{b.S, b.Rinv, b.R1, b.Rtot, b.work, k});
+        // the second factor goes to Gacc (free until the small SVD); where the product of the two
+        // factors is needed, an fp64 MFMA GEMM forms it afterwards (run_refresh_back)
+        op.chol2.push_back(CholBlock{b.S, b.Rinv, nullptr, b.Gacc, b.work, k});
     }
     build_stage(op.gram1, variant(1, 1, 0, 2, 2), g1, ar);
     build_stage(op.q1, variant(0, 1, 0, 2, 2), q1, ar, 1);
@@ -317,7 +319,7 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Z, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
         uo.push_back(LogicalGemm{b.Y, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
         vo.push_back(LogicalGemm{b.Z, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
-        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r, b.eig});
+        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r, b.eig, b.R1});
     }
     for (int d = 0; d < 2; ++d) {
         build_stage(rp.sketch[d], variant(0, 1, d, 2, 2), sk[d], ar);
@@ -351,6 +353,7 @@ int run_refresh_back(const RefreshProgram& rp, bool grouped, Ctx& cx) {
         Timed timed(cx, TSR_PROF_JACOBI);
         int max_k = 0;
         for (const JacobiBlock& jb : rp.jac) max_k = std::max(max_k, jb.k);
+        TSR_HIP(launch_rtot_product(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
         static const bool chain = [] { const char* e = getenv("TSR_TUNE_EIG_CHAIN"); return !(e && e[0] == '0'); }();
         if (chain && max_k <= EIG_MAXK)
             TSR_HIP(launch_eig_svd(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));

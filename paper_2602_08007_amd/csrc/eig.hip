@@ -43,7 +43,8 @@ __device__ inline double eig_rcp(double x) {
 // workgroup of four waves a 64 x 64 tile; operands come straight from L2 (the matrices are a
 // few hundred KB), 16 k-values per round.
 // WHICH = 0: T = R R^T (R upper triangular: the sum for T[i][j] starts at max(i, j));
-// WHICH = 1: E^T R into the second half of tmp (the sum for column c ends at c).
+// WHICH = 1: E^T R into the second half of tmp (the sum for column c ends at c);
+// WHICH = 2: R = R2 R1 with R2 in Gacc, both upper triangular (the sum runs from i to j).
 template <int WHICH>
 __global__ __launch_bounds__(256) void eig_gemm_kernel(const JacobiBlock* table, const JacobiBlock single) {
     JacobiBlock jb = single;
@@ -57,12 +58,13 @@ __global__ __launch_bounds__(256) void eig_gemm_kernel(const JacobiBlock* table,
     const int m0 = tm * 64 + (wave >> 1) * 32, n0 = tn * 64 + (wave & 1) * 32;
     if (m0 >= k || n0 >= k) return;
     const double* __restrict__ A;
-    const double* __restrict__ B = blk->R;
+    const double* __restrict__ B = (WHICH == 2) ? blk->R1 : blk->R;
     double* __restrict__ C;
     long long sam, sak, sbk, sbn;
     int k_lo = 0, k_hi = k;
     if (WHICH == 0) { A = blk->R; sam = k; sak = 1; sbk = 1; sbn = k; C = blk->tmp; k_lo = max(m0, n0) & ~3; }
-    else { A = blk->Gacc; sam = 1; sak = k; sbk = k; sbn = 1; C = blk->tmp + (size_t)k * k; k_hi = min(k, n0 + 32); }
+    else if (WHICH == 1) { A = blk->Gacc; sam = 1; sak = k; sbk = k; sbn = 1; C = blk->tmp + (size_t)k * k; k_hi = min(k, n0 + 32); }
+    else { A = blk->Gacc; sam = k; sak = 1; sbk = k; sbn = 1; C = blk->R; k_lo = m0 & ~3; k_hi = min(k, n0 + 32); }
     const int li = lane & 15, lk = lane >> 4;
     d4 acc[2][2];
 #pragma unroll
@@ -545,6 +547,16 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_finish_kernel(const JacobiBlo
 }
 
 }  // namespace
+
+hipError_t launch_rtot_product(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
+                               hipStream_t stream) {
+    if (blocks <= 0 || max_k < 1) return hipSuccess;
+    JacobiBlock sb{};
+    if (single) sb = *single;
+    const int tiles = (max_k + 63) / 64;
+    hipLaunchKernelGGL(eig_gemm_kernel<2>, dim3(tiles * tiles, blocks), dim3(256), 0, stream, table_dev, sb);
+    return hipGetLastError();
+}
 
 hipError_t launch_eig_svd(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
                           hipStream_t stream) {

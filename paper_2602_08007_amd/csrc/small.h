@@ -58,7 +58,11 @@ struct JacobiBlock {
     float* XrT; float* GrT; float* sigma;
     int k, r;
     double* scratch;
+    const double* R1;
 };
+// R = R2 R1 for the two triangular factors of CholeskyQR2 (R2 in Gacc, result in R; fp64 MFMA)
+hipError_t launch_rtot_product(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
+                               hipStream_t stream);
 // single kernel per matrix: tridiagonalization and implicit QL sweeps (any k up to 1024)
 hipError_t launch_jacobi(const JacobiBlock* table_dev, const JacobiBlock* single, int blocks, int max_k,
                          hipStream_t stream);

@@ -248,7 +248,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
     const int ti = tid >> 5, tc = tid & 31;    // 32 x 32 thread grid
     __shared__ double Ld[CHB][CHB_P];
     __shared__ double Li[CHB][CHB_P];
-    extern __shared__ double Pn[];             // [(block rows - 1) * CHB][CHB_P]
+    extern __shared__ double Pn[];             // [block rows * CHB][CHB_P]
 
     for (int idx = tid; idx < k * k; idx += SMALL_THREADS) { A[idx] = (double)S[idx]; X[idx] = 0.0; }
     __syncthreads();
@@ -376,42 +376,39 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
         __syncthreads();
     }
 
-    // ---- off-diagonal blocks of X = L^-1, block row by block row:
-    //      X[I][J] = -Li_I * sum_{K=J}^{I-1} L[I][K] X[K][J]   for all J < I at once.
-    // The sums (32 rows x 32 I columns) are parked in the panel buffer as Pn[col][row].
+    // ---- off-diagonal blocks of X = L^-1, block column by block column (forward substitution
+    // with 32 right-hand sides):  X[I][J] = -Li_I * sum_{K=J}^{I-1} L[I][K] X[K][J].
+    // The block column of X stays in the panel buffer (block K - J at rows (K - J) * 32), each
+    // 32 x 32 block of L passes through LDS once per block column, thread (ti, tc) owns entry
+    // (ti, tc) of the block being formed.
     const int nblk = (k + CHB - 1) / CHB;
-    for (int I = 1; I < nblk; ++I) {
-        const int ib = min(CHB, k - I * CHB);
-        const int ncol = I * CHB;
-        Li[ti][tc] = (ti < ib && tc < ib) ? X[(size_t)(I * CHB + ti) * k + I * CHB + tc] : 0.0;
-        // thread (ti, tc): row ti of the block row, columns tc, tc + 32, ...
-        for (int col = tc; col < ncol; col += CHB) {
-            double sacc = 0.0;
-            if (ti < ib) {
-                const double* lrow = A + (size_t)(I * CHB + ti) * k;
-                const double* xcol = X + col;
-                double pa[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-                for (int c = (col / CHB) * CHB; c < ncol; c += 8) {      // both bounds are multiples of 32
-                    double xv[8], lv[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) { xv[u] = xcol[(size_t)(c + u) * k]; lv[u] = lrow[c + u]; }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) pa[u] += lv[u] * xv[u];
-                }
-                sacc = ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pa[4] + pa[5]) + (pa[6] + pa[7]));
-            }
-            Pn[col * CHB_P + ti] = sacc;
-        }
-        __syncthreads();
-        for (int col = tc; col < ncol; col += CHB) {
-            if (ti < ib) {
-                double v = 0.0;
+    for (int J = 0; J + 1 < nblk; ++J) {
+        Pn[ti * CHB_P + tc] = X[(size_t)(J * CHB + ti) * k + J * CHB + tc];      // J < nblk - 1: a full block
+        for (int I = J + 1; I < nblk; ++I) {
+            const int ib = min(CHB, k - I * CHB);
+            const bool rowok = ti < ib;
+            const double* lrow = A + (size_t)(I * CHB + min(ti, ib - 1)) * k;
+            double lcur = lrow[J * CHB + tc];
+            double acc = 0.0;
+            for (int K = J; K < I; ++K) {
+                Ld[ti][tc] = rowok ? lcur : 0.0;
+                __syncthreads();
+                if (K + 1 < I) lcur = lrow[(K + 1) * CHB + tc];
+                const double* xb = Pn + (size_t)(K - J) * CHB * CHB_P;
 #pragma unroll 8
-                for (int a2 = 0; a2 < CHB; ++a2) v += Li[ti][a2] * Pn[col * CHB_P + a2];     // Li lower: zero for a2 > ti
-                X[(size_t)(I * CHB + ti) * k + col] = -v;
+                for (int a = 0; a < CHB; ++a) acc += Ld[ti][a] * xb[a * CHB_P + tc];
+                __syncthreads();
             }
+            Ld[ti][tc] = acc;
+            Li[ti][tc] = (ti < ib && tc < ib) ? X[(size_t)(I * CHB + ti) * k + I * CHB + tc] : 0.0;
+            __syncthreads();
+            double v = 0.0;
+#pragma unroll 8
+            for (int a = 0; a < CHB; ++a) v += Li[ti][a] * Ld[a][tc];            // Li lower: zero for a > ti
+            Pn[((I - J) * CHB + ti) * CHB_P + tc] = -v;                          // rows past the matrix: zero
+            if (rowok) X[(size_t)(I * CHB + ti) * k + J * CHB + tc] = -v;
+            __syncthreads();
         }
-        __syncthreads();
     }
     __syncthreads();
 
@@ -473,14 +470,13 @@ hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, 
     CholBlock sb{};
     if (single) sb = *single;
     if (max_k <= CHB_MAXK) {
-        // panel rows below the first diagonal block, and (inverse phase) every column left of the
-        // last block row: both at most (number of block rows - 1) * CHB
-        const int pn_rows = (max_k > CHB) ? ((max_k + CHB - 1) / CHB - 1) * CHB : 1;
+        // panel rows below the first diagonal block; in the inverse phase one block column of X
+        const int pn_rows = ((max_k + CHB - 1) / CHB) * CHB;
         const int lds = pn_rows * CHB_P * 8;
         static thread_local bool configured = false;
         if (!configured) {
             hipError_t e = hipFuncSetAttribute((const void*)chol_inv_blocked_kernel,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, ((CHB_MAXK + CHB - 1) / CHB - 1) * CHB * CHB_P * 8);
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, ((CHB_MAXK + CHB - 1) / CHB) * CHB * CHB_P * 8);
             if (e != hipSuccess) return e;
             configured = true;
         }
