@@ -2,9 +2,10 @@
 // Algorithm 1's refresh step) as a chain of launches, for k <= EIG_MAXK:
 //   1. T = R R^T                        fp64 MFMA GEMM, 64 x 64 tiles over the whole chip
 //   2. per matrix, one workgroup:       Householder tridiagonalization of T (reflectors parked in
-//      the rows of T they cleared), eigenvalues by bisection (one per thread), eigenvectors of
-//      the tridiagonal matrix by inverse iteration (one per thread, pivoted LU of T - lambda I),
-//      Gram-Schmidt inside groups of numerically equal eigenvalues
+//      the rows of T they cleared); then, in a launch of its own, eigenvalues by bisection (one
+//      per thread), eigenvectors of the tridiagonal matrix by inverse iteration (one per
+//      thread, pivoted LU of T - lambda I), Gram-Schmidt inside groups of numerically equal
+//      eigenvalues
 //   3. E = H_0 H_1 ... Z                reflectors applied to 64 eigenvectors per workgroup, the
 //      vectors held in registers
 //   4. E^T R                            fp64 MFMA GEMM
@@ -129,19 +130,14 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
     const JacobiBlock* blk = &jb;
     const int k = blk->k;
     double* T = blk->tmp;                       // symmetric, full storage; afterwards the reflectors
-    double* Z = blk->tmp + (size_t)k * k;       // eigenvectors of the tridiagonal matrix, Z[i][j] = j-th vector
-    double* U0 = blk->scratch;                  // per thread j: reciprocal pivots, first and second
-    double* U1 = U0 + (size_t)k * k;            //   super-diagonal of the LU factor, entry [i][j]
-    double* U2 = U1 + (size_t)k * k;
     const int tid = threadIdx.x, nt = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
     __shared__ double s_d[EIG_MAXK];            // diagonal
     __shared__ double s_e[EIG_MAXK];            // sub-diagonal, s_e[i] couples i and i + 1
-    __shared__ double s_v[EIG_MAXK];            // Householder vector; later the eigenvalues
-    __shared__ double s_w[EIG_MAXK];            // work vector; later the squared sub-diagonal
+    __shared__ double s_v[EIG_MAXK];            // Householder vector
+    __shared__ double s_w[EIG_MAXK];            // work vector
     __shared__ double s_part[EIG_PARTS * EIG_MAXK];
     __shared__ double s_red[EIG_THREADS / 64];
-    __shared__ int s_first[EIG_MAXK];           // first member of the group an eigenvalue belongs to
 
     auto block_sum = [&](double v) -> double {
         v = eig_wave_sum(v);
@@ -150,16 +146,6 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
         __syncthreads();
         double t = 0.0;
         for (int i = 0; i < nw; ++i) t += s_red[i];
-        return t;
-    };
-    auto block_max = [&](double v) -> double {
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
-        __syncthreads();
-        if (lane == 0) s_red[wave] = v;
-        __syncthreads();
-        double t = s_red[0];
-        for (int i = 1; i < nw; ++i) t = fmax(t, s_red[i]);
         return t;
     };
 
@@ -227,6 +213,53 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
         s_d[k - 1] = T[(size_t)(k - 1) * k + k - 1];
         s_e[k - 1] = 0.0;
     }
+    __syncthreads();
+    // the tridiagonal matrix travels to the next launch behind the LU scratch
+    double* DE = blk->scratch + (size_t)3 * k * k;
+    for (int i = tid; i < k; i += nt) { DE[i] = s_d[i]; DE[k + i] = s_e[i]; }
+}
+
+// Eigenvalues and eigenvectors of the tridiagonal matrix (d, e) left by eig_tridiag_kernel.
+__global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBlock* table, const JacobiBlock single) {
+    JacobiBlock jb = single;
+    if (table) jb = table[blockIdx.x];
+    const JacobiBlock* blk = &jb;
+    const int k = blk->k;
+    double* Z = blk->tmp + (size_t)k * k;       // eigenvectors of the tridiagonal matrix, Z[i][j] = j-th vector
+    double* U0 = blk->scratch;                  // per thread j: reciprocal pivots, first and second
+    double* U1 = U0 + (size_t)k * k;            //   super-diagonal of the LU factor, entry [i][j]
+    double* U2 = U1 + (size_t)k * k;
+    const double* DE = blk->scratch + (size_t)3 * k * k;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+    __shared__ double s_d[EIG_MAXK];            // diagonal
+    __shared__ double s_e[EIG_MAXK];            // sub-diagonal, s_e[i] couples i and i + 1
+    __shared__ double s_v[EIG_MAXK];            // eigenvalues, ascending
+    __shared__ double s_w[EIG_MAXK];            // squared sub-diagonal
+    __shared__ double s_part[EIG_MAXK];         // Gram-Schmidt coefficients
+    __shared__ double s_red[EIG_THREADS / 64];
+    __shared__ int s_first[EIG_MAXK];           // first member of the group an eigenvalue belongs to
+
+    auto block_sum = [&](double v) -> double {
+        v = eig_wave_sum(v);
+        __syncthreads();
+        if (lane == 0) s_red[wave] = v;
+        __syncthreads();
+        double t = 0.0;
+        for (int i = 0; i < nw; ++i) t += s_red[i];
+        return t;
+    };
+    auto block_max = [&](double v) -> double {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+        __syncthreads();
+        if (lane == 0) s_red[wave] = v;
+        __syncthreads();
+        double t = s_red[0];
+        for (int i = 1; i < nw; ++i) t = fmax(t, s_red[i]);
+        return t;
+    };
+    for (int i = tid; i < k; i += nt) { s_d[i] = DE[i]; s_e[i] = DE[k + i]; }
     __syncthreads();
 
     // ---- eigenvalues by bisection on the Sturm count, eigenvalue j (ascending) on thread j
@@ -567,6 +600,7 @@ hipError_t launch_eig_svd(const JacobiBlock* table_dev, const JacobiBlock* singl
     const int tiles = (max_k + 63) / 64;
     hipLaunchKernelGGL(eig_gemm_kernel<0>, dim3(tiles * tiles, blocks), dim3(256), 0, stream, table_dev, sb);
     hipLaunchKernelGGL(eig_tridiag_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
+    hipLaunchKernelGGL(eig_vectors_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
     const dim3 bt_grid(tiles, blocks);
     if (max_k <= 32) hipLaunchKernelGGL((eig_backtransform_kernel<8, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);
     else if (max_k <= 96) hipLaunchKernelGGL((eig_backtransform_kernel<24, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);

@@ -233,6 +233,12 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_kernel(const CholBlock
 // register tiles, so the fp64 matrix in global memory is read and written once per block
 // column instead of once per column.  The inverse is assembled block row by block row from
 // the inverted diagonal blocks.
+__device__ inline double readlane_f64(double v, int lane) {      // lane: a compile-time constant
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
 constexpr int CHB = 32;
 constexpr int CHB_P = CHB + 1;
 constexpr int CHB_MAXK = 544;
@@ -246,11 +252,15 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
     double* X = blk->work + (size_t)k * k;     // X = L^-1 (lower)
     const int tid = threadIdx.x;
     const int ti = tid >> 5, tc = tid & 31;    // 32 x 32 thread grid
+    typedef double d4_t __attribute__((ext_vector_type(4)));
+    const int wv = tid >> 6, li16 = tid & 15, lk4 = (tid & 63) >> 4;      // wave; MFMA lane coordinates
     __shared__ double Ld[CHB][CHB_P];
     __shared__ double Li[CHB][CHB_P];
+    __shared__ double s_invd[CHB];             // reciprocal diagonal of the current diagonal block
     extern __shared__ double Pn[];             // [block rows * CHB][CHB_P]
 
-    for (int idx = tid; idx < k * k; idx += SMALL_THREADS) { A[idx] = (double)S[idx]; X[idx] = 0.0; }
+    // (X is written where it is read: diagonal blocks whole, the blocks below them in the inverse phase)
+    for (int idx = tid; idx < k * k; idx += SMALL_THREADS) A[idx] = (double)S[idx];
     __syncthreads();
 
     for (int J = 0; J < k; J += CHB) {
@@ -258,9 +268,10 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
         // ---- diagonal block -> LDS (identity padding), unblocked factorization
         Ld[ti][tc] = (ti < jb && tc < jb) ? ((tc <= ti) ? A[(size_t)(J + ti) * k + J + tc] : 0.0) : (ti == tc ? 1.0 : 0.0);
         __syncthreads();
-        // One wave factors the 32 x 32 block: lane i owns row i in registers, column j of L is
-        // final after step j and is published through LDS for the later steps (LDS operations of
-        // one wave complete in order, so no workgroup barrier is needed inside the loop).
+        // One wave factors the 32 x 32 block, right-looking: lane i owns row i in registers; at
+        // step j the pivot is read from lane j, and every lane updates the rest of its row with
+        // the entries of column j read from their lanes (independent multiply-adds, no serial
+        // chain beyond the pivot's reciprocal square root).
         if (tid < 64) {
             const int i = tid & 31;
             const bool act = tid < CHB;
@@ -270,32 +281,34 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
             const double sdiag = (i < jb) ? (double)S[(size_t)(J + i) * k + J + i] : 1.0;
 #pragma unroll
             for (int j = 0; j < CHB; ++j) {
-                double v = arow[j];
-#pragma unroll
-                for (int c = 0; c < j; ++c) v -= arow[c] * Ld[j][c];
-                const double piv = __shfl(v, j, 64);
-                const double s0 = __shfl(sdiag, j, 64);
+                const double piv = readlane_f64(arow[j], j);
+                const double s0 = readlane_f64(sdiag, j);
                 const bool ok = (piv > 0.0) && (piv > tol * s0);
-                const double d = ok ? sqrt(piv) : 0.0;
-                const double invd = ok ? 1.0 / d : 0.0;
-                arow[j] = (i == j) ? d : v * invd;
-                if (act && i >= j) Ld[i][j] = arow[j];
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                __builtin_amdgcn_wave_barrier();
+                const double pp = ok ? piv : 1.0;
+                double rinv = __builtin_amdgcn_rsq(pp);
+                const double hh = 0.5 * pp;
+                rinv = rinv * (1.5 - hh * rinv * rinv);
+                rinv = rinv * (1.5 - hh * rinv * rinv);
+                const double invd = ok ? rinv : 0.0;
+                const double lij = (i > j) ? arow[j] * invd : ((i == j) ? pp * invd : 0.0);
+                arow[j] = lij;
+                if (act) { if (i >= j) Ld[i][j] = lij; if (i == j) s_invd[j] = invd; }
+#pragma unroll
+                for (int c = j + 1; c < CHB; ++c) arow[c] -= lij * readlane_f64(lij, c);
             }
         }
         __syncthreads();
-        // ---- inverse of the diagonal block (dropped pivots: zero row and column)
+        // ---- inverse of the diagonal block (dropped pivots: zero row and column); column c on
+        // lane c, four partial sums per entry
         if (tid < CHB) {
-            const int c = tid;                                // column c of the inverse, in registers
+            const int c = tid;
             double xc[CHB];
 #pragma unroll
             for (int i = 0; i < CHB; ++i) {
-                double sacc = (i == c) ? 1.0 : 0.0;
+                double sa[4] = {(i == c) ? 1.0 : 0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                for (int j = 0; j < i; ++j) sacc -= Ld[i][j] * xc[j];
-                const double d = Ld[i][i];
-                xc[i] = (d != 0.0) ? sacc / d : 0.0;
+                for (int j = 0; j < i; ++j) sa[j & 3] -= Ld[i][j] * xc[j];
+                xc[i] = ((sa[0] + sa[1]) + (sa[2] + sa[3])) * s_invd[i];
                 Li[i][c] = xc[i];
             }
         }
@@ -304,73 +317,59 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
             A[(size_t)(J + ti) * k + J + tc] = (tc <= ti) ? Ld[ti][tc] : 0.0;
             X[(size_t)(J + ti) * k + J + tc] = (tc <= ti) ? Li[ti][tc] : 0.0;
         }
-        // ---- panel: rows below, P = A[rows, J..J+jb) Li^T
+        // ---- panel: rows below, P = A[rows, J..J+jb) Li^T, on fp64 MFMAs (lane l supplies
+        // A[l % 16][l / 16] and B[l / 16][l % 16], receives D[4 v + l / 16][l % 16]): 16-row
+        // tiles dealt to the waves, the rows of A straight from global memory, Li^T from LDS.
+        // P goes back to A and stays in the panel buffer (rows past the matrix: zeros).
         const int r0 = J + jb;
         const int nr = k - r0;
-        for (int idx = tid; idx < nr * CHB; idx += SMALL_THREADS) {
-            const int i = idx >> 5, c = idx & 31;
-            Pn[i * CHB_P + c] = (c < jb) ? A[(size_t)(r0 + i) * k + J + c] : 0.0;
-        }
-        __syncthreads();
-        {
-            constexpr int MAXPASS = (CHB_MAXK + CHB - 1) / CHB;
-            double res[MAXPASS];
+        const int nrt = (nr + 15) >> 4;
+        for (int t = wv; t < nrt; t += SMALL_THREADS / 64) {       // one wave reads and rewrites its 16 rows
+            const int i0 = t * 16;
+            const int row = i0 + li16;
+            const double* arow_g = A + (size_t)(r0 + min(row, nr - 1)) * k + J;
+            d4_t acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+            double a[8];
 #pragma unroll
-            for (int p = 0; p < MAXPASS; ++p) {
-                const int i = p * CHB + ti;
-                double acc = 0.0;
-                if (i < nr) {
-#pragma unroll 8
-                    for (int j = 0; j < CHB; ++j) acc += Pn[i * CHB_P + j] * Li[tc][j];   // Li[tc][j] = 0 for j > tc
-                }
-                res[p] = acc;
+            for (int q = 0; q < 8; ++q) {
+                const int c = 4 * q + lk4;
+                a[q] = (row < nr && c < jb) ? arow_g[min(c, jb - 1)] : 0.0;
             }
-            __syncthreads();
 #pragma unroll
-            for (int p = 0; p < MAXPASS; ++p) {
-                const int i = p * CHB + ti;
-                if (i < nr) {
-                    Pn[i * CHB_P + tc] = res[p];
-                    if (tc < jb) A[(size_t)(r0 + i) * k + J + tc] = res[p];
-                }
+            for (int q = 0; q < 8; ++q) {
+                acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], Li[li16][4 * q + lk4], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], Li[16 + li16][4 * q + lk4], acc1, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + 4 * v + lk4;
+                Pn[i * CHB_P + li16] = acc0[v];
+                Pn[i * CHB_P + 16 + li16] = acc1[v];
+                if (i < nr && li16 < jb) A[(size_t)(r0 + i) * k + J + li16] = acc0[v];
+                if (i < nr && 16 + li16 < jb) A[(size_t)(r0 + i) * k + J + 16 + li16] = acc1[v];
             }
         }
         __syncthreads();
-        // ---- trailing update, lower triangle, 4 x 4 tiles: A[i][c] -= sum_j P[i][j] P[c][j]
+        // ---- trailing update, lower triangle by 16 x 16 tiles: A[i][c] -= sum_j P[i][j] P[c][j]
         {
-            const int T = (nr + 3) >> 2;
-            const int ntile = T * (T + 1) / 2;
-            for (int q = tid; q < ntile; q += SMALL_THREADS) {
-                int tr = (int)((sqrt(8.0 * (double)q + 1.0) - 1.0) * 0.5);
+            const int ntile = nrt * (nrt + 1) / 2;
+            for (int q = wv; q < ntile; q += SMALL_THREADS / 64) {
+                int tr = (int)((sqrtf(8.0f * (float)q + 1.0f) - 1.0f) * 0.5f);
                 while ((tr + 1) * (tr + 2) / 2 <= q) ++tr;
                 while (tr * (tr + 1) / 2 > q) --tr;
                 const int tcx = q - tr * (tr + 1) / 2;
-                const int i0 = tr * 4, c0 = tcx * 4;
-                double acc[4][4];
+                const int i0 = tr * 16, c0 = tcx * 16;
+                const double* pa = Pn + (size_t)(i0 + li16) * CHB_P + lk4;
+                const double* pb = Pn + (size_t)(c0 + li16) * CHB_P + lk4;
+                d4_t acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 8; ++u)
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(pa[4 * u], pb[4 * u], acc, 0, 0, 0);
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
-#pragma unroll 4
-                for (int j = 0; j < CHB; ++j) {
-                    double pi[4], pc[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        pi[u] = (i0 + u < nr) ? Pn[(i0 + u) * CHB_P + j] : 0.0;
-                        pc[u] = (c0 + u < nr) ? Pn[(c0 + u) * CHB_P + j] : 0.0;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) acc[u][v] += pi[u] * pc[v];
+                for (int v = 0; v < 4; ++v) {
+                    const int i = i0 + 4 * v + lk4, c = c0 + li16;
+                    if (i < nr && c <= i) A[(size_t)(r0 + i) * k + r0 + c] -= acc[v];
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int i = i0 + u, c = c0 + v;
-                        if (i < nr && c <= i) A[(size_t)(r0 + i) * k + r0 + c] -= acc[u][v];
-                    }
             }
         }
         __syncthreads();
@@ -378,36 +377,62 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
 
     // ---- off-diagonal blocks of X = L^-1, block column by block column (forward substitution
     // with 32 right-hand sides):  X[I][J] = -Li_I * sum_{K=J}^{I-1} L[I][K] X[K][J].
-    // The block column of X stays in the panel buffer (block K - J at rows (K - J) * 32), each
-    // 32 x 32 block of L passes through LDS once per block column, thread (ti, tc) owns entry
-    // (ti, tc) of the block being formed.
+    // The block column of X stays in the panel buffer (block K - J at rows (K - J) * 32); the
+    // 32 x 32 products run on fp64 MFMAs (v_mfma_f64_16x16x4: lane l supplies A[l % 16][l / 16]
+    // and B[l / 16][l % 16], receives D[4 v + l / 16][l % 16]), one 16 x 16 tile on each of
+    // the first four waves, the blocks of L straight from global memory.
     const int nblk = (k + CHB - 1) / CHB;
-    for (int J = 0; J + 1 < nblk; ++J) {
-        Pn[ti * CHB_P + tc] = X[(size_t)(J * CHB + ti) * k + J * CHB + tc];      // J < nblk - 1: a full block
-        for (int I = J + 1; I < nblk; ++I) {
-            const int ib = min(CHB, k - I * CHB);
-            const bool rowok = ti < ib;
-            const double* lrow = A + (size_t)(I * CHB + min(ti, ib - 1)) * k;
-            double lcur = lrow[J * CHB + tc];
-            double acc = 0.0;
-            for (int K = J; K < I; ++K) {
-                Ld[ti][tc] = rowok ? lcur : 0.0;
+    {
+        const int tr = (wv >> 1) & 1, tcb = wv & 1;
+        for (int J = 0; J + 1 < nblk; ++J) {
+            Pn[ti * CHB_P + tc] = X[(size_t)(J * CHB + ti) * k + J * CHB + tc];      // J < nblk - 1: a full block
+            __syncthreads();
+            for (int I = J + 1; I < nblk; ++I) {
+                const int ib = min(CHB, k - I * CHB);
+                const int lr = 16 * tr + li16;                 // this lane's row of the A operand
+                const bool rok = lr < ib;
+                if (wv < 4) {
+                    d4_t acc = {0.0, 0.0, 0.0, 0.0};
+                    const double* lrow = A + (size_t)(I * CHB + min(lr, ib - 1)) * k + lk4;
+                    double an[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) an[q] = lrow[J * CHB + 4 * q];
+                    for (int K = J; K < I; ++K) {
+                        double a[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) a[q] = rok ? an[q] : 0.0;
+                        if (K + 1 < I) {
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) an[q] = lrow[(K + 1) * CHB + 4 * q];
+                        }
+                        const double* xb = Pn + (size_t)((K - J) * CHB + lk4) * CHB_P + 16 * tcb + li16;
+#pragma unroll
+                        for (int q = 0; q < 8; ++q)
+                            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], xb[4 * q * CHB_P], acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Ld[16 * tr + 4 * v + lk4][16 * tcb + li16] = acc[v];
+                }
                 __syncthreads();
-                if (K + 1 < I) lcur = lrow[(K + 1) * CHB + tc];
-                const double* xb = Pn + (size_t)(K - J) * CHB * CHB_P;
-#pragma unroll 8
-                for (int a = 0; a < CHB; ++a) acc += Ld[ti][a] * xb[a * CHB_P + tc];
+                if (wv < 4) {
+                    d4_t acc = {0.0, 0.0, 0.0, 0.0};
+                    const double* xd = X + (size_t)(I * CHB + min(lr, ib - 1)) * k + I * CHB;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const int c = 4 * q + lk4;
+                        const double a = (rok && c < ib) ? xd[min(c, ib - 1)] : 0.0;     // Li_I, lower triangular
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Ld[c][16 * tcb + li16], acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int r = 16 * tr + 4 * v + lk4, cc = 16 * tcb + li16;
+                        const double val = -acc[v];
+                        Pn[((I - J) * CHB + r) * CHB_P + cc] = val;                      // rows past the matrix: zero
+                        if (r < ib) X[(size_t)(I * CHB + r) * k + J * CHB + cc] = val;
+                    }
+                }
                 __syncthreads();
             }
-            Ld[ti][tc] = acc;
-            Li[ti][tc] = (ti < ib && tc < ib) ? X[(size_t)(I * CHB + ti) * k + I * CHB + tc] : 0.0;
-            __syncthreads();
-            double v = 0.0;
-#pragma unroll 8
-            for (int a = 0; a < CHB; ++a) v += Li[ti][a] * Ld[a][tc];            // Li lower: zero for a > ti
-            Pn[((I - J) * CHB + ti) * CHB_P + tc] = -v;                          // rows past the matrix: zero
-            if (rowok) X[(size_t)(I * CHB + ti) * k + J * CHB + tc] = -v;
-            __syncthreads();
         }
     }
     __syncthreads();

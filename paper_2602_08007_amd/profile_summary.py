@@ -28,7 +28,7 @@ def _find(d, suffix):
 
 
 def _short(name):
-    name = name.replace("void tsr::", "").replace("tsr::", "")
+    name = name.replace("(anonymous namespace)::", "").replace("void tsr::", "").replace("tsr::", "")
     return name.split("(")[0]
 
 
