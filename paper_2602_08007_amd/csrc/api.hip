@@ -55,8 +55,10 @@ struct GemmStage {
 
 // Decide k-splits, carve partial buffers from `ar`, and list the tiles.
 // want_tiles: keep splitting k while the launch has fewer tiles than this.
+// lower_only: the outputs are symmetric and only tiles on or below the diagonal are computed
+// (the rest of the output is left unwritten).
 void build_stage(GemmStage& st, const GemmVariant& var, const std::vector<LogicalGemm>& gemms, Arena& ar,
-                 int want_tiles = 512) {
+                 int want_tiles = 512, bool lower_only = false) {
     st = GemmStage{};
     st.var = var;
     if (gemms.empty()) return;
@@ -114,7 +116,8 @@ void build_stage(GemmStage& st, const GemmVariant& var, const std::vector<Logica
             const int tmn = ceil_div(g.M, GEMM_BM), tnn = ceil_div(g.N, GEMM_BN);
             for (int ks = 0; ks < ksplit[j]; ++ks)
                 for (int tm = 0; tm < tmn; ++tm)
-                    for (int tn = 0; tn < tnn; ++tn) st.tiles.push_back(GemmTile{(int)j, tm, tn, ks});
+                    for (int tn = 0; tn < tnn; ++tn)
+                        if (!lower_only || tn <= tm) st.tiles.push_back(GemmTile{(int)j, tm, tn, ks});
             st.tiles_m = tmn; st.tiles_n = tnn; st.ksplit = ksplit[j];
         }
         i = e;
@@ -132,6 +135,7 @@ int run_stage(const GemmStage& st, bool grouped, float alpha, float beta, Ctx& c
     } else {
         L.single = st.probs[0];
         L.tiles_m = st.tiles_m; L.tiles_n = st.tiles_n; L.ksplit = st.ksplit;
+        L.n_tiles = st.tiles_m * st.tiles_n * st.ksplit;       // the block index is decoded over the full grid
     }
     if (st.direct) {
         L.alpha = alpha; L.beta = beta;
@@ -265,9 +269,10 @@ void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool o
         // factors is needed, an fp64 MFMA GEMM forms it afterwards (run_refresh_back)
         op.chol2.push_back(CholBlock{b.S, b.Rinv, nullptr, b.Gacc, b.work, k});
     }
-    build_stage(op.gram1, variant(1, 1, 0, 2, 2), g1, ar);
+    // the Cholesky kernels read the lower triangle of the Gram matrix only
+    build_stage(op.gram1, variant(1, 1, 0, 2, 2), g1, ar, 512, true);
     build_stage(op.q1, variant(0, 1, 0, 2, 2), q1, ar, 1);
-    build_stage(op.gram2, variant(1, 1, 0, 3, 3), g2, ar);
+    build_stage(op.gram2, variant(1, 1, 0, 3, 3), g2, ar, 512, true);
     build_stage(op.q2, variant(0, 1, 0, 3, 3), q2, ar, 1);
 }
 
