@@ -459,14 +459,12 @@ __global__ __launch_bounds__(64 * WAVES) void eig_backtransform_kernel(const Jac
     const int k = blk->k;
     const int c0 = blockIdx.x * 64;
     if (c0 >= k) return;
-    // the reflectors (written by the previous launch, constant here) are read through a
-    // constant-address-space pointer: their addresses are uniform over a wave, which lets them
-    // travel through the scalar data path
-    typedef const double __attribute__((address_space(4))) gdouble;
+    typedef const double __attribute__((address_space(1))) gdouble;
     typedef double d8 __attribute__((ext_vector_type(8)));
     typedef d8 __attribute__((aligned(8))) d8u;
-    typedef const d8u __attribute__((address_space(4))) cd8u;
+    typedef const d8u __attribute__((address_space(1))) cd8u;
     static_assert(EPT % 8 == 0, "rows per wave come in chunks of eight");
+    // the reflector entries have wave-uniform addresses: they travel through the scalar data path
     const gdouble* __restrict__ T = (const gdouble*)blk->tmp;
     const double* __restrict__ Z = blk->tmp + (size_t)k * k;
     double* __restrict__ E = blk->Gacc;
@@ -495,7 +493,11 @@ __global__ __launch_bounds__(64 * WAVES) void eig_backtransform_kernel(const Jac
 #pragma unroll
             for (int c = 0; c < EPT / 8; ++c) {
                 const int ib = i0 + 8 * c;
-                if (ib + 7 > j && ib < k) {
+                if (ib > j && ib + 7 < k) {                 // whole chunk inside the reflector
+                    const d8u v8 = *(const cd8u*)(vrow + ib);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) part += v8[u] * x[8 * c + u];
+                } else if (ib + 7 > j && ib < k) {
                     const d8u v8 = *(const cd8u*)(vrow + ib);
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
@@ -515,7 +517,11 @@ __global__ __launch_bounds__(64 * WAVES) void eig_backtransform_kernel(const Jac
 #pragma unroll
             for (int c = 0; c < EPT / 8; ++c) {
                 const int ib = i0 + 8 * c;
-                if (ib + 7 > j && ib < k) {
+                if (ib > j && ib + 7 < k) {
+                    const d8u v8 = *(const cd8u*)(vrow + ib);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) x[8 * c + u] -= s * v8[u];
+                } else if (ib + 7 > j && ib < k) {
                     const d8u v8 = *(const cd8u*)(vrow + ib);
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
