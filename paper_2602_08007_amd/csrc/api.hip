@@ -294,6 +294,8 @@ int run_orth(const OrthProgram& op, bool grouped, Ctx& cx) {
     return run_stage(op.q2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM);
 }
 
+void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena& ar);
+
 // Carves every refresh buffer from `ar` and builds all stages.  Omega pointers may be null
 // at build time (they are patched in before the launch).
 void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, const float* const* omegas, int p,
@@ -314,6 +316,11 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         b.eig = (b.k <= EIG_MAXK) ? ar.take<double>(3 * k * k + 2 * k) : nullptr;
         rp.blocks.push_back(b);
     }
+    build_refresh_stages(rp, omegas, ar);
+}
+
+// Stages and tables of the refresh of rp.blocks (whose buffers are already carved).
+void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena& ar) {
     std::vector<LogicalGemm> sk[2], gtq[2], gq[2], uo, vo;
     rp.jac.clear();
     for (size_t i = 0; i < rp.blocks.size(); ++i) {
@@ -384,6 +391,30 @@ int check_refresh_shape(int m, int n, int r, int p) {
 
 }  // namespace
 
+void upload_refresh(RefreshProgram& rp, Arena& ar, Uploader& up) {
+    for (int d = 0; d < 2; ++d) {
+        upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gq[d], ar, up);
+    }
+    for (OrthProgram* op : {&rp.orthY, &rp.orthZ}) {
+        upload_stage(op->gram1, ar, up); upload_stage(op->q1, ar, up);
+        upload_stage(op->gram2, ar, up); upload_stage(op->q2, ar, up);
+        op->d_chol1 = up.put(op->chol1, ar); op->d_chol2 = up.put(op->chol2, ar);
+    }
+    rp.d_jac = up.put(rp.jac, ar);
+    upload_stage(rp.uout, ar, up); upload_stage(rp.vout, ar, up);
+}
+
+// Number of block groups the batched refresh runs side by side, each on a stream of its own:
+// the factorization kernels keep one workgroup per matrix busy for milliseconds, the GEMM
+// stages of the other groups fill the rest of the chip meanwhile.
+int refresh_group_count(int blocks) {
+    const char* e = getenv("TSR_TUNE_REFRESH_GROUPS");
+    int g = e ? atoi(e) : 3;
+    g = std::max(1, std::min(g, 8));
+    while (g > 1 && blocks / g < 4) --g;
+    return g;
+}
+
 // ====================================================================== C ABI
 struct tsr_plan {
     std::vector<BlockView> blocks;
@@ -396,10 +427,22 @@ struct tsr_plan {
     bool force_generic = false;   // sizing only: measure the generic programs
     std::vector<CoreBlock> cores; const CoreBlock* d_cores = nullptr; long long max_core = 0;
     RefreshProgram refresh;
+    // the same refresh cut into groups of blocks (sharing the buffers of `refresh`), run on
+    // side streams when no stage timing is asked for
+    std::vector<RefreshProgram> groups;
+    std::vector<std::vector<int>> group_blocks;     // indices into refresh.blocks
+    std::vector<hipStream_t> side;                  // groups 1.. (group 0 runs on the caller's stream)
+    std::vector<hipEvent_t> joined;
+    hipEvent_t fork = nullptr;
     char* ws = nullptr;
     Uploader up;
     Prof prof;
-    ~tsr_plan() { prof.clear(); }
+    ~tsr_plan() {
+        prof.clear();
+        for (hipStream_t st : side) (void)hipStreamDestroy(st);
+        for (hipEvent_t ev : joined) (void)hipEventDestroy(ev);
+        if (fork) (void)hipEventDestroy(fork);
+    }
 };
 
 extern "C" {
@@ -707,7 +750,34 @@ static void build_plan(tsr_plan& pl, Arena& ar) {
         pl.cores.push_back(CoreBlock{b.C, b.M, b.Vm, b.D, cnt});
         pl.max_core = std::max(pl.max_core, cnt);
     }
-    if (pl.with_refresh) build_refresh(pl.refresh, pl.blocks, nullptr, pl.p, nullptr, ar);
+    pl.groups.clear(); pl.group_blocks.clear();
+    if (pl.with_refresh) {
+        build_refresh(pl.refresh, pl.blocks, nullptr, pl.p, nullptr, ar);
+        const int ng = refresh_group_count((int)pl.blocks.size());
+        if (ng > 1) {
+            // heaviest blocks first onto the lightest group
+            std::vector<int> order(pl.blocks.size());
+            for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+            std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+                return (long long)pl.blocks[a].m * pl.blocks[a].n > (long long)pl.blocks[b].m * pl.blocks[b].n;
+            });
+            pl.group_blocks.assign(ng, {});
+            std::vector<long long> load(ng, 0);
+            for (int bi : order) {
+                int best = 0;
+                for (int g = 1; g < ng; ++g) if (load[g] < load[best]) best = g;
+                pl.group_blocks[best].push_back(bi);
+                load[best] += (long long)pl.blocks[bi].m * pl.blocks[bi].n;
+            }
+            pl.groups.resize(ng);
+            for (int g = 0; g < ng; ++g) {
+                std::sort(pl.group_blocks[g].begin(), pl.group_blocks[g].end());
+                pl.groups[g].blocks.clear();
+                for (int bi : pl.group_blocks[g]) pl.groups[g].blocks.push_back(pl.refresh.blocks[bi]);
+                build_refresh_stages(pl.groups[g], nullptr, ar);
+            }
+        }
+    }
     // device tables
     Uploader& up = pl.up;
     pl.d_cores = up.put(pl.cores, ar);
@@ -720,17 +790,8 @@ static void build_plan(tsr_plan& pl, Arena& ar) {
         upload_stage(pl.lift.tvt, ar, up);
     }
     if (pl.with_refresh) {
-        RefreshProgram& rp = pl.refresh;
-        for (int d = 0; d < 2; ++d) {
-            upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gq[d], ar, up);
-        }
-        for (OrthProgram* op : {&rp.orthY, &rp.orthZ}) {
-            upload_stage(op->gram1, ar, up); upload_stage(op->q1, ar, up);
-            upload_stage(op->gram2, ar, up); upload_stage(op->q2, ar, up);
-            op->d_chol1 = up.put(op->chol1, ar); op->d_chol2 = up.put(op->chol2, ar);
-        }
-        rp.d_jac = up.put(rp.jac, ar);
-        upload_stage(rp.uout, ar, up); upload_stage(rp.vout, ar, up);
+        upload_refresh(pl.refresh, ar, up);
+        for (RefreshProgram& g : pl.groups) upload_refresh(g, ar, up);
     }
 }
 
@@ -779,6 +840,18 @@ int tsr_plan_create(const tsr_matrix_desc* descs, int count, int n_workers, int 
         if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
         if (e != hipSuccess) { delete pl; return hip_fail(e); }
     }
+    if (pl->groups.size() > 1) {
+        // side streams at the default priority; without them the refresh runs as one program
+        bool ok = hipEventCreateWithFlags(&pl->fork, hipEventDisableTiming) == hipSuccess;
+        for (size_t g = 1; ok && g < pl->groups.size(); ++g) {
+            hipStream_t sg = nullptr; hipEvent_t ev = nullptr;
+            ok = hipStreamCreateWithFlags(&sg, hipStreamNonBlocking) == hipSuccess;
+            if (ok) pl->side.push_back(sg);
+            ok = ok && hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess;
+            if (ev) pl->joined.push_back(ev);
+        }
+        if (!ok) { delete pl; return hip_fail(hipGetLastError()); }
+    }
     *plan_out = pl;
     return TSR_OK;
 }
@@ -799,17 +872,13 @@ int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream) {
     return run_lift(plan->lift, true, h->lr, h->wd, h->scale, cx);
 }
 
-int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void* stream) {
-    if (!plan || !Omegas || q < 0) return TSR_INVALID_ARG;
-    if (!plan->with_refresh) return TSR_INVALID_ARG;
-    RefreshProgram& rp = plan->refresh;
-    hipStream_t st = (hipStream_t)stream;
-    // patch the sketch stage's B pointers with this call's Omegas and re-upload those tables
+// Points the sketch stage of `rp` at this call's Omegas (om[i] belongs to rp.blocks[i]) and
+// refreshes the device copy of those tables on `st`.
+static int patch_omegas(RefreshProgram& rp, const std::vector<const float*>& om, hipStream_t st) {
     size_t cursor[2] = {0, 0};
     for (size_t i = 0; i < rp.blocks.size(); ++i) {
-        if (!Omegas[i]) return TSR_INVALID_ARG;
         const int d = rp.blocks[i].g_dtype;
-        rp.sketch[d].probs[cursor[d]++].B = Omegas[i];
+        rp.sketch[d].probs[cursor[d]++].B = om[i];
     }
     for (int d = 0; d < 2; ++d) {
         GemmStage& sgm = rp.sketch[d];
@@ -817,10 +886,53 @@ int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void*
         TSR_HIP(hipMemcpyAsync((void*)sgm.d_probs, sgm.probs.data(), sgm.probs.size() * sizeof(GemmProblem),
                                hipMemcpyHostToDevice, st));
     }
+    return TSR_OK;
+}
+
+int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void* stream) {
+    if (!plan || !Omegas || q < 0) return TSR_INVALID_ARG;
+    if (!plan->with_refresh) return TSR_INVALID_ARG;
+    RefreshProgram& rp = plan->refresh;
+    hipStream_t st = (hipStream_t)stream;
+    for (size_t i = 0; i < rp.blocks.size(); ++i) if (!Omegas[i]) return TSR_INVALID_ARG;
+    // with stage timing on, or with a single group, the whole refresh runs as one program
+    const bool side_by_side = plan->groups.size() > 1 && !plan->prof.on && plan->side.size() + 1 == plan->groups.size();
+    std::vector<const float*> om;
+    if (side_by_side) {
+        for (size_t g = 0; g < plan->groups.size(); ++g) {
+            om.clear();
+            for (int bi : plan->group_blocks[g]) om.push_back(Omegas[bi]);
+            TSR_TRY(patch_omegas(plan->groups[g], om, st));
+        }
+    } else {
+        om.assign(Omegas, Omegas + rp.blocks.size());
+        TSR_TRY(patch_omegas(rp, om, st));
+    }
     TSR_HIP(hipStreamSynchronize(st));
-    Ctx cx{st, &plan->prof};
     plan->fast.bases_dirty = true;
-    return run_refresh(rp, true, q, cx);
+    if (!side_by_side) {
+        Ctx cx{st, &plan->prof};
+        return run_refresh(rp, true, q, cx);
+    }
+    // fork: the side streams start after everything queued on the caller's stream so far
+    TSR_HIP(hipEventRecord(plan->fork, st));
+    int rc = TSR_OK;
+    for (size_t g = 1; g < plan->groups.size(); ++g) {
+        hipStream_t sg = plan->side[g - 1];
+        TSR_HIP(hipStreamWaitEvent(sg, plan->fork, 0));
+        Ctx cg{sg, nullptr};
+        const int r = run_refresh(plan->groups[g], true, q, cg);
+        if (rc == TSR_OK) rc = r;
+        TSR_HIP(hipEventRecord(plan->joined[g - 1], sg));
+    }
+    {
+        Ctx c0{st, nullptr};
+        const int r = run_refresh(plan->groups[0], true, q, c0);
+        if (rc == TSR_OK) rc = r;
+    }
+    // join: the caller's stream continues when every group is done
+    for (size_t g = 1; g < plan->groups.size(); ++g) TSR_HIP(hipStreamWaitEvent(st, plan->joined[g - 1], 0));
+    return rc;
 }
 
 int tsr_plan_kernel_path(const tsr_plan* plan) { return plan ? (plan->use_fast ? 1 : 0) : -1; }
