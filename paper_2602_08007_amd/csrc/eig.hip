@@ -134,8 +134,10 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
     const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
     __shared__ double s_d[EIG_MAXK];            // diagonal
     __shared__ double s_e[EIG_MAXK];            // sub-diagonal, s_e[i] couples i and i + 1
-    __shared__ double s_v[EIG_MAXK];            // Householder vector
-    __shared__ double s_w[EIG_MAXK];            // work vector
+    __shared__ double s_v[EIG_MAXK];            // Householder vector v and companion w of two
+    __shared__ double s_w[EIG_MAXK];            //   consecutive reflectors (pending / being formed)
+    __shared__ double s_vn[EIG_MAXK];
+    __shared__ double s_wn[EIG_MAXK];
     __shared__ double s_part[EIG_PARTS * EIG_MAXK];
     __shared__ double s_red[EIG_THREADS / 64];
 
@@ -149,68 +151,98 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
         return t;
     };
 
-    // ---- Householder tridiagonalization.  Step j clears column j below the sub-diagonal with
-    // H_j = I - beta v v^T on indices j+1..k-1; v goes to row j of T (columns j+1..), beta to
-    // T[j][j].  The product T22 v has only n1 outputs: each output's sum is cut into pieces so
-    // that all threads carry loads (the step is bound by memory latency, not by arithmetic).
+    // ---- Householder tridiagonalization.  Reflector t, H_t = I - beta v v^T on indices
+    // t+1..k-1, clears column t below the sub-diagonal; v goes to row t of T (columns t+1..),
+    // beta to T[t][t].  The rank-two update of reflector t-1,  T -= v w^T + w v^T, is still
+    // pending when reflector t is formed: column t is corrected on the fly, and one pass over
+    // the trailing matrix then applies the pending update and multiplies the updated matrix
+    // with the new v (T is read and written once per reflector; the pass runs at the rate one
+    // CU moves the matrix to and from L2).  That pass has only n1 output sums: each is cut into
+    // pieces so that all threads carry loads.  (v, w) are indexed from t for the pending pair
+    // and from t+1 for the new one.
     const int parts = EIG_PARTS;
     const int tpp = nt / parts;
     const int part = tid / tpp, li = tid % tpp;
-    for (int j = 0; j + 2 < k; ++j) {
-        const int n1 = k - j - 1;
+    for (int i = tid; i < k; i += nt) { s_v[i] = 0.0; s_w[i] = 0.0; }
+    __syncthreads();
+    double* pv_ = s_v; double* pw_ = s_w;      // pending pair
+    double* nv_ = s_vn; double* nw_ = s_wn;    // pair being formed
+    for (int t = 0; t + 2 < k; ++t) {
+        const int n1 = k - t - 1;
+        const double v0 = pv_[0], w0 = pw_[0];
+        // column t below the diagonal, read along row t (T is kept symmetric in full storage)
         double psum = 0.0;
-        for (int i = tid; i < n1; i += nt) { const double x = T[(size_t)(j + 1 + i) * k + j]; s_v[i] = x; psum += x * x; }
+        for (int i = tid; i < n1; i += nt) {
+            const double x = T[(size_t)t * k + t + 1 + i] - v0 * pw_[1 + i] - w0 * pv_[1 + i];
+            nv_[i] = x;
+            psum += x * x;
+        }
+        const double dnew = T[(size_t)t * k + t] - 2.0 * v0 * w0;
         const double xnorm2 = block_sum(psum);
-        const double x0 = s_v[0];
+        const double x0 = nv_[0];
         const double xn = sqrt(xnorm2);
         double alpha = (x0 >= 0.0) ? -xn : xn;
-        const double vnorm2 = xnorm2 - 2.0 * alpha * x0 + alpha * alpha;
+        const double vnorm2 = xnorm2 - 2.0 * alpha * x0 + alpha * alpha;     // |x - alpha e1|^2
         const bool skip = (xnorm2 - x0 * x0 <= 0.0) || vnorm2 <= 0.0;        // already tridiagonal here
         if (skip) alpha = x0;
-        __syncthreads();
         const double beta = skip ? 0.0 : 2.0 / vnorm2;
-        if (tid == 0) { s_d[j] = T[(size_t)j * k + j]; s_e[j] = alpha; T[(size_t)j * k + j] = beta; if (!skip) s_v[0] = x0 - alpha; }
         __syncthreads();
-        if (skip) continue;
-        for (int i = tid; i < n1; i += nt) T[(size_t)j * k + j + 1 + i] = s_v[i];
+        if (tid == 0) { s_d[t] = dnew; s_e[t] = alpha; T[(size_t)t * k + t] = beta; nv_[0] = x0 - alpha; }
+        if (skip) { for (int i = tid; i < n1; i += nt) nv_[i] = 0.0; }       // no reflector: only the pending update runs
+        __syncthreads();
+        if (!skip) { for (int i = tid; i < n1; i += nt) T[(size_t)t * k + t + 1 + i] = nv_[i]; }
         const int seg = (n1 + parts - 1) / parts;
         const int c_lo = min(n1, part * seg), c_hi = min(n1, c_lo + seg);
+        // entry (c, i) of the trailing matrix, c in this thread's piece: pending update, then its
+        // term of p = T v (rows read as columns, coalesced over the output index i)
         for (int i = li; i < n1; i += tpp) {
+            const double vi = pv_[1 + i], wi = pw_[1 + i];
             double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-            const double* col = T + (size_t)(j + 1) * k + (j + 1 + i);
+            double* col = T + (size_t)(t + 1) * k + (t + 1 + i);
             int c = c_lo;
             for (; c + 8 <= c_hi; c += 8) {
                 double x[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) x[u] = col[(size_t)(c + u) * k];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc[u] += x[u] * s_v[c + u];
+                for (int u = 0; u < 8; ++u) {
+                    x[u] -= pv_[1 + c + u] * wi + pw_[1 + c + u] * vi;
+                    col[(size_t)(c + u) * k] = x[u];
+                    acc[u] += x[u] * nv_[c + u];
+                }
             }
-            for (; c < c_hi; ++c) acc[0] += col[(size_t)c * k] * s_v[c];
+            for (; c < c_hi; ++c) {
+                const double x = col[(size_t)c * k] - (pv_[1 + c] * wi + pw_[1 + c] * vi);
+                col[(size_t)c * k] = x;
+                acc[0] += x * nv_[c];
+            }
             s_part[part * EIG_MAXK + i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
         }
         __syncthreads();
         double pv = 0.0;
         for (int i = tid; i < n1; i += nt) {
-            double t = 0.0;
-            for (int q = 0; q < parts; ++q) t += s_part[q * EIG_MAXK + i];
-            t *= beta;
-            s_w[i] = t;
-            pv += t * s_v[i];
+            double a = 0.0;
+            for (int q = 0; q < parts; ++q) a += s_part[q * EIG_MAXK + i];
+            a *= beta;
+            nw_[i] = a;
+            pv += a * nv_[i];
         }
         const double kk2 = 0.5 * beta * block_sum(pv);
-        for (int i = tid; i < n1; i += nt) s_w[i] -= kk2 * s_v[i];           // w = p - (beta/2)(p.v) v
+        for (int i = tid; i < n1; i += nt) nw_[i] -= kk2 * nv_[i];           // w = p - (beta/2)(p.v) v
         __syncthreads();
-        // T22 -= v w^T + w v^T
-        for (int idx = tid; idx < n1 * n1; idx += nt) {
-            const int i = idx / n1, c = idx % n1;
-            T[(size_t)(j + 1 + i) * k + j + 1 + c] -= s_v[i] * s_w[c] + s_w[i] * s_v[c];
-        }
-        __syncthreads();
+        double* sw;
+        sw = pv_; pv_ = nv_; nv_ = sw;
+        sw = pw_; pw_ = nw_; nw_ = sw;
     }
+    // the last pending update touches the trailing 2 x 2 block only
     if (tid == 0) {
-        if (k >= 2) { s_d[k - 2] = T[(size_t)(k - 2) * k + k - 2]; s_e[k - 2] = T[(size_t)(k - 1) * k + k - 2]; }
-        s_d[k - 1] = T[(size_t)(k - 1) * k + k - 1];
+        if (k >= 2) {
+            s_d[k - 2] = T[(size_t)(k - 2) * k + k - 2] - 2.0 * pv_[0] * pw_[0];
+            s_e[k - 2] = T[(size_t)(k - 1) * k + k - 2] - pv_[1] * pw_[0] - pw_[1] * pv_[0];
+            s_d[k - 1] = T[(size_t)(k - 1) * k + k - 1] - 2.0 * pv_[1] * pw_[1];
+        } else {
+            s_d[0] = T[0];
+        }
         s_e[k - 1] = 0.0;
     }
     __syncthreads();
