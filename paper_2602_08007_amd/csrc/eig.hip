@@ -269,6 +269,9 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
     __shared__ double s_v[EIG_MAXK];            // eigenvalues, ascending
     __shared__ double s_w[EIG_MAXK];            // squared sub-diagonal
     __shared__ double s_part[EIG_MAXK];         // Gram-Schmidt coefficients
+    __shared__ double s_lo[EIG_MAXK];           // eigenvalue brackets
+    __shared__ double s_hi[EIG_MAXK];
+    __shared__ int s_cnt[EIG_THREADS];          // Sturm counts of the probes
     __shared__ double s_red[EIG_THREADS / 64];
     __shared__ int s_first[EIG_MAXK];           // first member of the group an eigenvalue belongs to
 
@@ -294,7 +297,7 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
     for (int i = tid; i < k; i += nt) { s_d[i] = DE[i]; s_e[i] = DE[k + i]; }
     __syncthreads();
 
-    // ---- eigenvalues by bisection on the Sturm count, eigenvalue j (ascending) on thread j
+    // ---- eigenvalues from Sturm counts
     double gl = 0.0, gu = 0.0;
     {
         double lo = 1e300, hi = -1e300;
@@ -320,23 +323,44 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
         gl -= margin; gu += margin;
     }
     __syncthreads();
-    if (tid < k) {
-        double lo = gl, hi = gu;
-        const double atol = EIG_EPS * tnorm;
-        for (int it = 0; it < 100; ++it) {
-            const double mid = 0.5 * (lo + hi);
-            if (hi - lo <= atol || !(mid > lo) || !(mid < hi)) break;
-            double q = s_d[0] - mid;
-            if (fabs(q) < pivmin) q = -pivmin;
-            int cnt = (q < 0.0) ? 1 : 0;
-            for (int i = 1; i < k; ++i) {
-                q = (s_d[i] - mid) - s_w[i - 1] * eig_rcp(q);
+    // Multisection: eigenvalue j (ascending) is worked on by S = threads / k neighbouring
+    // threads, whose S probes cut its bracket into S + 1 pieces per pass; the number of
+    // eigenvalues below a probe (Sturm count) tells on which side of it eigenvalue j lies.
+    {
+        const int S = max(1, min(nt / k, 7));
+        const int ej = tid / S, es = tid % S;
+        const bool eact = ej < k;
+        int passes = 0;
+        for (double shrink = 1.0; shrink < 1.5e17; shrink *= (double)(S + 1)) ++passes;   // 2^-57 of the bracket
+        for (int i = tid; i < k; i += nt) { s_lo[i] = gl; s_hi[i] = gu; }
+        __syncthreads();
+        const double inv_pieces = 1.0 / (double)(S + 1);
+        for (int pass = 0; pass < passes; ++pass) {
+            if (eact) {
+                const double lo = s_lo[ej], hi = s_hi[ej];
+                const double x = lo + (double)(es + 1) * ((hi - lo) * inv_pieces);
+                double q = s_d[0] - x;
                 if (fabs(q) < pivmin) q = -pivmin;
-                cnt += (q < 0.0) ? 1 : 0;
+                int cnt = (q < 0.0) ? 1 : 0;
+                for (int i = 1; i < k; ++i) {
+                    q = (s_d[i] - x) - s_w[i - 1] * eig_rcp(q);
+                    if (fabs(q) < pivmin) q = -pivmin;
+                    cnt += (q < 0.0) ? 1 : 0;
+                }
+                s_cnt[tid] = cnt;
             }
-            if (cnt > tid) hi = mid; else lo = mid;
+            __syncthreads();
+            if (eact && es == 0) {
+                const double lo = s_lo[ej], hi = s_hi[ej];
+                const double step = (hi - lo) * inv_pieces;
+                int m = 0;                                   // leading probes at or below eigenvalue ej
+                while (m < S && s_cnt[tid + m] <= ej) ++m;
+                if (m > 0) s_lo[ej] = lo + (double)m * step;
+                if (m < S) s_hi[ej] = lo + (double)(m + 1) * step;
+            }
+            __syncthreads();
         }
-        s_v[tid] = 0.5 * (lo + hi);
+        if (tid < k) s_v[tid] = 0.5 * (s_lo[tid] + s_hi[tid]);
     }
     __syncthreads();
 
@@ -383,12 +407,12 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
             };
             {
                 int i = 0;
-                for (; i + 4 < k; i += 4) {                  // rows i+1 .. i+4 fetched together
-                    double yn[4];
+                for (; i + 8 < k; i += 8) {                  // rows i+1 .. i+8 fetched together
+                    double yn[8];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) yn[u] = yval(i + 1 + u);
+                    for (int u = 0; u < 8; ++u) yn[u] = yval(i + 1 + u);
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) step(i + u, yn[u]);
+                    for (int u = 0; u < 8; ++u) step(i + u, yn[u]);
                 }
                 for (; i + 1 < k; ++i) step(i, yval(i + 1));
             }
@@ -398,19 +422,19 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
                 if (round == 0) { u0[(size_t)(k - 1) * k] = eig_rcp(piv); u1[(size_t)(k - 1) * k] = 0.0; u2[(size_t)(k - 1) * k] = 0.0; }
                 zc[(size_t)(k - 1) * k] = ycur;
             }
-            // backward: U x = y, four rows fetched together
+            // backward: U x = y, eight rows fetched together
             double x1 = 0.0, x2 = 0.0, amax = 0.0;      // x[i+1], x[i+2]
             bool bad = false;
             int i = k - 1;
-            for (; i >= 3; i -= 4) {
-                double y[4], p0[4], p1[4], p2[4];
+            for (; i >= 7; i -= 8) {
+                double y[8], p0[8], p1[8], p2[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 8; ++u) {
                     const size_t o = (size_t)(i - u) * k;
                     y[u] = zc[o]; p0[u] = u0[o]; p1[u] = u1[o]; p2[u] = u2[o];
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 8; ++u) {
                     const double x = (y[u] - p1[u] * x1 - p2[u] * x2) * p0[u];
                     zc[(size_t)(i - u) * k] = x;
                     amax = fmax(amax, fabs(x));
