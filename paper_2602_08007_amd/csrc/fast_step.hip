@@ -374,10 +374,12 @@ void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {
     fs.d_shadows = up.put(fs.shadows, ar);
     fs.d_adam = up.put(fs.adam, ar);
     // Adam rides in the epilogue of U^T P when every core is written whole by that GEMM: one
-    // worker, no k split, persistent launch, one problem per block in block order
+    // worker, no k split, persistent launch, one problem per block in block order.  Only with
+    // 64 x 64 tiles (cores up to 256 x 256): with the 128 x 128 tiles of larger cores the long
+    // epilogue measured slower than the separate Adam kernel.
     fs.adam_fused = false;
     if (tune_int("TSR_TUNE_ADAM_FUSED", 1, 0, 1) != 0 && fs.utp.reduces.empty() && !fs.utp.ranges.empty() &&
-        (fs.utp.var.shape == NT_64x64 || fs.utp.var.shape == NT_128x128) && fs.utp.probs.size() == fs.adam.size()) {
+        fs.utp.var.shape == NT_64x64 && fs.utp.probs.size() == fs.adam.size()) {
         bool ok = true;
         for (size_t j = 0; j < fs.adam.size(); ++j) {
             const NtProblem& p = fs.utp.probs[j];

@@ -589,7 +589,7 @@ static const NtEntry kNt[] = {
     NT_SHAPE(NT_128x128_K32, 128, 128, 2, 2, 32, 3, 2), NT_SHAPE(NT_256x64_K32, 256, 64, 4, 1, 32, 3, 2),
     NT_SHAPE(NT_256x128_K32, 256, 128, 2, 2, 32, 2, 1), NT_SHAPE(NT_128x256_K32, 128, 256, 2, 2, 32, 2, 1),
     NT_SHAPE(NT_256x128, 256, 128, 2, 2, 64, 1, 1),
-    NT_ENTRY_ADAM(NT_64x64, 64, 64, 2, 2, 64, 4), NT_ENTRY_ADAM(NT_128x128, 128, 128, 2, 2, 64, 2),
+    NT_ENTRY_ADAM(NT_64x64, 64, 64, 2, 2, 64, 4),
 };
 
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream) {
