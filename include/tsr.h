@@ -227,7 +227,7 @@ int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void*
  * TSR_PROF_KINDS entries.  Stage kinds of the step: G V, U^T P (with its split-k reduction),
  * Adam on the cores, U D, the fused T V^T weight update.  Of the refresh: the GEMMs that
  * read G (sketch and power iterations and B), the GEMMs of the thin QR, its Cholesky
- * kernels, the Jacobi SVD, the two basis-update GEMMs. */
+ * kernels, the small SVD of the k x k factor (kind name "jacobi"), the two basis-update GEMMs. */
 enum {
     TSR_PROF_GV = 0, TSR_PROF_UTP = 1, TSR_PROF_ADAM = 2, TSR_PROF_UD = 3, TSR_PROF_TVT = 4,
     TSR_PROF_SKETCH_GEMM = 5, TSR_PROF_ORTH_GEMM = 6, TSR_PROF_CHOL = 7, TSR_PROF_JACOBI = 8,

@@ -207,6 +207,41 @@ def test_refresh_exact_rank_r_input(tsr):
     assert float(sigma[r:].abs().max()) < 1e-4
 
 
+@pytest.mark.parametrize("m,n", [(200, 150), (130, 320)])
+def test_refresh_repeated_singular_values(tsr, m, n):
+    # exact rank 8 with singular values 4,4,4,2,2,2,2,1: inside a group of equal values any
+    # orthonormal basis is a valid set of singular vectors, so what is unique is compared: the
+    # values, the top-r subspace, the subspace of the leading group, orthonormality.  The
+    # eigen-solver sees groups of (numerically) equal eigenvalues plus p zeros.
+    r, p = 8, 4
+    A = si.orthonormal(m, r, si.stream_key(521, m))
+    B = si.orthonormal(n, r, si.stream_key(522, n))
+    sv = torch.tensor([4.0, 4.0, 4.0, 2.0, 2.0, 2.0, 2.0, 1.0], dtype=torch.float64)
+    G64 = (A * sv[None, :]) @ B.T
+    Om = si.omega(n, r + p, si.stream_key(523, n))
+    U, V, sigma = run_refresh(tsr, G64.float(), Om, r, p, 1)
+    check_orthonormal(U); check_orthonormal(V)
+    assert projector_err(U, A) < TOL_F32 and projector_err(V, B) < TOL_F32
+    assert projector_err(U[:, :3], A[:, :3]) < 1e-3 and projector_err(V[:, :3], B[:, :3]) < 1e-3
+    assert rel_fro(sigma[:r], sv.numpy()) < TOL_F32
+    assert float(sigma[r:].abs().max()) < 1e-4
+    # the same through the oracle: values and subspaces agree
+    Uo, Vo, so = orc.refresh_rsvd(G64.float().numpy(), orc.f64(Om), r, p, 1)
+    assert projector_err(U, Uo) < TOL_F32 and projector_err(V, Vo) < TOL_F32
+    assert rel_fro(sigma[:r], so[:r]) < TOL_F32
+
+
+def test_refresh_zero_gradient_is_finite(tsr):
+    # degenerate input: nothing to find.  Every sketch column is dropped as dependent, the
+    # singular values are zero and the bases come out as zeros: finite, no NaN from 0 / 0
+    m, n, r, p = 96, 160, 8, 4
+    Om = si.omega(n, r + p, 531)
+    U, V, sigma = run_refresh(tsr, torch.zeros(m, n), Om, r, p, 1)
+    assert torch.isfinite(U).all() and torch.isfinite(V).all() and torch.isfinite(sigma).all()
+    assert float(sigma.abs().max()) == 0.0
+    assert float(U.abs().max()) == 0.0 and float(V.abs().max()) == 0.0
+
+
 def test_refresh_config1(tsr):
     # 512 x 1376, r = 64, p = 8, q = 1, spectrum 1/i + noise 1e-3.  The tail of the signal is
     # below the noise, so the top-r projector is gap limited: the well conditioned quantities
