@@ -245,8 +245,9 @@ struct OrthProgram {        // X (rows x k) -> orthonormal basis, in place, Xalt
 struct RefreshProgram {
     std::vector<RefreshBlock> blocks;
     GemmStage sketch[2];    // Y = G Omega
-    GemmStage gtq[2];       // Z = G^T Y'   (Y' = current Q held in Y)
-    GemmStage gq[2];        // Y = G Z'
+    GemmStage gtq[2];       // Z = G^T Q    (final Q, held in Y)
+    GemmStage gtq_alt[2];   // Z = G^T Q'   (Q' = once-orthonormalised sketch, held in Yalt)
+    GemmStage gq[2];        // Y = G Q'row  (once-orthonormalised row basis, held in Zalt)
     OrthProgram orthY, orthZ;
     std::vector<JacobiBlock> jac; const JacobiBlock* d_jac = nullptr;
     GemmStage uout, vout;
@@ -276,7 +277,13 @@ void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool o
     build_stage(op.q2, variant(0, 1, 0, 3, 3), q2, ar, 1);
 }
 
-int run_orth(const OrthProgram& op, bool grouped, Ctx& cx) {
+// passes = 2: CholeskyQR2, X (and Xalt) -> orthonormal basis in X.  passes = 1: one Cholesky
+// pass, X -> X R^-1 in Xalt: a basis of the same span with the same triangular orientation,
+// orthonormal to about the conditioning of X squared times the fp32-grade accuracy of the Gram
+// matrix.  That is all the normalisations inside the power iteration are for (they keep the
+// columns from collapsing onto the leading directions); what the refresh returns goes through
+// the two-pass form.
+int run_orth(const OrthProgram& op, bool grouped, Ctx& cx, int passes = 2) {
     const int nb = (int)op.chol1.size();
     int max_k = 0;
     for (const CholBlock& cb : op.chol1) max_k = std::max(max_k, cb.k);
@@ -286,6 +293,7 @@ int run_orth(const OrthProgram& op, bool grouped, Ctx& cx) {
         TSR_HIP(launch_chol_inv(grouped ? op.d_chol1 : nullptr, grouped ? nullptr : &op.chol1[0], nb, max_k, 1e-6, cx.s));
     }
     TSR_TRY(run_stage(op.q1, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    if (passes == 1) return TSR_OK;
     TSR_TRY(run_stage(op.gram2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     {
         Timed timed(cx, TSR_PROF_CHOL);
@@ -321,14 +329,15 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
 
 // Stages and tables of the refresh of rp.blocks (whose buffers are already carved).
 void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena& ar) {
-    std::vector<LogicalGemm> sk[2], gtq[2], gq[2], uo, vo;
+    std::vector<LogicalGemm> sk[2], gtq[2], gtqa[2], gq[2], uo, vo;
     rp.jac.clear();
     for (size_t i = 0; i < rp.blocks.size(); ++i) {
         const RefreshBlock& b = rp.blocks[i];
         const float* om = omegas ? omegas[i] : nullptr;
         sk[b.g_dtype].push_back(LogicalGemm{b.G, om, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
         gtq[b.g_dtype].push_back(LogicalGemm{b.G, b.Y, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
-        gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Z, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
+        gtqa[b.g_dtype].push_back(LogicalGemm{b.G, b.Yalt, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
+        gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Zalt, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
         uo.push_back(LogicalGemm{b.Y, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
         vo.push_back(LogicalGemm{b.Z, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
         rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r, b.eig, b.R1});
@@ -336,6 +345,7 @@ void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena&
     for (int d = 0; d < 2; ++d) {
         build_stage(rp.sketch[d], variant(0, 1, d, 2, 2), sk[d], ar);
         build_stage(rp.gtq[d], variant(1, 1, d, 2, 2), gtq[d], ar);
+        build_stage(rp.gtq_alt[d], variant(1, 1, d, 2, 2), gtqa[d], ar);
         build_stage(rp.gq[d], variant(0, 1, d, 2, 2), gq[d], ar);
     }
     build_orth(rp.orthY, rp.blocks, true, ar);
@@ -344,16 +354,19 @@ void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena&
     build_stage(rp.vout, variant(0, 0, 0, 3, 3), vo, ar, 1);
 }
 
-// Sketch chain of one worker: leaves the final Q in Y and B^T = G^T Q in Z.
+// Sketch chain of one worker: leaves the final Q in Y and B^T = G^T Q in Z.  Inside the power
+// iteration the bases are normalised by one Cholesky pass (run_orth, passes = 1), the final Q by
+// CholeskyQR2: right-multiplying a sketch by an upper-triangular factor changes neither its span
+// nor the Q factor of anything computed from it.
 int run_refresh_front(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.sketch[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
-    TSR_TRY(run_orth(rp.orthY, grouped, cx));
     for (int it = 0; it < q; ++it) {
-        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
-        TSR_TRY(run_orth(rp.orthZ, grouped, cx));
+        TSR_TRY(run_orth(rp.orthY, grouped, cx, 1));                                    // Q' in Yalt
+        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq_alt[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
+        TSR_TRY(run_orth(rp.orthZ, grouped, cx, 1));                                    // Q'row in Zalt
         for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
-        TSR_TRY(run_orth(rp.orthY, grouped, cx));
     }
+    TSR_TRY(run_orth(rp.orthY, grouped, cx));
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     return TSR_OK;
 }
@@ -393,7 +406,8 @@ int check_refresh_shape(int m, int n, int r, int p) {
 
 void upload_refresh(RefreshProgram& rp, Arena& ar, Uploader& up) {
     for (int d = 0; d < 2; ++d) {
-        upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gq[d], ar, up);
+        upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gtq_alt[d], ar, up);
+        upload_stage(rp.gq[d], ar, up);
     }
     for (OrthProgram* op : {&rp.orthY, &rp.orthZ}) {
         upload_stage(op->gram1, ar, up); upload_stage(op->q1, ar, up);
