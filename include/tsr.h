@@ -139,8 +139,10 @@ int tsr_backproject_apply(float* W, int m, int n, long long ldw,
  * Omega is n x (r+p), N(0,1), supplied by the caller (the paper shares it by RNG seed).
  * Requires r + p <= min(m, n).  Writes U (m x r), V (n x r) and, if sigma != NULL, the
  * r + p singular values of B in descending order.
- * orth is a Cholesky-based thin QR repeated twice with fp64 factorization of the Gram
- * matrix; a Gram matrix that is singular to working precision (a gradient of rank below
+ * orth is a Cholesky-based thin QR with fp64 factorization of the Gram matrix, repeated
+ * twice for the final Q and for the factor of B^T and applied once to the sketches inside
+ * the power iteration (same span, same Q factor of what follows; they only need to stay
+ * well conditioned); a Gram matrix that is singular to working precision (a gradient of rank below
  * r + p, e.g. all zeros) gives zero columns in place of the undetermined directions.
  * Workspace: tsr_refresh_workspace_bytes(m, n, r, p). */
 size_t tsr_refresh_workspace_bytes(int m, int n, int r, int p);
