@@ -321,7 +321,7 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         b.XrT = ar.take<float>((size_t)b.r * k); b.GrT = ar.take<float>((size_t)b.r * k);
         b.work = ar.take<double>(2 * k * k + 64); b.R1 = ar.take<double>(k * k);
         b.Rtot = ar.take<double>(k * k); b.Gacc = ar.take<double>(k * k);
-        b.eig = (b.k <= EIG_MAXK) ? ar.take<double>(3 * k * k + 2 * k) : nullptr;
+        b.eig = (b.k <= EIG_MAXK) ? ar.take<double>(3 * k * k + 3 * k + 8) : nullptr;
         rp.blocks.push_back(b);
     }
     build_refresh_stages(rp, omegas, ar);

@@ -2,10 +2,9 @@
 // Algorithm 1's refresh step) as a chain of launches, for k <= EIG_MAXK:
 //   1. T = R R^T                        fp64 MFMA GEMM, 64 x 64 tiles over the whole chip
 //   2. per matrix, one workgroup:       Householder tridiagonalization of T (reflectors parked in
-//      the rows of T they cleared); then, in a launch of its own, eigenvalues by bisection (one
-//      per thread), eigenvectors of the tridiagonal matrix by inverse iteration (one per
-//      thread, pivoted LU of T - lambda I), Gram-Schmidt inside groups of numerically equal
-//      eigenvalues
+//      the rows of T they cleared); then eigenvalues by Sturm-count multisection (chip-wide),
+//      eigenvectors of the tridiagonal matrix by inverse iteration (one per thread, pivoted LU
+//      of T - lambda I), Gram-Schmidt inside groups of numerically equal eigenvalues
 //   3. E = H_0 H_1 ... Z                reflectors applied to 64 eigenvectors per workgroup, the
 //      vectors held in registers
 //   4. E^T R                            fp64 MFMA GEMM
@@ -38,6 +37,21 @@ __device__ inline double eig_rcp(double x) {
     return r;
 }
 
+// Kernels that cut a matrix into chunks run one workgroup per (block b, chunk c) on a 1-D grid.
+// Workgroups are handed to the eight XCDs in turn.  Chunk-major numbering spreads the chunks of
+// a block over the XCDs; "pinned" numbering (block index fastest, padded to a multiple of
+// eight) keeps block b on XCD b % 8, where the one-workgroup-per-block kernels also run it.
+struct EigGrid { int n_blocks, chunks, pinned; };
+__device__ inline bool eig_decode(const EigGrid g, int& b, int& c) {
+    const int lin = blockIdx.x;
+    if (g.pinned) { const int bx = (g.n_blocks + 7) / 8 * 8; b = lin % bx; c = lin / bx; }
+    else { c = lin % g.chunks; b = lin / g.chunks; }
+    return b < g.n_blocks && c < g.chunks;
+}
+inline dim3 eig_grid(const EigGrid g) {
+    return dim3((unsigned)((g.pinned ? (g.n_blocks + 7) / 8 * 8 : g.n_blocks) * g.chunks));
+}
+
 // ------------------------------------------------------------------ fp64 MFMA GEMMs
 // v_mfma_f64_16x16x4: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16] and receives
 // D[4 v + l / 16][l % 16] in element v.  One wave owns a 32 x 32 patch (2 x 2 MFMA tiles), a
@@ -47,14 +61,16 @@ __device__ inline double eig_rcp(double x) {
 // WHICH = 1: E^T R into the second half of tmp (the sum for column c ends at c);
 // WHICH = 2: R = R2 R1 with R2 in Gacc, both upper triangular (the sum runs from i to j).
 template <int WHICH>
-__global__ __launch_bounds__(256) void eig_gemm_kernel(const JacobiBlock* table, const JacobiBlock single) {
+__global__ __launch_bounds__(256) void eig_gemm_kernel(const JacobiBlock* table, const JacobiBlock single, const EigGrid grid) {
     JacobiBlock jb = single;
-    if (table) jb = table[blockIdx.y];
+    int gb, gc;
+    if (!eig_decode(grid, gb, gc)) return;
+    if (table) jb = table[gb];
     const JacobiBlock* blk = &jb;
     const int k = blk->k;
     const int tiles = (k + 63) >> 6;
-    if ((int)blockIdx.x >= tiles * tiles) return;
-    const int tm = blockIdx.x / tiles, tn = blockIdx.x % tiles;
+    if (gc >= tiles * tiles) return;
+    const int tm = gc / tiles, tn = gc % tiles;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m0 = tm * 64 + (wave >> 1) * 32, n0 = tn * 64 + (wave & 1) * 32;
     if (m0 >= k || n0 >= k) return;
@@ -251,39 +267,35 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
     for (int i = tid; i < k; i += nt) { DE[i] = s_d[i]; DE[k + i] = s_e[i]; }
 }
 
-// Eigenvalues and eigenvectors of the tridiagonal matrix (d, e) left by eig_tridiag_kernel.
-__global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBlock* table, const JacobiBlock single) {
+// Eigenvalues and eigenvectors of the tridiagonal matrix (d, e) left by eig_tridiag_kernel, in
+// three launches: eigenvalues (chip-wide), inverse iteration (one wave per workgroup),
+// orthogonalisation inside groups of numerically equal eigenvalues (one workgroup per matrix).
+// Behind the LU scratch (3 k^2 doubles) sit d (k), e (k), the eigenvalues (k, ascending) and the
+// radius of the spectrum's bracket (1; zero marks a zero or non-finite matrix).
+
+// Sturm-count multisection: 32 eigenvalues per workgroup, 8 threads each; 7 probes cut an
+// eigenvalue's bracket into 8 pieces per pass, and the number of eigenvalues below a probe
+// tells on which side of it the wanted one lies.
+constexpr int EIG_VAL_PER_WG = 32;
+__global__ __launch_bounds__(256) void eig_values_kernel(const JacobiBlock* table, const JacobiBlock single, const EigGrid grid) {
     JacobiBlock jb = single;
-    if (table) jb = table[blockIdx.x];
+    int gb, gc;
+    if (!eig_decode(grid, gb, gc)) return;
+    if (table) jb = table[gb];
     const JacobiBlock* blk = &jb;
     const int k = blk->k;
-    double* Z = blk->tmp + (size_t)k * k;       // eigenvectors of the tridiagonal matrix, Z[i][j] = j-th vector
-    double* U0 = blk->scratch;                  // per thread j: reciprocal pivots, first and second
-    double* U1 = U0 + (size_t)k * k;            //   super-diagonal of the LU factor, entry [i][j]
-    double* U2 = U1 + (size_t)k * k;
+    const int e0 = gc * EIG_VAL_PER_WG;
+    if (e0 >= k) return;
     const double* DE = blk->scratch + (size_t)3 * k * k;
+    double* LAM = blk->scratch + (size_t)3 * k * k + 2 * k;
     const int tid = threadIdx.x, nt = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
     __shared__ double s_d[EIG_MAXK];            // diagonal
-    __shared__ double s_e[EIG_MAXK];            // sub-diagonal, s_e[i] couples i and i + 1
-    __shared__ double s_v[EIG_MAXK];            // eigenvalues, ascending
     __shared__ double s_w[EIG_MAXK];            // squared sub-diagonal
-    __shared__ double s_part[EIG_MAXK];         // Gram-Schmidt coefficients
-    __shared__ double s_lo[EIG_MAXK];           // eigenvalue brackets
-    __shared__ double s_hi[EIG_MAXK];
-    __shared__ int s_cnt[EIG_THREADS];          // Sturm counts of the probes
-    __shared__ double s_red[EIG_THREADS / 64];
-    __shared__ int s_first[EIG_MAXK];           // first member of the group an eigenvalue belongs to
-
-    auto block_sum = [&](double v) -> double {
-        v = eig_wave_sum(v);
-        __syncthreads();
-        if (lane == 0) s_red[wave] = v;
-        __syncthreads();
-        double t = 0.0;
-        for (int i = 0; i < nw; ++i) t += s_red[i];
-        return t;
-    };
+    __shared__ double s_lo[EIG_VAL_PER_WG];     // eigenvalue brackets
+    __shared__ double s_hi[EIG_VAL_PER_WG];
+    __shared__ int s_cnt[256];                  // Sturm counts of the probes
+    __shared__ double s_red[4];
     auto block_max = [&](double v) -> double {
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
@@ -294,82 +306,104 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
         for (int i = 1; i < nw; ++i) t = fmax(t, s_red[i]);
         return t;
     };
-    for (int i = tid; i < k; i += nt) { s_d[i] = DE[i]; s_e[i] = DE[k + i]; }
-    __syncthreads();
-
-    // ---- eigenvalues from Sturm counts
     double gl = 0.0, gu = 0.0;
     {
         double lo = 1e300, hi = -1e300;
         for (int i = tid; i < k; i += nt) {
-            const double rad = ((i > 0) ? fabs(s_e[i - 1]) : 0.0) + ((i < k - 1) ? fabs(s_e[i]) : 0.0);
-            lo = fmin(lo, s_d[i] - rad);
-            hi = fmax(hi, s_d[i] + rad);
-            s_w[i] = s_e[i] * s_e[i];
+            const double di = DE[i], ei = DE[k + i];
+            const double rad = ((i > 0) ? fabs(DE[k + i - 1]) : 0.0) + ((i < k - 1) ? fabs(ei) : 0.0);
+            lo = fmin(lo, di - rad);
+            hi = fmax(hi, di + rad);
+            s_d[i] = di;
+            s_w[i] = ei * ei;
         }
         gu = block_max(hi);
         gl = -block_max(-lo);
     }
-    const double tnorm = fmax(fabs(gl), fabs(gu));
-    if (!(tnorm > 0.0) || !(tnorm < 1e300)) {
-        // zero (or non-finite) matrix: every orthonormal basis is one of eigenvectors
-        for (int idx = tid; idx < k * k; idx += nt) Z[idx] = (idx / k == idx % k) ? 1.0 : 0.0;
+    double tnorm = fmax(fabs(gl), fabs(gu));
+    const bool degenerate = !(tnorm > 0.0) || !(tnorm < 1e300);   // zero (or non-finite) matrix
+    if (degenerate) tnorm = 0.0;
+    if (gc == 0 && tid == 0) LAM[k] = tnorm;
+    if (degenerate) {
+        if (tid < EIG_VAL_PER_WG && e0 + tid < k) LAM[e0 + tid] = 0.0;
         return;
     }
     const double pivmin = fmax(1e-290, 1e-32 * tnorm);
-    const double tiny = EIG_EPS * tnorm;                 // floor of an LU pivot
     {
         const double margin = 2.0 * EIG_EPS * tnorm * (double)k + 2.0 * pivmin;
         gl -= margin; gu += margin;
     }
+    constexpr int S = 7;
+    const int el = tid >> 3, es = tid & 7;
+    const int ej = e0 + el;
+    const bool eact = ej < k && es < S;
+    int passes = 0;
+    for (double shrink = 1.0; shrink < 1.5e17; shrink *= (double)(S + 1)) ++passes;       // 2^-57 of the bracket
+    if (tid < EIG_VAL_PER_WG) { s_lo[tid] = gl; s_hi[tid] = gu; }
     __syncthreads();
-    // Multisection: eigenvalue j (ascending) is worked on by S = threads / k neighbouring
-    // threads, whose S probes cut its bracket into S + 1 pieces per pass; the number of
-    // eigenvalues below a probe (Sturm count) tells on which side of it eigenvalue j lies.
-    {
-        const int S = max(1, min(nt / k, 7));
-        const int ej = tid / S, es = tid % S;
-        const bool eact = ej < k;
-        int passes = 0;
-        for (double shrink = 1.0; shrink < 1.5e17; shrink *= (double)(S + 1)) ++passes;   // 2^-57 of the bracket
-        for (int i = tid; i < k; i += nt) { s_lo[i] = gl; s_hi[i] = gu; }
-        __syncthreads();
-        const double inv_pieces = 1.0 / (double)(S + 1);
-        for (int pass = 0; pass < passes; ++pass) {
-            if (eact) {
-                const double lo = s_lo[ej], hi = s_hi[ej];
-                const double x = lo + (double)(es + 1) * ((hi - lo) * inv_pieces);
-                double q = s_d[0] - x;
+    const double inv_pieces = 1.0 / (double)(S + 1);
+    for (int pass = 0; pass < passes; ++pass) {
+        if (eact) {
+            const double lo = s_lo[el], hi = s_hi[el];
+            const double x = lo + (double)(es + 1) * ((hi - lo) * inv_pieces);
+            double q = s_d[0] - x;
+            if (fabs(q) < pivmin) q = -pivmin;
+            int cnt = (q < 0.0) ? 1 : 0;
+            for (int i = 1; i < k; ++i) {
+                q = (s_d[i] - x) - s_w[i - 1] * eig_rcp(q);
                 if (fabs(q) < pivmin) q = -pivmin;
-                int cnt = (q < 0.0) ? 1 : 0;
-                for (int i = 1; i < k; ++i) {
-                    q = (s_d[i] - x) - s_w[i - 1] * eig_rcp(q);
-                    if (fabs(q) < pivmin) q = -pivmin;
-                    cnt += (q < 0.0) ? 1 : 0;
-                }
-                s_cnt[tid] = cnt;
+                cnt += (q < 0.0) ? 1 : 0;
             }
-            __syncthreads();
-            if (eact && es == 0) {
-                const double lo = s_lo[ej], hi = s_hi[ej];
-                const double step = (hi - lo) * inv_pieces;
-                int m = 0;                                   // leading probes at or below eigenvalue ej
-                while (m < S && s_cnt[tid + m] <= ej) ++m;
-                if (m > 0) s_lo[ej] = lo + (double)m * step;
-                if (m < S) s_hi[ej] = lo + (double)(m + 1) * step;
-            }
-            __syncthreads();
+            s_cnt[tid] = cnt;
         }
-        if (tid < k) s_v[tid] = 0.5 * (s_lo[tid] + s_hi[tid]);
+        __syncthreads();
+        if (eact && es == 0) {
+            const double lo = s_lo[el], hi = s_hi[el];
+            const double step = (hi - lo) * inv_pieces;
+            int m = 0;                                       // leading probes at or below eigenvalue ej
+            while (m < S && s_cnt[tid + m] <= ej) ++m;
+            if (m > 0) s_lo[el] = lo + (double)m * step;
+            if (m < S) s_hi[el] = lo + (double)(m + 1) * step;
+        }
+        __syncthreads();
     }
-    __syncthreads();
+    if (tid < EIG_VAL_PER_WG && e0 + tid < k) LAM[e0 + tid] = 0.5 * (s_lo[tid] + s_hi[tid]);
+}
 
-    // ---- eigenvectors by inverse iteration, vector j on thread j.  T - lambda I = P L U with
-    // partial pivoting; U (three diagonals, pivots as reciprocals) is kept, L is applied to the
-    // right-hand side while it is formed and formed again in every round.
-    if (tid < k) {
-        const int j = tid;
-        const double lam = s_v[j];
+// Eigenvectors by inverse iteration, vector j on its own thread, one wave per workgroup (the
+// recurrences are serial in the row index and wait on L2 for their operands: a wave alone on
+// its SIMD; eight rows are fetched at a time).  T - lambda I = P L U with
+// partial pivoting; U (three diagonals, pivots as reciprocals) is kept, L is applied to the
+// right-hand side while it is formed and formed again in every round.
+__global__ __launch_bounds__(64) void eig_invit_kernel(const JacobiBlock* table, const JacobiBlock single, const EigGrid grid) {
+    JacobiBlock jb = single;
+    int gb, gc;
+    if (!eig_decode(grid, gb, gc)) return;
+    if (table) jb = table[gb];
+    const JacobiBlock* blk = &jb;
+    const int k = blk->k;
+    if (gc * 64 >= k) return;
+    double* Z = blk->tmp + (size_t)k * k;       // eigenvectors of the tridiagonal matrix, Z[i][j] = j-th vector
+    double* U0 = blk->scratch;                  // per thread j: reciprocal pivots, first and second
+    double* U1 = U0 + (size_t)k * k;            //   super-diagonal of the LU factor, entry [i][j]
+    double* U2 = U1 + (size_t)k * k;
+    const double* DE = blk->scratch + (size_t)3 * k * k;
+    const double* LAM = DE + 2 * k;
+    const int tid = threadIdx.x;
+    const int j = gc * 64 + tid;
+    __shared__ double s_d[EIG_MAXK];            // diagonal
+    __shared__ double s_e[EIG_MAXK];            // sub-diagonal, s_e[i] couples i and i + 1
+    for (int i = tid; i < k; i += 64) { s_d[i] = DE[i]; s_e[i] = DE[k + i]; }
+    __syncthreads();
+    const double tnorm = LAM[k];
+    if (tnorm == 0.0) {
+        // zero (or non-finite) matrix: every orthonormal basis is one of eigenvectors
+        if (j < k) for (int i = 0; i < k; ++i) Z[(size_t)i * k + j] = (i == j) ? 1.0 : 0.0;
+        return;
+    }
+    const double tiny = EIG_EPS * tnorm;                 // floor of an LU pivot
+    if (j < k) {
+        const double lam = LAM[j];
         double* zc = Z + j;
         double* u0 = U0 + j; double* u1 = U1 + j; double* u2 = U2 + j;
         double scale = 1.0;
@@ -463,8 +497,45 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
         const double nrm = scale / sqrt(ss);
         for (int i = 0; i < k; ++i) zc[(size_t)i * k] *= nrm;
     }
-    __syncthreads();
+}
 
+// Eigenvalues closer than ortol form a group; inside a group the vectors of the inverse
+// iteration span the right subspace but need not be orthogonal: Gram-Schmidt (two passes) in
+// order.  One workgroup per matrix; returns at once when there is no group.
+__global__ __launch_bounds__(EIG_THREADS) void eig_groups_kernel(const JacobiBlock* table, const JacobiBlock single) {
+    JacobiBlock jb = single;
+    if (table) jb = table[blockIdx.x];
+    const JacobiBlock* blk = &jb;
+    const int k = blk->k;
+    double* Z = blk->tmp + (size_t)k * k;
+    const double* LAM = blk->scratch + (size_t)3 * k * k + 2 * k;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+    __shared__ double s_v[EIG_MAXK];            // eigenvalues, ascending
+    __shared__ double s_part[EIG_MAXK];         // Gram-Schmidt coefficients
+    __shared__ double s_red[EIG_THREADS / 64];
+    __shared__ int s_first[EIG_MAXK];           // first member of the group an eigenvalue belongs to
+    __shared__ int s_any;
+    auto block_sum = [&](double v) -> double {
+        v = eig_wave_sum(v);
+        __syncthreads();
+        if (lane == 0) s_red[wave] = v;
+        __syncthreads();
+        double t = 0.0;
+        for (int i = 0; i < nw; ++i) t += s_red[i];
+        return t;
+    };
+    const double tnorm = LAM[k];
+    if (tnorm == 0.0) return;
+    if (tid == 0) s_any = 0;
+    for (int i = tid; i < k; i += nt) s_v[i] = LAM[i];
+    __syncthreads();
+    {
+        const double ortol0 = 1e-9 * tnorm;
+        for (int i = 1 + tid; i < k; i += nt) if (s_v[i] - s_v[i - 1] <= ortol0) s_any = 1;
+    }
+    __syncthreads();
+    if (s_any == 0) return;
     // ---- eigenvalues closer than ortol form a group; inside a group the vectors found above
     // span the right subspace but need not be orthogonal: Gram-Schmidt (two passes) in order.
     {
@@ -508,12 +579,14 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_vectors_kernel(const JacobiBl
 // waves owns EPT consecutive rows (in registers); the reflector entries are uniform over a
 // wave.  One barrier per reflector (the dot product spans the waves).
 template <int EPT, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void eig_backtransform_kernel(const JacobiBlock* table, const JacobiBlock single) {
+__global__ __launch_bounds__(64 * WAVES) void eig_backtransform_kernel(const JacobiBlock* table, const JacobiBlock single, const EigGrid grid) {
     JacobiBlock jb = single;
-    if (table) jb = table[blockIdx.y];
+    int gb, gc;
+    if (!eig_decode(grid, gb, gc)) return;
+    if (table) jb = table[gb];
     const JacobiBlock* blk = &jb;
     const int k = blk->k;
-    const int c0 = blockIdx.x * 64;
+    const int c0 = gc * 64;
     if (c0 >= k) return;
     typedef const double __attribute__((address_space(1))) gdouble;
     typedef double d8 __attribute__((ext_vector_type(8)));
@@ -649,7 +722,8 @@ hipError_t launch_rtot_product(const JacobiBlock* table_dev, const JacobiBlock* 
     JacobiBlock sb{};
     if (single) sb = *single;
     const int tiles = (max_k + 63) / 64;
-    hipLaunchKernelGGL(eig_gemm_kernel<2>, dim3(tiles * tiles, blocks), dim3(256), 0, stream, table_dev, sb);
+    const EigGrid gt{blocks, tiles * tiles, 0};
+    hipLaunchKernelGGL(eig_gemm_kernel<2>, eig_grid(gt), dim3(256), 0, stream, table_dev, sb, gt);
     return hipGetLastError();
 }
 
@@ -660,16 +734,22 @@ hipError_t launch_eig_svd(const JacobiBlock* table_dev, const JacobiBlock* singl
     JacobiBlock sb{};
     if (single) sb = *single;
     const int tiles = (max_k + 63) / 64;
-    hipLaunchKernelGGL(eig_gemm_kernel<0>, dim3(tiles * tiles, blocks), dim3(256), 0, stream, table_dev, sb);
+    const EigGrid gt{blocks, tiles * tiles, 0};
+    const EigGrid gv{blocks, (max_k + EIG_VAL_PER_WG - 1) / EIG_VAL_PER_WG, 0};
+    const EigGrid gi{blocks, (max_k + 63) / 64, 1};      // measured: pinned 0.70 ms, chunk-major 0.74 (84 blocks, k = 264)
+    hipLaunchKernelGGL(eig_gemm_kernel<0>, eig_grid(gt), dim3(256), 0, stream, table_dev, sb, gt);
     hipLaunchKernelGGL(eig_tridiag_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
-    hipLaunchKernelGGL(eig_vectors_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
-    const dim3 bt_grid(tiles, blocks);
-    if (max_k <= 32) hipLaunchKernelGGL((eig_backtransform_kernel<8, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);
-    else if (max_k <= 96) hipLaunchKernelGGL((eig_backtransform_kernel<24, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);
-    else if (max_k <= 160) hipLaunchKernelGGL((eig_backtransform_kernel<40, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb);
-    else if (max_k <= 320) hipLaunchKernelGGL((eig_backtransform_kernel<40, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb);
-    else hipLaunchKernelGGL((eig_backtransform_kernel<72, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb);
-    hipLaunchKernelGGL(eig_gemm_kernel<1>, dim3(tiles * tiles, blocks), dim3(256), 0, stream, table_dev, sb);
+    hipLaunchKernelGGL(eig_values_kernel, eig_grid(gv), dim3(256), 0, stream, table_dev, sb, gv);
+    hipLaunchKernelGGL(eig_invit_kernel, eig_grid(gi), dim3(64), 0, stream, table_dev, sb, gi);
+    hipLaunchKernelGGL(eig_groups_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
+    const EigGrid gbt{blocks, tiles, 0};
+    const dim3 bt_grid = eig_grid(gbt);
+    if (max_k <= 32) hipLaunchKernelGGL((eig_backtransform_kernel<8, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb, gbt);
+    else if (max_k <= 96) hipLaunchKernelGGL((eig_backtransform_kernel<24, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb, gbt);
+    else if (max_k <= 160) hipLaunchKernelGGL((eig_backtransform_kernel<40, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb, gbt);
+    else if (max_k <= 320) hipLaunchKernelGGL((eig_backtransform_kernel<40, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb, gbt);
+    else hipLaunchKernelGGL((eig_backtransform_kernel<72, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb, gbt);
+    hipLaunchKernelGGL(eig_gemm_kernel<1>, eig_grid(gt), dim3(256), 0, stream, table_dev, sb, gt);
     hipLaunchKernelGGL(eig_finish_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
     return hipGetLastError();
 }

@@ -52,7 +52,7 @@ hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, 
 // Gacc R = diag(sigma) X^T (rows mutually orthogonal), from the symmetric eigenproblem of R R^T.
 // Outputs, for the r largest sigma in descending order: XrT (r x k fp32) rows x_j^T, GrT
 // (r x k fp32) rows of Gacc, and sigma (k fp32, optional, all k values descending).
-// Work: Gacc k x k doubles, tmp 2 k x k + 64 doubles, scratch 3 k x k + 2 k doubles (launch_eig_svd only).
+// Work: Gacc k x k doubles, tmp 2 k x k + 64 doubles, scratch 3 k x k + 3 k + 8 doubles (launch_eig_svd only).
 struct JacobiBlock {
     double* R; double* Gacc; double* tmp;
     float* XrT; float* GrT; float* sigma;
