@@ -408,7 +408,7 @@ __global__ __launch_bounds__(64) void eig_invit_kernel(const JacobiBlock* table,
         double* u0 = U0 + j; double* u1 = U1 + j; double* u2 = U2 + j;
         double scale = 1.0;
         for (int round = 0; round < 3; ++round) {
-            // forward: eliminate, apply to y (round 0: the start vector, later scale * previous x)
+            // forward: eliminate, apply to y (first time round: the start vector, later scale * previous x)
             auto yval = [&](int i) -> double {
                 return (round == 0) ? eig_start_value((unsigned)i, (unsigned)j) : scale * zc[(size_t)i * k];
             };

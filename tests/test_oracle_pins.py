@@ -334,6 +334,40 @@ def test_rsvd_independent_of_orth_basis():
     assert np.linalg.norm(projector(V1) - projector(V0)) < 1e-9
 
 
+def test_rsvd_unchanged_by_triangular_rescaling_inside_the_power_iteration():
+    # The oracle takes orth at every normalisation of the power iteration (Section 3.5).  What
+    # the refresh returns does not depend on how well the INTERMEDIATE bases are normalised:
+    # replacing orth(X) by X T^-1 for any upper-triangular T (which is what a single Cholesky
+    # pass of a thin QR delivers) keeps every span, and keeps the positively oriented Q factor of
+    # the final sketch.  Composed here from the oracle's QR and SVD with q = 2 against the
+    # oracle's own refresh.
+    m, n, r, p, q = 36, 29, 5, 3, 2
+    k = r + p
+    G = RNG.standard_normal((m, n)); Om = si.omega(n, k, 131).numpy()
+    U0, V0, S0, Q0 = orc.refresh_rsvd(G, Om, r, p, q, return_q=True)
+
+    def loose(X, seed):          # X T^-1 with a fixed, far from orthonormalising, triangular T
+        T = np.triu(np.random.default_rng(seed).uniform(0.5, 2.0, (k, k)))
+        return X @ np.linalg.inv(T)
+
+    Y = loose(G @ Om, 1)
+    for it in range(q):
+        Z = loose(G.T @ Y, 10 + it)
+        Y = G @ Z
+        if it + 1 < q:
+            Y = loose(Y, 20 + it)
+    Q, R = orc.householder_qr(Y)
+    sgn = np.sign(np.diag(R)); sgn[sgn == 0] = 1.0
+    Q = Q * sgn                                   # orientation diag(R) > 0
+    # same span, and the same basis up to the sign convention of the oracle's own QR
+    assert np.linalg.norm(projector(Q) - projector(Q0)) < 1e-9
+    assert np.abs(np.abs(Q0.T @ Q) - np.eye(k)).max() < 1e-8
+    Ut, S, Vt, _ = orc.jacobi_svd(Q.T @ G)
+    assert np.allclose(S, S0, rtol=1e-9)
+    assert np.linalg.norm(projector(Q @ Ut[:, :r]) - projector(U0)) < 1e-8
+    assert np.linalg.norm(projector(Vt[:, :r]) - projector(V0)) < 1e-8
+
+
 def test_rsvd_rejects_oversized_sketch():
     G = RNG.standard_normal((10, 8))
     with pytest.raises(ValueError):
