@@ -172,8 +172,8 @@ def check_orthonormal(X, tol=1e-4):
     assert np.abs(X.T @ X - np.eye(X.shape[1])).max() < tol
 
 
-# the last case has k = r + p = 560: beyond the blocked Cholesky and the split sums of the
-# eigen-solver (both for k <= 544), so it runs their general variants
+# the last case has k = r + p = 560: beyond the blocked Cholesky and the multi-launch small SVD
+# (both for k <= 544), so it runs their general variants (unblocked Cholesky, single-kernel QL)
 @pytest.mark.parametrize("m,n,r,p,q", [(96, 160, 8, 4, 1), (160, 96, 8, 4, 0), (300, 260, 24, 8, 2),
                                        (640, 600, 552, 8, 1)])
 def test_refresh_well_separated_spectrum(tsr, m, n, r, p, q):
@@ -595,6 +595,35 @@ def test_refresh_batched_matches_single(tsr):
         U_ref, V_ref, _ = orc.refresh_rsvd(h["G"][0], om, r, p, q)
         assert projector_err(b["U"], U_ref) < TOL_F32 and projector_err(b["V"], V_ref) < TOL_F32
         check_orthonormal(b["U"]); check_orthonormal(b["V"])
+    plan.close()
+
+
+@pytest.mark.parametrize("groups", [1, 2, 3])
+def test_refresh_batched_in_groups(tsr, groups, monkeypatch):
+    # twelve blocks of mixed shapes and dtypes: the batched refresh cuts them into groups that run
+    # side by side on streams of the plan; followed at once by work on the caller's stream
+    # (the steps), which must see the refreshed bases.  Every grouping gives the same answer.
+    monkeypatch.setenv("TSR_TUNE_REFRESH_GROUPS", str(groups))
+    shapes = [(192, 256), (256, 192), (320, 320), (130, 264)] * 3
+    r, p, q = 16, 8, 1
+    blocks, host = make_blocks(shapes, r, 1, torch.float32, 711, noise=1e-3)
+    for i, (b, h, (m, n)) in enumerate(zip(blocks, host, shapes)):
+        G64, _, _ = si.exact_lowrank(m, n, r, si.stream_key(712, i))
+        h["G"] = (G64.float() + si.normal((m, n), si.stream_key(713, i), std=1e-3))[None]
+        b["G"].copy_(h["G"][0])
+    plan = tsr.Plan(blocks, with_refresh=True, p=p)
+    omegas = [si.omega(n, r + p, si.stream_key(714, i)) for i, (m, n) in enumerate(shapes)]
+    dev_om = [dev(o) for o in omegas]
+    for rep in range(2):                                   # twice: the side streams are reused
+        plan.tsr_refresh_batched(dev_om, q)
+        plan.tsr_step_batched(1 + rep, lr=0.0)             # queued behind the refresh; lr = 0 leaves W alone
+    torch.cuda.synchronize()
+    for b, h, om in zip(blocks, host, omegas):
+        U_ref, V_ref, _ = orc.refresh_rsvd(h["G"][0], om, r, p, q)
+        assert projector_err(b["U"], U_ref) < TOL_F32 and projector_err(b["V"], V_ref) < TOL_F32
+        check_orthonormal(b["U"]); check_orthonormal(b["V"])
+        # the step that followed projected with the refreshed bases
+        assert rel_fro(b["C"], orc.project_core(h["G"][0], orc.f64(b["U"]), orc.f64(b["V"]))) < TOL_F32
     plan.close()
 
 
