@@ -265,10 +265,10 @@ void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool o
         q1.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
         g2.push_back(LogicalGemm{Xalt, Xalt, k, k, k, k, rows, b.S, k});
         q2.push_back(LogicalGemm{Xalt, b.Rinv, k, k, rows, k, k, X, k});
-        op.chol1.push_back(CholBlock{b.S, b.Rinv, nullptr, b.R1, b.work, k});
+        op.chol1.push_back(CholBlock{b.S, b.Rinv, b.R1, b.work, k});
         // the second factor goes to Gacc (free until the small SVD); where the product of the two
         // factors is needed, an fp64 MFMA GEMM forms it afterwards (run_refresh_back)
-        op.chol2.push_back(CholBlock{b.S, b.Rinv, nullptr, b.Gacc, b.work, k});
+        op.chol2.push_back(CholBlock{b.S, b.Rinv, b.Gacc, b.work, k});
     }
     // the Cholesky kernels read the lower triangle of the Gram matrix only
     build_stage(op.gram1, variant(1, 1, 0, 2, 2), g1, ar, 512, true);

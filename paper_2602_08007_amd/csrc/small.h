@@ -36,12 +36,12 @@ hipError_t launch_stream(float* dst, const float* src, long long count, float sc
 // ---- Cholesky-based orth helper: from the k x k Gram matrix S (fp32, symmetric) of a
 // tall matrix Y compute, in fp64, S = R^T R and write
 //   Rinv (fp32, k x k upper) = R^-1, so that Y Rinv has orthonormal columns,
-//   Rtot (fp64, k x k upper, optional) = R * Rprev (Rprev optional = identity).
-// A pivot at or below tol * S[j][j] marks column j as dependent: row/column j of Rinv and
-// row j of Rtot become zero.  work = 2 k x k doubles per matrix.
+//   Rtot (fp64, k x k upper, optional) = R.
+// Only the lower triangle of S is read.  A pivot at or below tol * S[j][j] marks column j as
+// dependent: row/column j of Rinv and row j of Rtot become zero.  work = 2 k x k doubles per matrix.
 struct CholBlock {
     const float* S; float* Rinv;
-    const double* Rprev; double* Rtot;
+    double* Rtot;
     double* work;
     int k;
 };

@@ -208,21 +208,12 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_kernel(const CholBlock
         const int a = idx / k, b = idx % k;
         Rinv[idx] = (a <= b) ? (float)X[(size_t)b * k + a] : 0.0f;
     }
-    // Rtot = R Rprev with R = L^T
+    // Rtot = R = L^T
     double* Rtot = blk->Rtot;
     if (Rtot != nullptr) {
-        const double* Rp = blk->Rprev;
         for (int idx = tid; idx < k * k; idx += nt) {
             const int a = idx / k, b = idx % k;
-            double s = 0.0;
-            if (a <= b) {
-                if (Rp == nullptr) {
-                    s = A[(size_t)b * k + a];
-                } else {
-                    for (int c = a; c <= b; ++c) s += A[(size_t)c * k + a] * Rp[(size_t)c * k + b];
-                }
-            }
-            Rtot[idx] = s;
+            Rtot[idx] = (a <= b) ? A[(size_t)b * k + a] : 0.0;
         }
     }
 }
@@ -443,48 +434,12 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
         const int a = idx / k, b = idx % k;
         Rinv[idx] = (a <= b) ? (float)X[(size_t)b * k + a] : 0.0f;
     }
-    // Rtot = R Rprev with R = L^T: both upper triangular, so entry (a, b) sums over a <= c <= b;
-    // 4 x 4 register tiles (rows of L^T are columns of A: four consecutive doubles per load)
+    // Rtot = R = L^T
     double* Rtot = blk->Rtot;
     if (Rtot != nullptr) {
-        const double* Rp = blk->Rprev;
-        if (Rp == nullptr) {
-            for (int idx = tid; idx < k * k; idx += SMALL_THREADS) {
-                const int a = idx / k, b = idx % k;
-                Rtot[idx] = (a <= b) ? A[(size_t)b * k + a] : 0.0;
-            }
-        } else {
-            const int tiles = (k + 3) >> 2;
-            for (int q = tid; q < tiles * tiles; q += SMALL_THREADS) {
-                const int a0 = (q / tiles) * 4, b0 = (q % tiles) * 4;
-                double acc[4][4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
-                if (b0 >= a0) {
-                    const int cend = min(k, b0 + 4);
-#pragma unroll 2
-                    for (int c = a0; c < cend; ++c) {
-                        double lv[4], rv[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            // A holds L in its lower triangle and zeros above it
-                            lv[u] = (a0 + u < k) ? A[(size_t)c * k + a0 + u] : 0.0;
-                            rv[u] = (b0 + u < k) ? Rp[(size_t)c * k + b0 + u] : 0.0;
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) acc[u][v] += lv[u] * rv[v];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (a0 + u < k && b0 + v < k) Rtot[(size_t)(a0 + u) * k + b0 + v] = (a0 + u <= b0 + v) ? acc[u][v] : 0.0;
-            }
+        for (int idx = tid; idx < k * k; idx += SMALL_THREADS) {
+            const int a = idx / k, b = idx % k;
+            Rtot[idx] = (a <= b) ? A[(size_t)b * k + a] : 0.0;
         }
     }
 }
