@@ -218,12 +218,14 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_kernel(const CholBlock
     }
 }
 
-// Blocked variant for k <= CHB_MAXK: 32-wide block columns.  Per block column the diagonal
-// block is factored and inverted in LDS, the panel below it is multiplied by that inverse and
-// kept in LDS, and the trailing matrix gets its rank-32 update from the LDS panel in 4 x 4
-// register tiles, so the fp64 matrix in global memory is read and written once per block
-// column instead of once per column.  The inverse is assembled block row by block row from
-// the inverted diagonal blocks.
+// Blocked variant for k <= CHB_MAXK, three launches.  First (this kernel, one workgroup per
+// matrix): 32-wide block columns; per block column the diagonal block is factored and inverted
+// in LDS, the panel below it is multiplied by that inverse and kept in LDS, and the trailing
+// matrix gets its rank-32 update from the LDS panel (fp64 MFMAs), so the fp64 matrix in global
+// memory is read and written once per block column instead of once per column.  It leaves L in
+// the lower triangle of `work` and the inverted diagonal blocks in the second k x k of `work`;
+// chol_inverse_kernel then forms the blocks of L^-1 below the diagonal and chol_output_kernel
+// writes R^-1 (fp32) and R.
 __device__ inline double readlane_f64(double v, int lane) {      // lane: a compile-time constant
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
@@ -365,81 +367,123 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
         }
         __syncthreads();
     }
+}
 
-    // ---- off-diagonal blocks of X = L^-1, block column by block column (forward substitution
-    // with 32 right-hand sides):  X[I][J] = -Li_I * sum_{K=J}^{I-1} L[I][K] X[K][J].
-    // The block column of X stays in the panel buffer (block K - J at rows (K - J) * 32); the
-    // 32 x 32 products run on fp64 MFMAs (v_mfma_f64_16x16x4: lane l supplies A[l % 16][l / 16]
-    // and B[l / 16][l % 16], receives D[4 v + l / 16][l % 16]), one 16 x 16 tile on each of
-    // the first four waves, the blocks of L straight from global memory.
+// Second launch of the blocked variant: the blocks of X = L^-1 below the diagonal, block column by
+// block column (forward substitution with 32 right-hand sides):
+//     X[I][J] = -Li_I * sum_{K=J}^{I-1} L[I][K] X[K][J].
+// Block columns are independent; CHOL_INV_SPLIT workgroups per matrix share them (column J costs
+// about nblk - 1 - J block rows, so they are dealt from both ends).  The block column of X stays
+// in LDS (block K - J at rows (K - J) * 32); the 32 x 32 products run on fp64 MFMAs
+// (v_mfma_f64_16x16x4: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16], receives
+// D[4 v + l / 16][l % 16]), one 16 x 16 tile per wave, the blocks of L straight from global memory.
+constexpr int CHOL_INV_SPLIT = 3;
+__global__ __launch_bounds__(256) void chol_inverse_kernel(const CholBlock* table, const CholBlock single, const int n_blocks) {
+    const int b = blockIdx.x / CHOL_INV_SPLIT, part = blockIdx.x % CHOL_INV_SPLIT;
+    if (b >= n_blocks) return;
+    CholBlock cb = single;
+    if (table) cb = table[b];
+    const int k = cb.k;
+    const double* A = cb.work;                 // L in the lower triangle
+    double* X = cb.work + (size_t)k * k;       // diagonal blocks hold the inverted diagonal blocks of L
+    typedef double d4_t __attribute__((ext_vector_type(4)));
+    const int tid = threadIdx.x;
+    const int wv = tid >> 6, li16 = tid & 15, lk4 = (tid & 63) >> 4;
+    const int tr = (wv >> 1) & 1, tcb = wv & 1;
+    __shared__ double Ld[CHB][CHB_P];
+    extern __shared__ double Pn[];             // [block rows * CHB][CHB_P]
     const int nblk = (k + CHB - 1) / CHB;
-    {
-        const int tr = (wv >> 1) & 1, tcb = wv & 1;
-        for (int J = 0; J + 1 < nblk; ++J) {
-            Pn[ti * CHB_P + tc] = X[(size_t)(J * CHB + ti) * k + J * CHB + tc];      // J < nblk - 1: a full block
-            __syncthreads();
-            for (int I = J + 1; I < nblk; ++I) {
-                const int ib = min(CHB, k - I * CHB);
-                const int lr = 16 * tr + li16;                 // this lane's row of the A operand
-                const bool rok = lr < ib;
-                if (wv < 4) {
-                    d4_t acc = {0.0, 0.0, 0.0, 0.0};
-                    const double* lrow = A + (size_t)(I * CHB + min(lr, ib - 1)) * k + lk4;
-                    double an[8];
+    const int ncol = nblk - 1;                 // block columns with blocks below the diagonal
+    // columns 0, 1, 2, ... go to parts 0, 1, 2, 2, 1, 0, 0, 1, ...: long and short columns mix
+    for (int J = 0; J < ncol; ++J) {
+        const int pos = J % (2 * CHOL_INV_SPLIT);
+        const int owner = (pos < CHOL_INV_SPLIT) ? pos : 2 * CHOL_INV_SPLIT - 1 - pos;
+        if (owner != part) continue;           // uniform over the workgroup
+        for (int e = tid; e < CHB * CHB; e += 256)
+            Pn[(e >> 5) * CHB_P + (e & 31)] = X[(size_t)(J * CHB + (e >> 5)) * k + J * CHB + (e & 31)];   // J < nblk - 1: a full block
+        __syncthreads();
+        for (int I = J + 1; I < nblk; ++I) {
+            const int ib = min(CHB, k - I * CHB);
+            const int lr = 16 * tr + li16;                 // this lane's row of the A operand
+            const bool rok = lr < ib;
+            {
+                d4_t acc = {0.0, 0.0, 0.0, 0.0};
+                const double* lrow = A + (size_t)(I * CHB + min(lr, ib - 1)) * k + lk4;
+                double an[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) an[q] = lrow[J * CHB + 4 * q];
-                    for (int K = J; K < I; ++K) {
-                        double a[8];
+                for (int q = 0; q < 8; ++q) an[q] = lrow[J * CHB + 4 * q];
+                for (int K = J; K < I; ++K) {
+                    double a[8];
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) a[q] = rok ? an[q] : 0.0;
-                        if (K + 1 < I) {
+                    for (int q = 0; q < 8; ++q) a[q] = rok ? an[q] : 0.0;
+                    if (K + 1 < I) {
 #pragma unroll
-                            for (int q = 0; q < 8; ++q) an[q] = lrow[(K + 1) * CHB + 4 * q];
-                        }
-                        const double* xb = Pn + (size_t)((K - J) * CHB + lk4) * CHB_P + 16 * tcb + li16;
-#pragma unroll
-                        for (int q = 0; q < 8; ++q)
-                            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], xb[4 * q * CHB_P], acc, 0, 0, 0);
+                        for (int q = 0; q < 8; ++q) an[q] = lrow[(K + 1) * CHB + 4 * q];
                     }
+                    const double* xb = Pn + (size_t)((K - J) * CHB + lk4) * CHB_P + 16 * tcb + li16;
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) Ld[16 * tr + 4 * v + lk4][16 * tcb + li16] = acc[v];
+                    for (int q = 0; q < 8; ++q)
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], xb[4 * q * CHB_P], acc, 0, 0, 0);
                 }
-                __syncthreads();
-                if (wv < 4) {
-                    d4_t acc = {0.0, 0.0, 0.0, 0.0};
-                    const double* xd = X + (size_t)(I * CHB + min(lr, ib - 1)) * k + I * CHB;
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        const int c = 4 * q + lk4;
-                        const double a = (rok && c < ib) ? xd[min(c, ib - 1)] : 0.0;     // Li_I, lower triangular
-                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Ld[c][16 * tcb + li16], acc, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int r = 16 * tr + 4 * v + lk4, cc = 16 * tcb + li16;
-                        const double val = -acc[v];
-                        Pn[((I - J) * CHB + r) * CHB_P + cc] = val;                      // rows past the matrix: zero
-                        if (r < ib) X[(size_t)(I * CHB + r) * k + J * CHB + cc] = val;
-                    }
-                }
-                __syncthreads();
+                for (int v = 0; v < 4; ++v) Ld[16 * tr + 4 * v + lk4][16 * tcb + li16] = acc[v];
             }
+            __syncthreads();
+            {
+                d4_t acc = {0.0, 0.0, 0.0, 0.0};
+                const double* xd = X + (size_t)(I * CHB + min(lr, ib - 1)) * k + I * CHB;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int c = 4 * q + lk4;
+                    const double a = (rok && c < ib) ? xd[min(c, ib - 1)] : 0.0;     // Li_I, lower triangular
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Ld[c][16 * tcb + li16], acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int r = 16 * tr + 4 * v + lk4, cc = 16 * tcb + li16;
+                    const double val = -acc[v];
+                    Pn[((I - J) * CHB + r) * CHB_P + cc] = val;                      // rows past the matrix: zero
+                    if (r < ib) X[(size_t)(I * CHB + r) * k + J * CHB + cc] = val;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Third launch: Rinv = X^T (upper triangular, fp32) and, if asked for, Rtot = L^T (fp64), by
+// 32 x 32 tiles transposed through LDS; one workgroup per tile of the output.
+__global__ __launch_bounds__(256) void chol_output_kernel(const CholBlock* table, const CholBlock single, const int n_blocks,
+                                                          const int tiles) {
+    const int b = blockIdx.x / (tiles * tiles), t = blockIdx.x % (tiles * tiles);
+    if (b >= n_blocks) return;
+    CholBlock cb = single;
+    if (table) cb = table[b];
+    const int k = cb.k;
+    const int ta = t / tiles, tb = t % tiles;      // output tile: rows ta * 32.., columns tb * 32..
+    if (ta * CHB >= k || tb * CHB >= k) return;
+    const double* A = cb.work;
+    const double* X = cb.work + (size_t)k * k;
+    __shared__ double tx[CHB][CHB_P];
+    __shared__ double tl[CHB][CHB_P];
+    const int tid = threadIdx.x;
+    const bool upper = ta <= tb;                    // tiles below the diagonal are zero
+    if (upper) {
+        for (int e = tid; e < CHB * CHB; e += 256) {
+            const int i = e >> 5, c = e & 31;       // source entry (tb * 32 + i, ta * 32 + c) of the lower triangles
+            const int sr = tb * CHB + i, sc = ta * CHB + c;
+            const bool ok = sr < k && sc < k && sc <= sr;
+            tx[i][c] = ok ? X[(size_t)sr * k + sc] : 0.0;
+            tl[i][c] = (ok && cb.Rtot) ? A[(size_t)sr * k + sc] : 0.0;
         }
     }
     __syncthreads();
-
-    // Rinv = X^T (upper triangular), fp32
-    float* Rinv = blk->Rinv;
-    for (int idx = tid; idx < k * k; idx += SMALL_THREADS) {
-        const int a = idx / k, b = idx % k;
-        Rinv[idx] = (a <= b) ? (float)X[(size_t)b * k + a] : 0.0f;
-    }
-    // Rtot = R = L^T
-    double* Rtot = blk->Rtot;
-    if (Rtot != nullptr) {
-        for (int idx = tid; idx < k * k; idx += SMALL_THREADS) {
-            const int a = idx / k, b = idx % k;
-            Rtot[idx] = (a <= b) ? A[(size_t)b * k + a] : 0.0;
+    for (int e = tid; e < CHB * CHB; e += 256) {
+        const int i = e >> 5, c = e & 31;           // output entry (ta * 32 + i, tb * 32 + c)
+        const int orow = ta * CHB + i, ocol = tb * CHB + c;
+        if (orow < k && ocol < k) {
+            cb.Rinv[(size_t)orow * k + ocol] = upper ? (float)tx[c][i] : 0.0f;
+            if (cb.Rtot) cb.Rtot[(size_t)orow * k + ocol] = upper ? tl[c][i] : 0.0;
         }
     }
 }
@@ -461,6 +505,16 @@ hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, 
             configured = true;
         }
         hipLaunchKernelGGL(chol_inv_blocked_kernel, dim3(blocks), dim3(SMALL_THREADS), lds, stream, table_dev, sb, tol);
+        static thread_local bool configured2 = false;
+        if (!configured2) {
+            hipError_t e = hipFuncSetAttribute((const void*)chol_inverse_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, ((CHB_MAXK + CHB - 1) / CHB) * CHB * CHB_P * 8);
+            if (e != hipSuccess) return e;
+            configured2 = true;
+        }
+        hipLaunchKernelGGL(chol_inverse_kernel, dim3(blocks * CHOL_INV_SPLIT), dim3(256), lds, stream, table_dev, sb, blocks);
+        const int tiles = (max_k + CHB - 1) / CHB;
+        hipLaunchKernelGGL(chol_output_kernel, dim3(blocks * tiles * tiles), dim3(256), 0, stream, table_dev, sb, blocks, tiles);
     } else {
         hipLaunchKernelGGL(chol_inv_kernel, dim3(blocks), dim3(SMALL_THREADS), 0, stream, table_dev, sb, tol);
     }
