@@ -754,7 +754,7 @@ hipError_t launch_eig_svd(const JacobiBlock* table_dev, const JacobiBlock* singl
     else if (max_k <= 96) hipLaunchKernelGGL((eig_backtransform_kernel<24, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb, gbt);
     else if (max_k <= 160) hipLaunchKernelGGL((eig_backtransform_kernel<40, 4>), bt_grid, dim3(256), 0, stream, table_dev, sb, gbt);
     else if (max_k <= 320) hipLaunchKernelGGL((eig_backtransform_kernel<40, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb, gbt);
-    else hipLaunchKernelGGL((eig_backtransform_kernel<72, 8>), bt_grid, dim3(512), 0, stream, table_dev, sb, gbt);
+    else hipLaunchKernelGGL((eig_backtransform_kernel<40, 16>), bt_grid, dim3(1024), 0, stream, table_dev, sb, gbt);
     hipLaunchKernelGGL(eig_gemm_kernel<1>, eig_grid(gt), dim3(256), 0, stream, table_dev, sb, gt);
     hipLaunchKernelGGL(eig_finish_kernel, dim3(blocks), dim3(EIG_THREADS), 0, stream, table_dev, sb);
     return hipGetLastError();
