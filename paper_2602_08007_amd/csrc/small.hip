@@ -409,21 +409,33 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const CholBlock* tabl
             {
                 d4_t acc = {0.0, 0.0, 0.0, 0.0};
                 const double* lrow = A + (size_t)(I * CHB + min(lr, ib - 1)) * k + lk4;
-                double an[8];
+                // the blocks of L of this block row travel four products ahead of their use (each
+                // product is eight MFMAs, far shorter than a trip to L2 or beyond)
+                double an[4][8];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) an[q] = lrow[J * CHB + 4 * q];
-                for (int K = J; K < I; ++K) {
-                    double a[8];
+                for (int d = 0; d < 4; ++d)
+                    if (J + d < I) {
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) a[q] = rok ? an[q] : 0.0;
-                    if (K + 1 < I) {
-#pragma unroll
-                        for (int q = 0; q < 8; ++q) an[q] = lrow[(K + 1) * CHB + 4 * q];
+                        for (int q = 0; q < 8; ++q) an[d][q] = lrow[(J + d) * CHB + 4 * q];
                     }
-                    const double* xb = Pn + (size_t)((K - J) * CHB + lk4) * CHB_P + 16 * tcb + li16;
+                for (int K0 = J; K0 < I; K0 += 4) {
 #pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], xb[4 * q * CHB_P], acc, 0, 0, 0);
+                    for (int d = 0; d < 4; ++d) {
+                        const int K = K0 + d;
+                        if (K < I) {                               // uniform
+                            double a[8];
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) a[q] = rok ? an[d][q] : 0.0;
+                            if (K + 4 < I) {
+#pragma unroll
+                                for (int q = 0; q < 8; ++q) an[d][q] = lrow[(K + 4) * CHB + 4 * q];
+                            }
+                            const double* xb = Pn + (size_t)((K - J) * CHB + lk4) * CHB_P + 16 * tcb + li16;
+#pragma unroll
+                            for (int q = 0; q < 8; ++q)
+                                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], xb[4 * q * CHB_P], acc, 0, 0, 0);
+                        }
+                    }
                 }
 #pragma unroll
                 for (int v = 0; v < 4; ++v) Ld[16 * tr + 4 * v + lk4][16 * tcb + li16] = acc[v];
