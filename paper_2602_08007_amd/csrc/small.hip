@@ -291,21 +291,47 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
             }
         }
         __syncthreads();
-        // ---- inverse of the diagonal block (dropped pivots: zero row and column); column c on
-        // lane c, four partial sums per entry
+        // ---- inverse of the diagonal block (dropped pivots: zero row and column), by halves:
+        // the four 8 x 8 diagonal sub-blocks by forward substitution (a column per lane), then the
+        // blocks below them from  X21 = -X22 (L21 X11)  at sizes 8 and 16, every entry of a product
+        // on its own thread; the panel buffer (free at this point) holds the inner products.
+        Li[ti][tc] = 0.0;
+        __syncthreads();
         if (tid < CHB) {
-            const int c = tid;
-            double xc[CHB];
+            const int d0 = tid & ~7, c = tid & 7;             // sub-block origin, column inside it
+            double xc[8];
 #pragma unroll
-            for (int i = 0; i < CHB; ++i) {
-                double sa[4] = {(i == c) ? 1.0 : 0.0, 0.0, 0.0, 0.0};
+            for (int i = 0; i < 8; ++i) {
+                double sa = (i == c) ? 1.0 : 0.0;
 #pragma unroll
-                for (int j = 0; j < i; ++j) sa[j & 3] -= Ld[i][j] * xc[j];
-                xc[i] = ((sa[0] + sa[1]) + (sa[2] + sa[3])) * s_invd[i];
-                Li[i][c] = xc[i];
+                for (int j = 0; j < i; ++j) sa -= Ld[d0 + i][d0 + j] * xc[j];
+                xc[i] = sa * s_invd[d0 + i];
+                Li[d0 + i][d0 + c] = xc[i];
             }
         }
         __syncthreads();
+#pragma unroll
+        for (int half = 8; half <= 16; half *= 2) {
+            // pairs of neighbouring diagonal blocks of size `half`: rows r0 + half .., columns r0 ..
+            const int npair = CHB / (2 * half);
+            const int per = half * half;
+            const bool mine = tid < npair * per;
+            const int pr = tid / per, e = tid % per;
+            const int i = e / half, c = e % half;
+            const int o = pr * 2 * half;                      // origin of the pair
+            if (mine) {
+                double m = 0.0;                               // (L21 X11)[i][c]
+                for (int j = c; j < half; ++j) m += Ld[o + half + i][o + j] * Li[o + j][o + c];
+                Pn[(o + half + i) * CHB_P + o + c] = m;
+            }
+            __syncthreads();
+            if (mine) {
+                double x = 0.0;                               // (X22 M)[i][c]
+                for (int j = 0; j <= i; ++j) x += Li[o + half + i][o + half + j] * Pn[(o + half + j) * CHB_P + o + c];
+                Li[o + half + i][o + c] = -x;
+            }
+            __syncthreads();
+        }
         if (ti < jb && tc < jb) {
             A[(size_t)(J + ti) * k + J + tc] = (tc <= ti) ? Ld[ti][tc] : 0.0;
             X[(size_t)(J + ti) * k + J + tc] = (tc <= ti) ? Li[ti][tc] : 0.0;
