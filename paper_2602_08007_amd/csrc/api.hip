@@ -864,7 +864,13 @@ int tsr_plan_create(const tsr_matrix_desc* descs, int count, int n_workers, int 
             ok = ok && hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess;
             if (ev) pl->joined.push_back(ev);
         }
-        if (!ok) { delete pl; return hip_fail(hipGetLastError()); }
+        if (!ok) {
+            // no side streams to be had: the refresh then runs as one program on the caller's stream
+            (void)hipGetLastError();
+            for (hipStream_t sg : pl->side) (void)hipStreamDestroy(sg);
+            for (hipEvent_t ev : pl->joined) (void)hipEventDestroy(ev);
+            pl->side.clear(); pl->joined.clear();
+        }
     }
     *plan_out = pl;
     return TSR_OK;
