@@ -378,7 +378,7 @@ __global__ __launch_bounds__(256) void eig_values_kernel(const JacobiBlock* tabl
 
 // Eigenvectors by inverse iteration, vector j on its own thread, one wave per workgroup (the
 // recurrences are serial in the row index and wait on L2 for their operands: a wave alone on
-// its SIMD; eight rows are fetched at a time).  T - lambda I = P L U with
+// its SIMD; up to sixteen rows are fetched at a time).  T - lambda I = P L U with
 // partial pivoting; U (three diagonals, pivots as reciprocals) is kept, L is applied to the
 // right-hand side while it is formed and formed again in every round.
 __global__ __launch_bounds__(64) void eig_invit_kernel(const JacobiBlock* table, const JacobiBlock single, const EigGrid grid) {
@@ -408,6 +408,8 @@ __global__ __launch_bounds__(64) void eig_invit_kernel(const JacobiBlock* table,
         return;
     }
     const double tiny = EIG_EPS * tnorm;                 // floor of an LU pivot
+    int vz;                                              // a zero the compiler keeps in a vector register
+    asm volatile("v_mov_b32 %0, 0" : "=v"(vz));
     if (j < k) {
         const double lam = LAM[j];
         double* zc = Z + j;
@@ -447,12 +449,12 @@ __global__ __launch_bounds__(64) void eig_invit_kernel(const JacobiBlock* table,
             };
             {
                 int i = 0;
-                for (; i + 8 < k; i += 8) {                  // rows i+1 .. i+8 fetched together
-                    double yn[8];
+                for (; i + 16 < k; i += 16) {                // rows i+1 .. i+16 fetched together
+                    double yn[16];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) yn[u] = yval(i + 1 + u);
+                    for (int u = 0; u < 16; ++u) yn[u] = yval(i + 1 + u);
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) step(i + u, yn[u]);
+                    for (int u = 0; u < 16; ++u) step(i + u, yn[u]);
                 }
                 for (; i + 1 < k; ++i) step(i, yval(i + 1));
             }
@@ -462,19 +464,20 @@ __global__ __launch_bounds__(64) void eig_invit_kernel(const JacobiBlock* table,
                 if (round == 0) { u0[(size_t)(k - 1) * k] = eig_rcp(piv); u1[(size_t)(k - 1) * k] = 0.0; u2[(size_t)(k - 1) * k] = 0.0; }
                 zc[(size_t)(k - 1) * k] = ycur;
             }
-            // backward: U x = y, eight rows fetched together
+            // backward: U x = y, sixteen rows fetched together (row offsets kept in vector registers:
+            // as wave-uniform values they would need more scalar registers than there are)
             double x1 = 0.0, x2 = 0.0, amax = 0.0;      // x[i+1], x[i+2]
             bool bad = false;
             int i = k - 1;
-            for (; i >= 7; i -= 8) {
-                double y[8], p0[8], p1[8], p2[8];
+            for (; i >= 15; i -= 16) {
+                double y[16], p0[16], p1[16], p2[16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const size_t o = (size_t)(i - u) * k;
+                for (int u = 0; u < 16; ++u) {
+                    const size_t o = (size_t)(i - u + vz) * k;
                     y[u] = zc[o]; p0[u] = u0[o]; p1[u] = u1[o]; p2[u] = u2[o];
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 16; ++u) {
                     const double x = (y[u] - p1[u] * x1 - p2[u] * x2) * p0[u];
                     zc[(size_t)(i - u) * k] = x;
                     amax = fmax(amax, fabs(x));
