@@ -424,7 +424,7 @@ void upload_refresh(RefreshProgram& rp, Arena& ar, Uploader& up) {
 int refresh_group_count(int blocks) {
     const char* e = getenv("TSR_TUNE_REFRESH_GROUPS");
     int g = e ? atoi(e) : 3;
-    g = std::max(1, std::min(g, 8));
+    g = std::max(1, std::min(g, 4));       // one stream per group: beyond the four hardware queues of a process they serialise
     while (g > 1 && blocks / g < 4) --g;
     return g;
 }
