@@ -185,7 +185,7 @@ int tsr_realign_moment(const float* U_old, const float* V_old, const float* U_ne
  * p is the refresh oversampling (the plan reserves refresh scratch only if with_refresh).
  * tsr_plan_create synchronizes the stream once (table upload); of the other calls only
  * tsr_refresh_batched does (see there).  A plan with refresh of 8 blocks and more also owns
- * up to two HIP streams and three events (host objects, released by tsr_plan_destroy). */
+ * up to three HIP streams and four events (host objects, released by tsr_plan_destroy). */
 typedef struct tsr_plan tsr_plan;
 size_t tsr_plan_workspace_bytes(const tsr_matrix_desc* descs, int count, int n_workers,
                                 int precision, int with_refresh, int p);
@@ -214,7 +214,8 @@ int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream);
 
 /* Refresh (U, V) of every block from worker 0's gradient (randomized SVD, Algorithm 1's
  * refresh step).  Omegas is a HOST array of `count` device pointers (block i: n_i x (r_i + p)).
- * Plans of 8 blocks and more run the refresh as up to three groups of blocks side by side: group
+ * Plans of 8 blocks and more run the refresh as a few groups of blocks (three by default, at
+ * most four) side by side: group
  * 0 on `stream`, the others on streams the plan owns (default priority), which start after the
  * work already queued on `stream` and which `stream` waits for before the call returns its
  * place in the queue to the caller; for the caller the call is ordered on `stream` like every
