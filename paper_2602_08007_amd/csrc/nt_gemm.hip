@@ -447,15 +447,14 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
 // DEPTH: k-tiles in flight in registers (gradient tile stages and V^T fragment slots).  A
 // workgroup streams its own rows of G from HBM, so the loop runs at memory latency / DEPTH per
 // k-tile until DEPTH k-tiles of MFMAs cover that latency.
-template <int RG, int TN, int DEPTH, int MINB>
-__global__ __launch_bounds__(NT_THREADS, MINB) void proj_kernel(const ProjItem* items) {
-    constexpr int BK = 64, KP = BK + 8;
+constexpr int PROJ_BK = 64, PROJ_KP = PROJ_BK + 8;
+
+template <int RG, int TN, int DEPTH>
+__device__ __forceinline__ void proj_panel(const ProjItem& it, unsigned short* lds) {
+    constexpr int BK = PROJ_BK, KP = PROJ_KP;
     constexpr int FM = RG / 4, FN = TN / 32;
     static_assert(RG % 4 == 0, "r must be a multiple of 128");
     static_assert(DEPTH == 2 || DEPTH == 4, "ring sizes the loop is unrolled for");
-    __shared__ __attribute__((aligned(16))) unsigned short lds[2 * TN * KP];
-    const ProjItem it = items[blockIdx.x];
-    if (it.G == nullptr) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int m = it.m, n = it.n, row0 = it.row0;
@@ -545,6 +544,14 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void proj_kernel(const ProjItem* 
                 __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_bits(acc[i][j][e]), rP, (int)vo, 0, 0);
             }
         }
+}
+
+template <int RG, int TN, int DEPTH, int MINB>
+__global__ __launch_bounds__(NT_THREADS, MINB) void proj_kernel(const ProjItem* items) {
+    __shared__ __attribute__((aligned(16))) unsigned short lds[2 * TN * PROJ_KP];
+    const ProjItem it = items[blockIdx.x];
+    if (it.G == nullptr) return;
+    proj_panel<RG, TN, DEPTH>(it, lds);
 }
 
 bool proj_supports_rank(int r) { return r == 128 || r == 256; }
