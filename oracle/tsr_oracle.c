@@ -317,3 +317,14 @@ int orc_num_threads(void) {
     return 1;
 #endif
 }
+
+/* Number of OpenMP threads the products use from now on (timing runs at one thread and at all
+ * threads; no effect on any result: each output element is summed by one thread in a fixed order). */
+void orc_set_num_threads(int n) {
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

@@ -33,6 +33,11 @@ def num_threads() -> int:
     return int(_lib.orc_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """OpenMP threads of the products from now on (timing only; results do not depend on it)."""
+    _lib.orc_set_num_threads(_i(int(n)))
+
+
 def matmul(A, B, ta=False, tb=False):
     """op(A) op(B) by triple loops; supports NN, TN (A^T B) and NT (A B^T)."""
     A, B = f64(A), f64(B)

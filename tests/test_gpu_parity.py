@@ -10,7 +10,7 @@ import torch
 
 import synth_inputs as si
 from oracle import tsr_oracle as orc
-from gpu_util import B1, B2, EPS, dev, f32, padded, projector_err, rel_fro
+from gpu_util import B1, B2, EPS, check_close, dev, f32, max_abs_rel, padded, parity_log, plan_trajectory, projector_err, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -97,10 +97,10 @@ def test_project_core(tsr, m, n, r, dtype, ld, prec):
     tsr.tsr_project_core(Gd, dev(U), dev(V), C, precision=precision)
     torch.cuda.synchronize()
     tol = TOL_F32 if prec == "split" else TOL_BF16
-    assert rel_fro(C, C_ref) < tol
+    check_close(C, C_ref, tol, "core")
     # alpha / accumulate: C <- C + 0.5 * core
     tsr.tsr_project_core(Gd, dev(U), dev(V), C, alpha=0.5, accumulate=True, precision=precision)
-    assert rel_fro(C, 1.5 * C_ref) < tol
+    check_close(C, 1.5 * C_ref, tol, "accumulated core")
 
 
 def test_project_core_identity_closed_form(tsr):
@@ -149,10 +149,10 @@ def test_backproject_apply(tsr, m, n, r, ld, prec):
     tsr.tsr_backproject_apply(Wd, dev(U), dev(V), dev(D), lr, wd, scale, precision=precision)
     torch.cuda.synchronize()
     tol = TOL_F32 if prec == "split" else TOL_BF16
-    assert rel_fro(Wd, W_ref) < tol
+    check_close(Wd, W_ref, tol, "weights")
     # the update itself (not hidden behind the much larger W)
     dW = orc.f64(Wd) - orc.f64(W0)
-    assert rel_fro(dW, dW_ref) < (2e-4 if prec == "split" else TOL_BF16)
+    check_close(dW, dW_ref, 2e-4 if prec == "split" else TOL_BF16, "movement")
     if ld:   # padding columns untouched
         assert torch.count_nonzero(Wd._base[:, n:]).item() == 0 if Wd._base is not None else True
 
@@ -258,7 +258,8 @@ def test_refresh_config1(tsr):
     assert rel_fro(sigma, S_ref) < TOL_F32
     gap = (S_ref[w.r - 1] - S_ref[w.r]) / S_ref[0]
     eu, ev = projector_err(U, U_ref), projector_err(V, V_ref)
-    print("config1 refresh: relative gap %.3e projector errors %.3e %.3e" % (gap, eu, ev))
+    parity_log("config1 single-60m 512x1376 refresh (r=64 p=8 q=1): relative gap %.2e projector errors U %.2e V %.2e sigma %.2e"
+               % (gap, eu, ev, rel_fro(sigma, S_ref)))
     assert eu < max(TOL_F32, 2e-7 / gap) and ev < max(TOL_F32, 2e-7 / gap)
     # captured energy ||U^T G V||_F agrees
     e_ref = np.linalg.norm(U_ref.T @ orc.f64(G) @ V_ref)
@@ -392,7 +393,8 @@ def test_config1_refresh_then_ten_steps(tsr):
             moved_ref = W - W1
             moved = orc.f64(Wa) - Wa1
             assert np.linalg.norm(moved - moved_ref) / wnorm < TOL_F32, t
-            print("config1 t=%d: D err %.2e, movement err / |movement| %.2e" % (t, rel_fro(Da, D), rel_fro(moved, moved_ref)))
+            parity_log("config1 single-60m t=%d (oracle's bases, refresh gradient = G_1): C=%.2e D=%.2e movement since t=1: %.2e"
+                       % (t, rel_fro(Ca, Cbar), rel_fro(Da, D), rel_fro(moved, moved_ref)))
             assert rel_fro(moved, moved_ref) < 5e-3, t
         tsr.tsr_project_core(Gd, U, V, Cb); tsr.tsr_adam_core(Cb, Mb, Vb, Db, t)
         tsr.tsr_backproject_apply(Wb, U, V, Db, lr)
@@ -401,9 +403,52 @@ def test_config1_refresh_then_ten_steps(tsr):
     # track B: weight movement after the shared step, own bases vs oracle bases (sign free)
     moved_ref = W - W1
     moved_b = orc.f64(Wb) - Wb1
-    print("config1 own-bases: movement error / |W| = %.3e, / |movement| = %.3e"
-          % (np.linalg.norm(moved_b - moved_ref) / wnorm, rel_fro(moved_b, moved_ref)))
+    parity_log("config1 single-60m own bases (GPU refresh): movement error / |W| = %.2e, / |movement| = %.2e"
+               % (np.linalg.norm(moved_b - moved_ref) / wnorm, rel_fro(moved_b, moved_ref)))
     assert np.linalg.norm(moved_b - moved_ref) / wnorm < TOL_F32
+
+
+def test_config1_separate_refresh_gradient_ten_steps(tsr):
+    """The well-posed variant of configuration 1: the bases come from a refresh on a separate draw
+    G_0, then steps 1..10 run on G_1..G_10 with the oracle's bases on both sides and the oracle on
+    its own trajectory (nothing re-synchronised).  No step projects the gradient its bases were
+    computed from, so the core is generic and the absolute weights are comparable: 1e-4 on the
+    core, the moments and W_t at every step, and the bars of the fp32 path on D and on the
+    movement (from step 2 on; D_1 = sign(c) is decided by rounding for the smallest entries)."""
+    w = si.workload("single-60m")
+    m, n = w.shapes[0]
+    r = w.r
+    lr = f32(1e-3)
+    base = si.stream_key(si.BASE_SEED, 1)
+    sig = si.make_signal(m, n, w.signal_rank, w.spectrum, base)
+    W0 = si.weights(m, n, si.stream_key(base, 7))
+    Om = si.omega(n, r + w.p, si.stream_key(base, 99))
+    G0 = si.gradient(sig, w.noise, si.stream_key(base, 500))
+    U_ref, V_ref, _ = orc.refresh_rsvd(G0, Om, r, w.p, w.q)
+    Ur, Vr = dev(torch.from_numpy(U_ref).float()), dev(torch.from_numpy(V_ref).float())
+    Ur64, Vr64 = orc.f64(Ur), orc.f64(Vr)
+    Wd = dev(W0); Md = torch.zeros(r, r, device="cuda"); Vd = torch.zeros(r, r, device="cuda")
+    Cd = torch.empty(r, r, device="cuda"); Dd = torch.empty(r, r, device="cuda")
+    W = orc.f64(W0).copy(); M = np.zeros((r, r)); Vm = np.zeros((r, r))
+    for t in range(1, 11):
+        G = si.gradient(sig, w.noise, si.stream_key(base, 500 + t))
+        W_prev, Wd_prev = W.copy(), orc.f64(Wd).copy()
+        Cbar, D = orc.tsr_adam_step(W, [G], Ur64, Vr64, M, Vm, t, lr=lr, beta1=B1, beta2=B2, eps=EPS)
+        tsr.tsr_project_core(dev(G), Ur, Vr, Cd); tsr.tsr_adam_core(Cd, Md, Vd, Dd, t)
+        tsr.tsr_backproject_apply(Wd, Ur, Vr, Dd, lr)
+        torch.cuda.synchronize()
+        ec, _ = check_close(Cd, Cbar, TOL_F32, "core t=%d" % t)
+        check_close(Md, M, TOL_F32, "first moment t=%d" % t); check_close(Vd, Vm, 2 * TOL_F32, "second moment t=%d" % t)
+        ew, ewm = check_close(Wd, W, TOL_F32, "weights t=%d" % t)
+        ed, em = rel_fro(Dd, D), rel_fro(orc.f64(Wd) - Wd_prev, W - W_prev)
+        parity_log("config1 single-60m t=%d (oracle's bases, refresh gradient G_0 separate): C=%.2e W=%.2e W_max=%.2e D=%.2e move=%.2e"
+                   % (t, ec, ew, ewm, ed, em))
+        if t >= 2:
+            assert ed < 5e-3 and em < 5e-3, (t, ed, em)
+    # the whole displacement after ten steps
+    total = rel_fro(orc.f64(Wd) - orc.f64(W0), W - orc.f64(W0))
+    parity_log("config1 single-60m W_10 - W_0 against the oracle's: %.2e" % total)
+    assert total < 5e-3
 
 
 # ------------------------------------------------------------------ batched plan
@@ -430,7 +475,7 @@ def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3, guard_w=False, pad
         Gs = torch.stack([si.gradient(sig, noise, si.stream_key(k, 10 + w), dtype=g_dtype) for w in range(workers)])
         U, V = bases(m, n, r, k)
         W0 = si.weights(m, n, si.stream_key(k, 4))
-        host.append(dict(G=Gs, U=U, V=V, W=W0))
+        host.append(dict(G=Gs, U=U, V=V, W=W0, sig=sig, key=k, noise=noise, g_dtype=g_dtype, workers=workers))
         Wd, Wfull = guarded(W0) if guard_w else (dev(W0), None)
         host[-1]["W_full"] = Wfull
         Gd = dev(Gs) if workers > 1 else dev(Gs[0])
@@ -446,10 +491,34 @@ def make_blocks(shapes, r, workers, g_dtype, key, noise=1e-3, guard_w=False, pad
     return blocks, host
 
 
+def fresh_gradients(blocks, host):
+    """next_grads for plan_trajectory: a new noise draw per step and worker on the same signal,
+    written into the device buffers the plan was created on (padding, if any, is left alone)."""
+    def put(t):
+        if t == 1:
+            return                      # step 1 runs on the gradients the blocks were made with
+        for b, h in zip(blocks, host):
+            Gs = torch.stack([si.gradient(h["sig"], h["noise"], si.stream_key(h["key"], 1000 * t + w), dtype=h["g_dtype"])
+                              for w in range(h["workers"])])
+            b["G"].copy_(Gs.to("cuda") if h["workers"] > 1 else Gs[0].to("cuda"))
+    return put
+
+
+# Bars of the trajectory checks against the oracle's own trajectory (no re-synchronisation).
+# The normalized update D = mhat / (sqrt(vhat) + eps) divides by the size of the core entry, so an
+# absolute core error e becomes a relative error e / |c| in D: entries of projected noise are three
+# orders of magnitude below the leading ones, which is why D and the movement W_t - W_{t-1} carry
+# a wider bar than the core itself.  Measured values are logged by every test that uses them.
+BAR_D = {"split": 5e-3, "bf16": 5e-2}
+BAR_MOVE = {"split": 5e-3, "bf16": 5e-2}
+BAR_MOVE_OWN = {"split": 2e-4, "bf16": 1e-2}
+
+
 @pytest.mark.parametrize("workers,g_dtype,prec", [(1, torch.float32, "split"), (1, torch.bfloat16, "bf16"),
                                                   (3, torch.bfloat16, "split"), (3, torch.bfloat16, "bf16"),
                                                   (1, torch.float32, "bf16")])
 def test_step_batched_matches_oracle(tsr, workers, g_dtype, prec):
+    # four steps, a fresh gradient at each, the oracle on its own trajectory throughout
     shapes = [(256, 256), (256, 688), (688, 256), (200, 336), (256, 256)]
     r = 32
     blocks, host = make_blocks(shapes, r, workers, g_dtype, si.stream_key(601, workers))
@@ -457,15 +526,9 @@ def test_step_batched_matches_oracle(tsr, workers, g_dtype, prec):
     plan = tsr.Plan(blocks, n_workers=workers, precision=precision)
     assert plan.tsr_plan_kernel_path() == (1 if prec == "bf16" else 0)
     tol = TOL_F32 if prec == "split" else TOL_BF16
-    state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
-    for t in (1, 2, 3):
-        plan.tsr_step_batched(t, lr=1e-3, wd=0.01)
-        torch.cuda.synchronize()
-        for b, h, s in zip(blocks, host, state):
-            Cbar, D = orc.tsr_adam_step(s["W"], [g for g in h["G"]], h["U"], h["V"], s["M"], s["Vm"], t, lr=f32(1e-3),
-                                        wd=f32(0.01), beta1=B1, beta2=B2, eps=EPS)
-            errs = (rel_fro(b["C"], Cbar), rel_fro(b["W"], s["W"]), rel_fro(b["M"], s["M"]))
-            assert max(errs) < tol, (t, errs)
+    plan_trajectory(plan, blocks, range(len(shapes)), (1, 2, 3, 4), tol, "batched-%s-w%d-%s" % (prec, workers, str(g_dtype)[6:]),
+                    wd=0.01, workers=workers, next_grads=fresh_gradients(blocks, host),
+                    bar_d=BAR_D[prec], bar_move=BAR_MOVE[prec], bar_move_own=BAR_MOVE_OWN[prec])
     core, dense = plan.payload_bytes(4)
     assert core == len(shapes) * r * r * 4 and dense == 4 * sum(m * n for m, n in shapes)
     plan.close()
@@ -488,25 +551,12 @@ def test_bf16_plan_fused_lift_ranks(tsr, r, workers, rows16):
                                pad_g=(rows16 == "padded"))
     plan = tsr.Plan(blocks, n_workers=workers, precision=tsr.TSR_PREC_BF16)
     assert plan.tsr_plan_kernel_path() == (1 if rows16 else 0)
-    state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
-    for t in (1, 2):
-        plan.tsr_step_batched(t, lr=1e-3, wd=0.05)
-        torch.cuda.synchronize()
-        for b, h, s in zip(blocks, host, state):
-            W_before = s["W"].copy()
-            Cbar, D = orc.tsr_adam_step(s["W"], [g for g in h["G"]], h["U"], h["V"], s["M"], s["Vm"], t, lr=f32(1e-3),
-                                        wd=f32(0.05), beta1=B1, beta2=B2, eps=EPS)
-            assert rel_fro(b["C"], Cbar) < TOL_BF16
-            # the lift itself, from the GPU's own D (at t = 1 the oracle's D is sign(c), which a
-            # bf16 core flips for the smallest entries; these tiny blocks would show that, not
-            # the kernel): updated weights and the movement relative to the movement
-            W_k = orc.backproject_apply(W_before.copy(), h["U"], h["V"], orc.f64(b["D"]), f32(1e-3), f32(0.05))
-            assert rel_fro(b["W"], W_k) < TOL_BF16
-            moved_gpu = orc.f64(b["W"]) - W_before
-            # GPU W started from its own previous W; compare movements (both include the decay term)
-            assert rel_fro(moved_gpu, W_k - W_before) < 3e-2, (t, rel_fro(moved_gpu, W_k - W_before))
-            s["W"][...] = orc.f64(b["W"])       # keep the trajectories together for the next step
-            assert guards_intact(h["W_full"], *b["W"].shape)    # nothing written outside the m x n block
+
+    def guards(i, t):
+        assert guards_intact(host[i]["W_full"], *blocks[i]["W"].shape)    # nothing written outside the m x n block
+    plan_trajectory(plan, blocks, range(len(shapes)), (1, 2, 3), TOL_BF16, "lift-ranks-r%d-w%d-%s" % (r, workers, rows16),
+                    wd=0.05, workers=workers, next_grads=fresh_gradients(blocks, host),
+                    bar_d=BAR_D["bf16"], bar_move=BAR_MOVE["bf16"], bar_move_own=BAR_MOVE_OWN["bf16"], after_block=guards)
     plan.close()
 
 
@@ -520,27 +570,12 @@ def test_bf16_plan_adam_in_core_epilogue(tsr, r, monkeypatch):
     blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, si.stream_key(641, r), guard_w=True)
     plan = tsr.Plan(blocks, n_workers=1, precision=tsr.TSR_PREC_BF16)
     assert plan.tsr_plan_kernel_path() == 1
-    state = [dict(W=orc.f64(h["W"]).copy(), M=np.zeros((r, r)), Vm=np.zeros((r, r))) for h in host]
-    for t in (1, 2, 3):
-        plan.tsr_step_batched(t, lr=1e-3, wd=0.05)
-        torch.cuda.synchronize()
-        for b, h, s in zip(blocks, host, state):
-            W_before = s["W"].copy()
-            M_before, Vm_before = s["M"].copy(), s["Vm"].copy()
-            Cbar, D = orc.tsr_adam_step(s["W"], [g for g in h["G"]], h["U"], h["V"], s["M"], s["Vm"], t, lr=f32(1e-3),
-                                        wd=f32(0.05), beta1=B1, beta2=B2, eps=EPS)
-            assert rel_fro(b["C"], Cbar) < TOL_BF16
-            assert rel_fro(b["M"], s["M"]) < TOL_BF16 and rel_fro(b["Vm"], s["Vm"]) < 2 * TOL_BF16
-            # Adam itself, from the GPU's own core: moments and direction to fp32 accuracy
-            Mk, Vk = M_before.copy(), Vm_before.copy()
-            Dk = orc.adam_core(orc.f64(b["C"]), Mk, Vk, t, B1, B2, EPS)
-            assert rel_fro(b["M"], Mk) < 1e-5 and rel_fro(b["Vm"], Vk) < 1e-5 and rel_fro(b["D"], Dk) < 1e-4
-            W_k = orc.backproject_apply(W_before.copy(), h["U"], h["V"], orc.f64(b["D"]), f32(1e-3), f32(0.05))
-            assert rel_fro(b["W"], W_k) < TOL_BF16
-            assert rel_fro(orc.f64(b["W"]) - W_before, W_k - W_before) < 3e-2
-            s["W"][...] = orc.f64(b["W"])
-            s["M"][...] = orc.f64(b["M"]); s["Vm"][...] = orc.f64(b["Vm"])
-            assert guards_intact(h["W_full"], *b["W"].shape)
+
+    def guards(i, t):
+        assert guards_intact(host[i]["W_full"], *blocks[i]["W"].shape)
+    plan_trajectory(plan, blocks, range(len(shapes)), (1, 2, 3, 4), TOL_BF16, "adam-epilogue-r%d" % r,
+                    wd=0.05, next_grads=fresh_gradients(blocks, host),
+                    bar_d=BAR_D["bf16"], bar_move=BAR_MOVE["bf16"], bar_move_own=BAR_MOVE_OWN["bf16"], after_block=guards)
     plan.close()
 
 
@@ -638,3 +673,48 @@ def test_determinism_bitwise(tsr):
     C1 = torch.empty(r, r, device="cuda"); C2 = torch.empty(r, r, device="cuda")
     tsr.tsr_project_core(G, U, V, C1); tsr.tsr_project_core(G, U, V, C2)
     assert torch.equal(C1, C2)
+
+
+def _bf16_plan_run(tsr, steps, restart_at=None):
+    """Runs `steps` plan steps of a small bf16 model; with restart_at the plan is destroyed after
+    that many steps and a new one is created on the same caller-owned buffers (a checkpoint is a
+    copy of those buffers: there is no other state).  Returns W, M, Vm of every block."""
+    shapes = [(320, 448), (448, 320), (256, 256), (130, 264)]
+    r = 64
+    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, si.stream_key(901))
+    put = fresh_gradients(blocks, host)
+    plan = tsr.Plan(blocks, precision=tsr.TSR_PREC_BF16)
+    assert plan.tsr_plan_kernel_path() == 1
+    for t in range(1, steps + 1):
+        put(t)
+        plan.tsr_step_batched(t, lr=1e-3, wd=0.01)
+        if restart_at is not None and t == restart_at:
+            torch.cuda.synchronize()
+            plan.close()
+            saved = [{k: b[k].clone() for k in ("W", "U", "V", "M", "Vm")} for b in blocks]      # the checkpoint
+            for b, sv in zip(blocks, saved):
+                for k, v in sv.items():
+                    b[k].zero_(); b[k].copy_(v)                                                    # restored
+            plan = tsr.Plan(blocks, precision=tsr.TSR_PREC_BF16)
+    torch.cuda.synchronize()
+    out = [(b["W"].clone(), b["M"].clone(), b["Vm"].clone()) for b in blocks]
+    plan.close()
+    return out
+
+
+def test_split_run_five_plus_five_equals_ten_bitwise(tsr):
+    # all optimizer state is the caller's flat buffers (W, U, V, m, v and the step count): ten steps
+    # in one go and five + checkpoint / restore / new plan + five give identical bits
+    a = _bf16_plan_run(tsr, 10)
+    b = _bf16_plan_run(tsr, 10, restart_at=5)
+    for (Wa, Ma, Va), (Wb, Mb, Vb) in zip(a, b):
+        assert torch.equal(Wa, Wb) and torch.equal(Ma, Mb) and torch.equal(Va, Vb)
+
+
+def test_whole_step_determinism_bitwise_bf16_plan(tsr):
+    # every reduction of the bf16 plan (k-split partials, worker sums) has a fixed order: two runs
+    # of the same steps give identical bits
+    a = _bf16_plan_run(tsr, 3)
+    b = _bf16_plan_run(tsr, 3)
+    for (Wa, Ma, Va), (Wb, Mb, Vb) in zip(a, b):
+        assert torch.equal(Wa, Wb) and torch.equal(Ma, Mb) and torch.equal(Va, Vb)
