@@ -46,7 +46,9 @@ typedef enum tsr_status {
     TSR_BAD_SHAPE = -2,           /* m, n, r <= 0, r > min(m, n), r + p > min(m, n), ld < n */
     TSR_BAD_DTYPE = -3,
     TSR_WORKSPACE_TOO_SMALL = -4,
-    TSR_HIP_ERROR = -5            /* a HIP runtime call failed (see tsr_last_hip_error)     */
+    TSR_HIP_ERROR = -5,           /* a HIP runtime call failed (see tsr_last_hip_error)     */
+    TSR_STATIC_SCRATCH_TOO_SMALL = -6   /* tsr_project_core_static: the problem needs more scratch than
+                                           TSR_PROJECT_STATIC_SCRATCH_BYTES                          */
 } tsr_status;
 
 /* Storage type of the gradient G (everything else is fp32). */
@@ -99,6 +101,25 @@ int tsr_project_core(const void* G, int g_dtype, int m, int n, long long ldg,
                      const float* U, const float* V, int r,
                      float alpha, int accumulate, float* C, int precision,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------- project, nothing allocated
+ * tsr_project_core for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and kernels as tsr_project_core, minus the workspace: the scratch (P = G V
+ * and the k-split partial cores) lives in a fixed array of TSR_PROJECT_STATIC_SCRATCH_BYTES inside
+ * the library's code object, one copy per GPU, held until the process ends.  The call allocates
+ * and frees no device memory.  A problem whose tsr_project_workspace_bytes(m, n, r) exceeds that
+ * size is refused with TSR_STATIC_SCRATCH_TOO_SMALL before anything is launched (16 MiB covers
+ * e.g. 2048 x 768 at r = 256; use tsr_project_core with a workspace beyond that).  The first
+ * call on a device looks the array's address up once (make that call outside graph capture).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time (different
+ * streams, or host threads) race on it and must be serialised by the caller; calls on one
+ * stream are safe.  Nothing in the array has to be cleared between calls: every value read was
+ * written earlier in the same call. */
+#define TSR_PROJECT_STATIC_SCRATCH_BYTES (16u << 20)
+int tsr_project_core_static(const void* G, int g_dtype, int m, int n, long long ldg,
+                            const float* U, const float* V, int r,
+                            float alpha, int accumulate, float* C, int precision, void* stream);
 
 /* ---------------------------------------------------------------- average (all-reduce stand-in)
  * Cbar = (1/K) sum_i Cs[i], Cs = K consecutive r x r cores, summed in worker order.

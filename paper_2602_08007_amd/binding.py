@@ -14,7 +14,8 @@ import torch
 __all__ = [
     "TSR_F32", "TSR_BF16", "TSR_PREC_SPLIT", "TSR_PREC_BF16", "TsrError", "lib", "lib_path",
     "tsr_status_string", "tsr_device_count",
-    "tsr_stream_scale", "tsr_project_workspace_bytes", "tsr_project_core", "tsr_core_average", "tsr_adam_core", "tsr_sgd_core",
+    "tsr_stream_scale", "tsr_project_workspace_bytes", "tsr_project_core", "tsr_project_core_static",
+    "TSR_PROJECT_STATIC_SCRATCH_BYTES", "tsr_core_average", "tsr_adam_core", "tsr_sgd_core",
     "tsr_backproject_workspace_bytes", "tsr_backproject_apply",
     "tsr_refresh_workspace_bytes", "tsr_refresh_rsvd", "tsr_refresh_workers_workspace_bytes", "tsr_refresh_rsvd_workers",
     "tsr_realign_workspace_bytes", "tsr_realign_moment",
@@ -56,6 +57,7 @@ _last_hip = _sig("tsr_last_hip_error", _i)
 _device_count = _sig("tsr_device_count", _i)
 _project_ws = _sig("tsr_project_workspace_bytes", _sz, _i, _i, _i)
 _project = _sig("tsr_project_core", _i, _vp, _i, _i, _i, _ll, _vp, _vp, _i, _f, _i, _vp, _i, _vp, _sz, _vp)
+_project_static = _sig("tsr_project_core_static", _i, _vp, _i, _i, _i, _ll, _vp, _vp, _i, _f, _i, _vp, _i, _vp)
 _average = _sig("tsr_core_average", _i, _vp, _i, _i, _vp, _vp)
 _stream_scale = _sig("tsr_stream_scale", _i, _vp, _vp, _ll, _f, _vp)
 _adam = _sig("tsr_adam_core", _i, _vp, _vp, _vp, _vp, _ll, _i, _f, _f, _f, _vp)
@@ -151,6 +153,19 @@ def tsr_project_core(G, U, V, C, alpha=1.0, accumulate=False, precision=TSR_PREC
         ws = workspace(tsr_project_workspace_bytes(m, n, r), G.device)
     _check(_project(_ptr(G), _gdtype(G), m, n, _ld(G), _ptr(U), _ptr(V), r, alpha, int(bool(accumulate)), _ptr(C),
                     precision, _ptr(ws), ws.numel(), _stream(stream)))
+    return C
+
+
+TSR_PROJECT_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def tsr_project_core_static(G, U, V, C, alpha=1.0, accumulate=False, precision=TSR_PREC_SPLIT, stream=None):
+    """tsr_project_core on the library's built-in scratch: nothing is allocated, here or there."""
+    m, n = G.shape
+    r = U.shape[1]
+    _f32c(U, V, C)
+    _check(_project_static(_ptr(G), _gdtype(G), m, n, _ld(G), _ptr(U), _ptr(V), r, alpha, int(bool(accumulate)), _ptr(C),
+                           precision, _stream(stream)))
     return C
 
 

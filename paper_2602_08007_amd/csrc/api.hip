@@ -9,6 +9,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -469,6 +470,7 @@ const char* tsr_status_string(int status) {
         case TSR_BAD_DTYPE: return "bad dtype";
         case TSR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case TSR_HIP_ERROR: return "HIP runtime error";
+        case TSR_STATIC_SCRATCH_TOO_SMALL: return "problem needs more scratch than the built-in static buffer holds";
         default: return "unknown status";
     }
 }
@@ -510,6 +512,59 @@ int tsr_project_core(const void* G, int g_dtype, int m, int n, long long ldg, co
     if (ldg < n) return TSR_BAD_SHAPE;
     if (!aligned256(ws)) return TSR_INVALID_ARG;
     if (ws_bytes < tsr_project_workspace_bytes(m, n, r)) return TSR_WORKSPACE_TOO_SMALL;
+    std::vector<BlockView> v;
+    one_block_view(v, G, g_dtype, m, n, r, ldg, nullptr, n, (float*)U, (float*)V, C, nullptr);
+    Arena ar(ws);
+    ProjectProgram pg;
+    build_project(pg, v, 1, precision, ar);
+    Ctx cx{(hipStream_t)stream, nullptr};
+    return run_project(pg, false, alpha, accumulate ? 1.0f : 0.0f, cx);
+}
+
+// ---------------------------------------------------------------- project, nothing allocated
+}  // extern "C"
+
+// Scratch of tsr_project_core_static: a fixed array in the code object, so every device that
+// loads the library holds its own copy at its own address until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels get the looked-up address.
+static __device__ __align__(256) unsigned char scratch[TSR_PROJECT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+    int dev = -1;
+    TSR_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return TSR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        TSR_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr) return TSR_INVALID_ARG;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TSR_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int tsr_project_core_static(const void* G, int g_dtype, int m, int n, long long ldg, const float* U, const float* V,
+                            int r, float alpha, int accumulate, float* C, int precision, void* stream) {
+    TSR_TRY(check_block(m, n, r));
+    TSR_TRY(check_dtype(g_dtype));
+    TSR_TRY(check_prec(precision));
+    if (!G || !U || !V || !C) return TSR_INVALID_ARG;
+    if (ldg < n) return TSR_BAD_SHAPE;
+    if (tsr_project_workspace_bytes(m, n, r) > (size_t)TSR_PROJECT_STATIC_SCRATCH_BYTES) return TSR_STATIC_SCRATCH_TOO_SMALL;
+    void* ws = nullptr;
+    TSR_TRY(static_scratch(&ws));
+    // every byte of the scratch that the kernels read (P = G V and the k-split partial cores) is
+    // written earlier in the same call: nothing has to start at zero, so nothing is cleared
     std::vector<BlockView> v;
     one_block_view(v, G, g_dtype, m, n, r, ldg, nullptr, n, (float*)U, (float*)V, C, nullptr);
     Arena ar(ws);

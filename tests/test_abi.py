@@ -62,6 +62,13 @@ def test_argument_validation_happens_on_the_host(tsr):
     assert f(fake, 0, 8, 8, 8, fake, fake, 4, 1.0, 0, fake, 0, ws, 16, null) == -4
     assert f(fake, 0, 8, 8, 8, fake, fake, 4, 1.0, 0, fake, 0, ctypes.c_void_p(0x10010), 1 << 30, null) == -1
     assert f(fake, 0, 8, 8, 8, fake, fake, 4, 1.0, 0, fake, 5, ws, 1 << 30, null) == -1
+    # the entry point on the built-in scratch: same validation, plus its own size limit (checked
+    # before any device call)
+    fs = lib.tsr_project_core_static
+    assert fs(fake, 0, 8, 8, 8, fake, fake, 9, 1.0, 0, fake, 0, null) == -2
+    assert fs(null, 0, 8, 8, 8, fake, fake, 4, 1.0, 0, fake, 0, null) == -1
+    assert fs(fake, 1, 2048, 5464, 5464, fake, fake, 512, 1.0, 0, fake, 1, null) == -6
+    assert "scratch" in tsr.tsr_status_string(-6)
     # adam: t >= 1, betas in [0, 1)
     g = lib.tsr_adam_core
     assert g(fake, fake, fake, fake, 16, 0, 0.9, 0.999, 1e-8, null) == -1
