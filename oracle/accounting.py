@@ -78,3 +78,28 @@ def tsr_schedule_bytes(shapes: List[Tuple[int, int]], r: int, p: int, K: int, T:
         else:
             out.append(step_bytes((synchronized_elements("tsr", m, n, r) for m, n in shapes), b_dtype))
     return out
+
+
+def exact_svd_refresh_elements(m: int, n: int, r: int) -> int:
+    """Entries synchronized on a refresh step when the refresh is an exact SVD: the dense averaged
+    gradient itself (Section 3.5: an exact SVD needs the full gradient), plus the core."""
+    return r * r + m * n
+
+
+def schedule_bytes(shapes: List[Tuple[int, int]], r: int, p: int, K: int, T: int, method: str = "tsr",
+                   refresh: str = "rsvd", b_dtype: int = 4) -> List[int]:
+    """B_t for t = 1..T (refresh iff t mod K == 0) for the ablation variants: method 'tsr'
+    (r x r cores) or 'one-sided' (r x n objects, Table 1); refresh 'rsvd' (sketches Q and B,
+    Section 3.5) or 'exact' (dense gradient)."""
+    out = []
+    for t in range(1, T + 1):
+        total = 0
+        for m, n in shapes:
+            step = synchronized_elements(method, m, n, r)
+            if t % K == 0:
+                k = r + p
+                total += step + (m * k + k * n if refresh == "rsvd" else m * n)
+            else:
+                total += step
+        out.append(b_dtype * total)
+    return out

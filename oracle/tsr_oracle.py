@@ -218,3 +218,41 @@ def tsr_adam_step(W, G_workers, U, V, M, Vm, t, lr, wd=0.0, beta1=0.9, beta2=0.9
     D = adam_core(Cbar, M, Vm, t, beta1, beta2, eps)
     backproject_apply(W, U, V, D, lr, wd, scale)
     return Cbar, D
+
+
+# ------------------------------------------------------------------ comparison paths of the ablations
+def project_one_sided(G, U):
+    """One-sided projection C1 = U^T G (r x n): the synchronized object of the one-sided row of
+    the table of communication objects (Table 1), compared with the two-sided core in the
+    ablation on two-sidedness (Section 4.3)."""
+    return matmul(U, G, ta=True)
+
+
+def backproject_one_sided(W, U, D1, lr, wd=0.0, scale=1.0):
+    """W <- W - lr (scale U D1 + wd W) with the r x n one-sided update D1, in place on the fp64
+    array W (the lift of the one-sided variant; pre-update W in the decay, as in Algorithm 1)."""
+    dW = matmul(U, D1)
+    W -= lr * (scale * dW + wd * W)
+    return W
+
+
+def one_sided_adam_step(W, G_workers, U, M1, V1, t, lr, wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0):
+    """One iteration of the one-sided variant for one block: project every worker's gradient with
+    U alone, average the r x n objects, Adam on them (the same element-wise lines of Algorithm 1),
+    lift with U and apply.  W, M1, V1 (r x n) in place; returns (C1bar, D1)."""
+    objs = [project_one_sided(G, U) for G in G_workers]
+    C1 = np.zeros_like(objs[0])
+    for c in objs:                      # arithmetic mean, summed in worker order (AR of Algorithm 1)
+        C1 += c
+    C1 /= len(objs)
+    D1 = adam_core(C1, M1, V1, t, beta1, beta2, eps)
+    backproject_one_sided(W, U, D1, lr, wd, scale)
+    return C1, D1
+
+
+def refresh_exact_svd(G, r):
+    """Exact-SVD refresh (what Section 3.5 replaces by the randomized sketch, compared in the
+    ablation on randomized SVD): the r leading singular triplets of the (synchronized) gradient
+    itself, by Jacobi on the matrix.  Returns (U m x r, V n x r, sigma min(m, n))."""
+    Uf, S, Vf = full_svd(G)
+    return np.ascontiguousarray(Uf[:, :r]), np.ascontiguousarray(Vf[:, :r]), S

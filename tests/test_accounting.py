@@ -61,3 +61,27 @@ def test_config5_payload_ratio():
     dense = acc.step_bytes((acc.synchronized_elements("adamw", m, n, 256) for m, n in shapes), 4)
     assert core == 168 * 256 * 256 * 4
     assert dense / core == pytest.approx(27.5, abs=0.1)
+
+
+def test_ablation_byte_ratios_on_60m_shapes():
+    """The two byte claims of the ablation paragraph (Section 4.3) from the formulas of Table 1 and
+    Section 3.5, on the LLaMA-60M block list with the settings of the paper's 60M run (r = 256,
+    embedding rank 64, refresh every 100 steps): two-sided against one-sided cumulative bytes
+    ("approximately two-thirds" less), randomized against exact SVD on the refresh step."""
+    linear = si.model_shapes("60m")
+    r, r_emb, p, K, T = 256, 64, 8, 100, 1000
+    vocab_blocks = [(si.VOCAB, si.LLAMA["60m"]["hidden"])] * 2          # embedding and LM head
+    def total(method, refresh):
+        return (sum(acc.schedule_bytes(linear, r, p, K, T, method, refresh)) +
+                sum(acc.schedule_bytes(vocab_blocks, r_emb, p, K, T, method, refresh)))
+    two, one = total("tsr", "rsvd"), total("one-sided", "rsvd")
+    assert 0.28 < two / one < 0.40, two / one                           # about two-thirds less
+    # the refresh step itself (the peak): sketches k (m + n) against the dense m n
+    peak_rsvd = max(a + b for a, b in zip(acc.schedule_bytes(linear, r, p, K, K), acc.schedule_bytes(vocab_blocks, r_emb, p, K, K)))
+    peak_exact = max(a + b for a, b in zip(acc.schedule_bytes(linear, r, p, K, K, refresh="exact"),
+                                           acc.schedule_bytes(vocab_blocks, r_emb, p, K, K, refresh="exact")))
+    assert 0.40 < peak_rsvd / peak_exact < 0.55, peak_rsvd / peak_exact  # "nearly half"
+    # per-step bytes do not depend on the refresh kind, so over a whole run the two differ less
+    assert total("tsr", "rsvd") < total("tsr", "exact")
+    assert acc.schedule_bytes(linear, r, p, K, 3) == acc.tsr_schedule_bytes(linear, r, p, K, 3)
+    assert acc.exact_svd_refresh_elements(8, 6, 2) == 4 + 48

@@ -49,9 +49,14 @@ def fresh_noise(blocks, key):
     return put
 
 
-# Bars against the oracle's own trajectory for bf16 operand arithmetic (see test_gpu_parity.py:
-# D divides by the size of the core entry, so it and the movement carry a wider bar than the core)
-BAR_D_BF16, BAR_MOVE_BF16, BAR_MOVE_OWN_BF16 = 5e-2, 5e-2, 1e-2
+# Bars against the oracle's own trajectory for bf16 operand arithmetic from a COLD start (zero
+# moments, t = 1, 2, 3, as the benchmark configurations state it).  D = mhat / (sqrt(vhat) + eps)
+# divides by the size of the core entry: an absolute core error e (about 2e-3 of the core's norm
+# spread over r^2 entries) is a relative error e / |c| in D, and most entries are projected noise
+# three orders of magnitude below the leading ones.  Measured on every configuration: 1.5e-2 to
+# 2.1e-2 at t = 2 (two draws in the moments), 1.1e-2 to 1.3e-2 at t = 3; the bar is 3e-2.  The
+# movement from the GPU's own D (the lift's arithmetic alone) measures 3e-3 and keeps 1e-2.
+BAR_D_BF16, BAR_MOVE_BF16, BAR_MOVE_OWN_BF16 = 3e-2, 3e-2, 1e-2
 
 
 def check_step_against_oracle(tsr, w, blocks, plan, sample, tol, steps=(1, 2), label=""):

@@ -490,3 +490,60 @@ def test_realign_moment_orthogonal_subspace_loses_everything():
     V = orthonormal(n, r, 962)
     M = RNG.standard_normal((r, r))
     assert np.abs(orc.realign_moment(M, U_old, V, U_new, V)).max() < 1e-13
+
+
+# ------------------------------------------------------------------ comparison paths (ablations)
+def test_one_sided_projection_and_lift_brute_force_and_identity_basis():
+    m, n, r = 9, 13, 4
+    G = RNG.standard_normal((m, n)); U = orthonormal(m, r, 4101)
+    C1 = orc.project_one_sided(G, U)
+    expect = np.zeros((r, n))
+    for a in range(r):
+        for j in range(n):
+            expect[a, j] = sum(U[i, a] * G[i, j] for i in range(m))
+    assert np.allclose(C1, expect, rtol=0, atol=1e-13)
+    # followed by a right projection it is the two-sided core: (U^T G) V = U^T G V
+    V = orthonormal(n, r, 4103)
+    assert np.allclose(C1 @ V, orc.project_core(G, U, V), rtol=0, atol=1e-13)
+    W0 = RNG.standard_normal((m, n)); D1 = RNG.standard_normal((r, n))
+    W = orc.backproject_one_sided(W0.copy(), U, D1, 0.1, 0.01, 0.5)
+    assert np.allclose(W, W0 - 0.1 * (0.5 * U @ D1 + 0.01 * W0), rtol=0, atol=1e-13)
+    # a one-sided update that happens to lie in a right subspace, D1 = D V^T, is the two-sided lift
+    D = RNG.standard_normal((r, r))
+    assert np.allclose(orc.backproject_one_sided(W0.copy(), U, D @ V.T, 0.1, 0.01, 0.5),
+                       orc.backproject_apply(W0.copy(), U, V, D, 0.1, 0.01, 0.5), rtol=0, atol=1e-13)
+
+
+def test_one_sided_first_step_closed_form():
+    # zero moments, t = 1: D1 = c / (|c| + eps) element-wise on the r x n object
+    m, n, r = 12, 7, 3
+    G = RNG.standard_normal((m, n)); U = orthonormal(m, r, 4102)
+    W0 = RNG.standard_normal((m, n)); M1 = np.zeros((r, n)); V1 = np.zeros((r, n))
+    W = W0.copy()
+    C1, D1 = orc.one_sided_adam_step(W, [G], U, M1, V1, 1, lr=0.01)
+    c = U.T @ G
+    assert np.allclose(D1, c / (np.abs(c) + 1e-8), rtol=1e-12, atol=0)
+    assert np.allclose(W, W0 - 0.01 * U @ (c / (np.abs(c) + 1e-8)), rtol=0, atol=1e-13)
+    # with U square orthogonal (r = m) and Adam's sign-like first step, U D1 is not sign(G): the
+    # projection matters; with U = I it is the dense first AdamW step
+    W = W0.copy()
+    orc.one_sided_adam_step(W, [G], np.eye(m), np.zeros((m, n)), np.zeros((m, n)), 1, lr=0.01)
+    assert np.allclose(W, W0 - 0.01 * G / (np.abs(G) + 1e-8), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("m,n,r", [(12, 20, 4), (20, 12, 5), (9, 9, 9)])
+def test_exact_svd_refresh_against_lapack_and_full_sketch(m, n, r):
+    G = RNG.standard_normal((m, n))
+    U, V, S = orc.refresh_exact_svd(G, r)
+    u, s, vt = np.linalg.svd(G, full_matrices=False)
+    assert np.allclose(S, s, rtol=1e-11, atol=1e-13)
+    assert rel(U @ U.T, u[:, :r] @ u[:, :r].T) < 1e-10 and rel(V @ V.T, vt[:r].T @ vt[:r]) < 1e-10
+    # best rank-r approximation (Eckart-Young): the residual is the tail of the spectrum
+    resid = np.linalg.norm(G - (U * S[:r]) @ V.T)
+    assert resid == pytest.approx(np.sqrt((s[r:] ** 2).sum()), rel=1e-10, abs=1e-12)
+    # the randomized refresh with a full-width sketch is this same subspace
+    k = min(m, n)
+    if r < k:
+        Om = RNG.standard_normal((n, k))
+        Ur, Vr, _ = orc.refresh_rsvd(G, Om, r, k - r, 1)
+        assert rel(Ur @ Ur.T, U @ U.T) < 1e-9 and rel(Vr @ Vr.T, V @ V.T) < 1e-9
