@@ -14,6 +14,9 @@
  *                                                                             tsr_refresh_batched
  *   refresh with N workers (averaged sketches, one GPU)                       tsr_refresh_rsvd_workers
  *   first moment re-expressed in refreshed bases (Appendix B)                 tsr_realign_moment
+ *   comparison paths of the ablations (one-sided, exact SVD)                  tsr_project_one_sided,
+ *                                                                             tsr_backproject_one_sided,
+ *                                                                             tsr_refresh_exact_svd
  *
  * Conventions
  *   - Every matrix is dense row-major.  G and W take an explicit leading dimension
@@ -185,6 +188,39 @@ int tsr_refresh_rsvd_workers(const void* G, int g_dtype, int m, int n, long long
                              int n_workers, const float* Omega, int r, int p, int q,
                              float* U, float* V, float* sigma,
                              void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------- comparison paths of the ablations
+ * The two variants the paper's ablation compares TSR with (Section 4.3; the "One-sided" row of
+ * the table of communication objects), on the same kernels, so that their cost and payload can be
+ * measured beside the two-sided path.  They are not part of Algorithm 1.
+ *
+ * One-sided projection: the synchronized object is C1 = U^T G (r x n) instead of the r x r core.
+ * It is held TRANSPOSED here, Ct = C1^T = G^T U (n x r, contiguous), which is also the layout
+ * tsr_adam_core takes for the element-wise update (count = n * r) and the lift reads:
+ *   Ct <- alpha G^T U (+ Ct if accumulate)                               tsr_project_one_sided
+ *   W  <- W - lr (scale U Dt^T + wd W), Dt (n x r) = D1^T                tsr_backproject_one_sided
+ * r <= m.  Workspace for either call: tsr_one_sided_workspace_bytes(m, n, r). */
+size_t tsr_one_sided_workspace_bytes(int m, int n, int r);
+int tsr_project_one_sided(const void* G, int g_dtype, int m, int n, long long ldg,
+                          const float* U, int r, float alpha, int accumulate, float* Ct, int precision,
+                          void* ws, size_t ws_bytes, void* stream);
+int tsr_backproject_one_sided(float* W, int m, int n, long long ldw,
+                              const float* U, const float* Dt, int r,
+                              float lr, float wd, float scale, int precision,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* Exact-SVD refresh (what Section 3.5 replaces by the randomized sketch): U (m x r), V (n x r) =
+ * the r leading singular vectors of G itself, sigma (optional) = all min(m, n) singular values,
+ * descending.  No sketch and no Omega: the thin QR of the gradient held tall, then the SVD of its
+ * triangular factor, on the kernels of tsr_refresh_rsvd's second half.  Requires
+ * min(m, n) <= 1024 (the small-SVD kernels' limit), else TSR_BAD_SHAPE.  Singular values below
+ * about 1e-3 of the largest lose relative accuracy (the Gram matrix squares the conditioning), and
+ * directions at rounding level come out as zero columns; the leading r are what the comparison
+ * needs.  Workspace: tsr_refresh_exact_workspace_bytes(m, n, r). */
+size_t tsr_refresh_exact_workspace_bytes(int m, int n, int r);
+int tsr_refresh_exact_svd(const void* G, int g_dtype, int m, int n, long long ldg, int r,
+                          float* U, float* V, float* sigma,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------- moment re-alignment (Appendix B)
  * First moment re-expressed in refreshed bases, the refresh-alignment assumption of the

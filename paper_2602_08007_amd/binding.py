@@ -19,6 +19,8 @@ __all__ = [
     "tsr_backproject_workspace_bytes", "tsr_backproject_apply",
     "tsr_refresh_workspace_bytes", "tsr_refresh_rsvd", "tsr_refresh_workers_workspace_bytes", "tsr_refresh_rsvd_workers",
     "tsr_realign_workspace_bytes", "tsr_realign_moment",
+    "tsr_one_sided_workspace_bytes", "tsr_project_one_sided", "tsr_backproject_one_sided",
+    "tsr_refresh_exact_workspace_bytes", "tsr_refresh_exact_svd",
     "tsr_matrix_desc", "tsr_hyper", "Plan", "workspace",
 ]
 
@@ -68,6 +70,11 @@ _refresh_ws = _sig("tsr_refresh_workspace_bytes", _sz, _i, _i, _i, _i)
 _refresh = _sig("tsr_refresh_rsvd", _i, _vp, _i, _i, _i, _ll, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp)
 _realign_ws = _sig("tsr_realign_workspace_bytes", _sz, _i, _i, _i)
 _realign = _sig("tsr_realign_moment", _i, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp)
+_one_sided_ws = _sig("tsr_one_sided_workspace_bytes", _sz, _i, _i, _i)
+_project_one = _sig("tsr_project_one_sided", _i, _vp, _i, _i, _i, _ll, _vp, _i, _f, _i, _vp, _i, _vp, _sz, _vp)
+_lift_one = _sig("tsr_backproject_one_sided", _i, _vp, _i, _i, _ll, _vp, _vp, _i, _f, _f, _f, _i, _vp, _sz, _vp)
+_exact_ws = _sig("tsr_refresh_exact_workspace_bytes", _sz, _i, _i, _i)
+_exact = _sig("tsr_refresh_exact_svd", _i, _vp, _i, _i, _i, _ll, _i, _vp, _vp, _vp, _vp, _sz, _vp)
 _refresh_workers_ws = _sig("tsr_refresh_workers_workspace_bytes", _sz, _i, _i, _i, _i, _i)
 _refresh_workers = _sig("tsr_refresh_rsvd_workers", _i, _vp, _i, _i, _i, _ll, _ll, _i, _vp, _i, _i, _i, _vp, _vp, _vp, _vp,
                         _sz, _vp)
@@ -141,6 +148,19 @@ def workspace(nbytes: int, device="cuda") -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def _temp_workspace(nbytes: int, device, stream) -> torch.Tensor:
+    """Workspace for a one-shot call that did not bring its own.  It is dropped when the call
+    returns, while the kernels may still be queued: that is safe on torch's current stream (the
+    caching allocator reuses the block in stream order) and is made safe on any other stream by
+    telling the allocator which stream uses the block."""
+    ws = workspace(nbytes, device)
+    if stream is not None and isinstance(stream, torch.cuda.Stream) and stream != torch.cuda.current_stream(ws.device):
+        ws.record_stream(stream)
+    elif stream is not None and not isinstance(stream, torch.cuda.Stream):
+        raise ValueError("pass a torch.cuda.Stream, or an explicit ws together with a raw stream handle")
+    return ws
+
+
 def tsr_project_workspace_bytes(m: int, n: int, r: int) -> int:
     return int(_project_ws(m, n, r))
 
@@ -150,7 +170,7 @@ def tsr_project_core(G, U, V, C, alpha=1.0, accumulate=False, precision=TSR_PREC
     r = U.shape[1]
     _f32c(U, V, C)
     if ws is None:
-        ws = workspace(tsr_project_workspace_bytes(m, n, r), G.device)
+        ws = _temp_workspace(tsr_project_workspace_bytes(m, n, r), G.device, stream)
     _check(_project(_ptr(G), _gdtype(G), m, n, _ld(G), _ptr(U), _ptr(V), r, alpha, int(bool(accumulate)), _ptr(C),
                     precision, _ptr(ws), ws.numel(), _stream(stream)))
     return C
@@ -205,7 +225,7 @@ def tsr_backproject_apply(W, U, V, D, lr, wd=0.0, scale=1.0, precision=TSR_PREC_
     if W.dtype != torch.float32:
         raise TypeError("W must be float32")
     if ws is None:
-        ws = workspace(tsr_backproject_workspace_bytes(m, n, r), W.device)
+        ws = _temp_workspace(tsr_backproject_workspace_bytes(m, n, r), W.device, stream)
     _check(_lift(_ptr(W), m, n, _ld(W), _ptr(U), _ptr(V), _ptr(D), r, lr, wd, scale, precision, _ptr(ws), ws.numel(),
                  _stream(stream)))
     return W
@@ -221,7 +241,7 @@ def tsr_refresh_rsvd(G, Omega, r, p, q, U, V, sigma=None, ws=None, stream=None):
     if tuple(Omega.shape) != (n, r + p):
         raise ValueError("Omega must be n x (r+p)")
     if ws is None:
-        ws = workspace(tsr_refresh_workspace_bytes(m, n, r, p), G.device)
+        ws = _temp_workspace(tsr_refresh_workspace_bytes(m, n, r, p), G.device, stream)
     _check(_refresh(_ptr(G), _gdtype(G), m, n, _ld(G), _ptr(Omega), r, p, q, _ptr(U), _ptr(V), _ptr(sigma), _ptr(ws),
                     ws.numel(), _stream(stream)))
     return U, V
@@ -240,7 +260,7 @@ def tsr_refresh_rsvd_workers(G, Omega, r, p, q, U, V, sigma=None, ws=None, strea
     if tuple(Omega.shape) != (n, r + p):
         raise ValueError("Omega must be n x (r+p)")
     if ws is None:
-        ws = workspace(tsr_refresh_workers_workspace_bytes(m, n, r, p, K), G.device)
+        ws = _temp_workspace(tsr_refresh_workers_workspace_bytes(m, n, r, p, K), G.device, stream)
     _check(_refresh_workers(_ptr(G), _gdtype(G), m, n, n, m * n, K, _ptr(Omega), r, p, q, _ptr(U), _ptr(V), _ptr(sigma),
                             _ptr(ws), ws.numel(), _stream(stream)))
     return U, V
@@ -257,10 +277,58 @@ def tsr_realign_moment(U_old, V_old, U_new, V_new, M, ws=None, stream=None):
     if tuple(U_new.shape) != (m, r) or tuple(V_old.shape) != (n, r) or tuple(V_new.shape) != (n, r) or tuple(M.shape) != (r, r):
         raise ValueError("shape mismatch")
     if ws is None:
-        ws = workspace(tsr_realign_workspace_bytes(m, n, r), M.device)
+        ws = _temp_workspace(tsr_realign_workspace_bytes(m, n, r), M.device, stream)
     _check(_realign(_ptr(U_old), _ptr(V_old), _ptr(U_new), _ptr(V_new), m, n, r, _ptr(M), _ptr(ws), ws.numel(),
                     _stream(stream)))
     return M
+
+
+def tsr_one_sided_workspace_bytes(m: int, n: int, r: int) -> int:
+    return int(_one_sided_ws(m, n, r))
+
+
+def tsr_project_one_sided(G, U, Ct, alpha=1.0, accumulate=False, precision=TSR_PREC_SPLIT, ws=None, stream=None):
+    """Ct (n x r) <- alpha G^T U (+ Ct): the one-sided object U^T G, held transposed."""
+    m, n = G.shape
+    r = U.shape[1]
+    _f32c(U, Ct)
+    if tuple(Ct.shape) != (n, r):
+        raise ValueError("Ct must be n x r")
+    if ws is None:
+        ws = _temp_workspace(tsr_one_sided_workspace_bytes(m, n, r), G.device, stream)
+    _check(_project_one(_ptr(G), _gdtype(G), m, n, _ld(G), _ptr(U), r, alpha, int(bool(accumulate)), _ptr(Ct), precision,
+                        _ptr(ws), ws.numel(), _stream(stream)))
+    return Ct
+
+
+def tsr_backproject_one_sided(W, U, Dt, lr, wd=0.0, scale=1.0, precision=TSR_PREC_SPLIT, ws=None, stream=None):
+    """W <- W - lr (scale U Dt^T + wd W) with the transposed one-sided update Dt (n x r)."""
+    m, n = W.shape
+    r = U.shape[1]
+    _f32c(U, Dt)
+    if W.dtype != torch.float32 or tuple(Dt.shape) != (n, r):
+        raise TypeError("W must be float32 and Dt n x r")
+    if ws is None:
+        ws = _temp_workspace(tsr_one_sided_workspace_bytes(m, n, r), W.device, stream)
+    _check(_lift_one(_ptr(W), m, n, _ld(W), _ptr(U), _ptr(Dt), r, lr, wd, scale, precision, _ptr(ws), ws.numel(),
+                     _stream(stream)))
+    return W
+
+
+def tsr_refresh_exact_workspace_bytes(m: int, n: int, r: int) -> int:
+    return int(_exact_ws(m, n, r))
+
+
+def tsr_refresh_exact_svd(G, r, U, V, sigma=None, ws=None, stream=None):
+    m, n = G.shape
+    _f32c(U, V, sigma)
+    if ws is None:
+        nbytes = tsr_refresh_exact_workspace_bytes(m, n, r)
+        if nbytes == 0:
+            raise TsrError(-2)
+        ws = _temp_workspace(nbytes, G.device, stream)
+    _check(_exact(_ptr(G), _gdtype(G), m, n, _ld(G), r, _ptr(U), _ptr(V), _ptr(sigma), _ptr(ws), ws.numel(), _stream(stream)))
+    return U, V
 
 
 class Plan:

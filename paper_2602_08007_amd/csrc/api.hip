@@ -234,73 +234,94 @@ struct RefreshBlock {
     float* U; float* V; float* sigma;
     // workspace
     float *Y, *Yalt, *Z, *Zalt, *S, *Rinv, *XrT, *GrT;
-    double *work, *R1, *Rtot, *Gacc, *eig;
+    double *work, *R1, *Rmid, *Rtot, *Gacc, *eig;
 };
 
-struct OrthProgram {        // X (rows x k) -> orthonormal basis, in place, Xalt as scratch
-    GemmStage gram1, q1, gram2, q2;
-    std::vector<CholBlock> chol1, chol2;
-    const CholBlock* d_chol1 = nullptr; const CholBlock* d_chol2 = nullptr;
+// orth(X) for X (rows x k) by Cholesky QR; the result is always left in Xalt (X is scratch).
+//   passes = 1 (normalisations inside the power iteration): one SHIFTED pass, Xalt = X R^-1 with
+//     R^T R = X^T X + s I.  Same span and the same triangular orientation as the exact factor; the
+//     shift keeps the factorization from breaking down however ill conditioned the sketch is (a
+//     steep spectrum squares into a Gram matrix whose small eigenvalues lie below its fp32-grade
+//     rounding), at the price of a basis that is only roughly orthonormal, which is all these
+//     intermediate bases are for.
+//   passes = 3 (the final Q and the factor of B^T): shifted pass A (X -> Xalt), shifted pass E
+//     (Xalt -> X), plain pass B with the Gram matrix at three bf16 pieces (X -> Xalt).  Each
+//     shifted pass brings the condition number down to about 1 / sqrt(shift) of what it was, so
+//     sketches with a condition number up to about 1e6 arrive at pass B well conditioned; pass B
+//     drops what is left at rounding level (pivot <= 1e-6 of its diagonal entry: directions beyond
+//     the numerical rank, e.g. of an exactly low-rank or zero gradient) as zero columns.
+constexpr double ORTH_SHIFT = 1e-4;       // relative to the largest diagonal entry of the Gram matrix
+constexpr double ORTH_DROP = 1e-6;
+
+struct OrthProgram {
+    GemmStage gramA, qA, gramE, qE, gramB, qB;
+    std::vector<CholBlock> cholA, cholE, cholB;
+    const CholBlock* d_cholA = nullptr; const CholBlock* d_cholE = nullptr; const CholBlock* d_cholB = nullptr;
 };
 
 struct RefreshProgram {
     std::vector<RefreshBlock> blocks;
     GemmStage sketch[2];    // Y = G Omega
-    GemmStage gtq[2];       // Z = G^T Q    (final Q, held in Y)
-    GemmStage gtq_alt[2];   // Z = G^T Q'   (Q' = once-orthonormalised sketch, held in Yalt)
-    GemmStage gq[2];        // Y = G Q'row  (once-orthonormalised row basis, held in Zalt)
+    GemmStage gtq[2];       // Z = G^T Q    (Q = orth result, held in Yalt)
+    GemmStage gq[2];        // Y = G Qrow   (Qrow = orth result, held in Zalt)
     OrthProgram orthY, orthZ;
-    std::vector<JacobiBlock> jac; const JacobiBlock* d_jac = nullptr;
+    std::vector<JacobiBlock> jac, jac_pre;
+    const JacobiBlock* d_jac = nullptr; const JacobiBlock* d_jac_pre = nullptr;
     GemmStage uout, vout;
 };
 
 void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool on_rows_m, Arena& ar) {
-    std::vector<LogicalGemm> g1, q1, g2, q2;
-    op.chol1.clear(); op.chol2.clear();
+    std::vector<LogicalGemm> gA, qA, gE, qE, gB, qB;
+    op.cholA.clear(); op.cholE.clear(); op.cholB.clear();
     for (const RefreshBlock& b : blocks) {
         const int rows = on_rows_m ? b.m : b.n;
         float* X = on_rows_m ? b.Y : b.Z;
         float* Xalt = on_rows_m ? b.Yalt : b.Zalt;
         const int k = b.k;
-        g1.push_back(LogicalGemm{X, X, k, k, k, k, rows, b.S, k});
-        q1.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
-        g2.push_back(LogicalGemm{Xalt, Xalt, k, k, k, k, rows, b.S, k});
-        q2.push_back(LogicalGemm{Xalt, b.Rinv, k, k, rows, k, k, X, k});
-        op.chol1.push_back(CholBlock{b.S, b.Rinv, b.R1, b.work, k});
-        // the second factor goes to Gacc (free until the small SVD); where the product of the two
-        // factors is needed, an fp64 MFMA GEMM forms it afterwards (run_refresh_back)
-        op.chol2.push_back(CholBlock{b.S, b.Rinv, b.Gacc, b.work, k});
+        gA.push_back(LogicalGemm{X, X, k, k, k, k, rows, b.S, k});
+        qA.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
+        gE.push_back(LogicalGemm{Xalt, Xalt, k, k, k, k, rows, b.S, k});
+        qE.push_back(LogicalGemm{Xalt, b.Rinv, k, k, rows, k, k, X, k});
+        gB.push_back(LogicalGemm{X, X, k, k, k, k, rows, b.S, k});
+        qB.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
+        // the three triangular factors (X = Q R3 R2 R1) go to R1, Rmid and Gacc (free until the small
+        // SVD); where their product is needed, fp64 MFMA GEMMs form it afterwards (run_refresh_back)
+        op.cholA.push_back(CholBlock{b.S, b.Rinv, b.R1, b.work, k});
+        op.cholE.push_back(CholBlock{b.S, b.Rinv, b.Rmid, b.work, k});
+        op.cholB.push_back(CholBlock{b.S, b.Rinv, b.Gacc, b.work, k});
     }
+    // The first pass meets the sketch at its raw scaling, where a rounding of X moves the span of
+    // the result: with an fp32 gradient X keeps three bf16 pieces there, as in the products with G.
+    int pieces_x = 2;
+    for (const RefreshBlock& b : blocks) if (b.g_dtype == TSR_F32) pieces_x = 3;
     // the Cholesky kernels read the lower triangle of the Gram matrix only
-    build_stage(op.gram1, variant(1, 1, 0, 2, 2), g1, ar, 512, true);
-    build_stage(op.q1, variant(0, 1, 0, 2, 2), q1, ar, 1);
-    build_stage(op.gram2, variant(1, 1, 0, 3, 3), g2, ar, 512, true);
-    build_stage(op.q2, variant(0, 1, 0, 3, 3), q2, ar, 1);
+    build_stage(op.gramA, variant(1, 1, 0, 2, 2), gA, ar, 512, true);
+    build_stage(op.qA, variant(0, 1, 0, pieces_x, pieces_x), qA, ar, 1);
+    build_stage(op.gramE, variant(1, 1, 0, 2, 2), gE, ar, 512, true);
+    build_stage(op.qE, variant(0, 1, 0, 2, 2), qE, ar, 1);
+    build_stage(op.gramB, variant(1, 1, 0, 3, 3), gB, ar, 512, true);
+    build_stage(op.qB, variant(0, 1, 0, 3, 3), qB, ar, 1);
 }
 
-// passes = 2: CholeskyQR2, X (and Xalt) -> orthonormal basis in X.  passes = 1: one Cholesky
-// pass, X -> X R^-1 in Xalt: a basis of the same span with the same triangular orientation,
-// orthonormal to about the conditioning of X squared times the fp32-grade accuracy of the Gram
-// matrix.  That is all the normalisations inside the power iteration are for (they keep the
-// columns from collapsing onto the leading directions); what the refresh returns goes through
-// the two-pass form.
-int run_orth(const OrthProgram& op, bool grouped, Ctx& cx, int passes = 2) {
-    const int nb = (int)op.chol1.size();
+int run_orth(const OrthProgram& op, bool grouped, Ctx& cx, int passes) {
+    const int nb = (int)op.cholA.size();
     int max_k = 0;
-    for (const CholBlock& cb : op.chol1) max_k = std::max(max_k, cb.k);
-    TSR_TRY(run_stage(op.gram1, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
-    {
+    for (const CholBlock& cb : op.cholA) max_k = std::max(max_k, cb.k);
+    auto chol = [&](const CholBlock* dev, const std::vector<CholBlock>& host, double tol, double shift) -> int {
         Timed timed(cx, TSR_PROF_CHOL);
-        TSR_HIP(launch_chol_inv(grouped ? op.d_chol1 : nullptr, grouped ? nullptr : &op.chol1[0], nb, max_k, 1e-6, cx.s));
-    }
-    TSR_TRY(run_stage(op.q1, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+        TSR_HIP(launch_chol_inv(grouped ? dev : nullptr, grouped ? nullptr : &host[0], nb, max_k, tol, shift, cx.s));
+        return TSR_OK;
+    };
+    TSR_TRY(run_stage(op.gramA, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    TSR_TRY(chol(op.d_cholA, op.cholA, ORTH_DROP, ORTH_SHIFT));
+    TSR_TRY(run_stage(op.qA, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     if (passes == 1) return TSR_OK;
-    TSR_TRY(run_stage(op.gram2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
-    {
-        Timed timed(cx, TSR_PROF_CHOL);
-        TSR_HIP(launch_chol_inv(grouped ? op.d_chol2 : nullptr, grouped ? nullptr : &op.chol2[0], nb, max_k, 1e-6, cx.s));
-    }
-    return run_stage(op.q2, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM);
+    TSR_TRY(run_stage(op.gramE, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    TSR_TRY(chol(op.d_cholE, op.cholE, ORTH_DROP, ORTH_SHIFT));
+    TSR_TRY(run_stage(op.qE, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    TSR_TRY(run_stage(op.gramB, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+    TSR_TRY(chol(op.d_cholB, op.cholB, ORTH_DROP, 0.0));
+    return run_stage(op.qB, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM);
 }
 
 void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena& ar);
@@ -320,7 +341,7 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         b.Z = ar.take<float>((size_t)b.n * k); b.Zalt = ar.take<float>((size_t)b.n * k);
         b.S = ar.take<float>(k * k); b.Rinv = ar.take<float>(k * k);
         b.XrT = ar.take<float>((size_t)b.r * k); b.GrT = ar.take<float>((size_t)b.r * k);
-        b.work = ar.take<double>(2 * k * k + 64); b.R1 = ar.take<double>(k * k);
+        b.work = ar.take<double>(2 * k * k + 64); b.R1 = ar.take<double>(k * k); b.Rmid = ar.take<double>(k * k);
         b.Rtot = ar.take<double>(k * k); b.Gacc = ar.take<double>(k * k);
         b.eig = (b.k <= EIG_MAXK) ? ar.take<double>(3 * k * k + 3 * k + 8) : nullptr;
         rp.blocks.push_back(b);
@@ -330,24 +351,28 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
 
 // Stages and tables of the refresh of rp.blocks (whose buffers are already carved).
 void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena& ar) {
-    std::vector<LogicalGemm> sk[2], gtq[2], gtqa[2], gq[2], uo, vo;
-    rp.jac.clear();
+    std::vector<LogicalGemm> sk[2], gtq[2], gq[2], uo, vo;
+    rp.jac.clear(); rp.jac_pre.clear();
     for (size_t i = 0; i < rp.blocks.size(); ++i) {
         const RefreshBlock& b = rp.blocks[i];
         const float* om = omegas ? omegas[i] : nullptr;
         sk[b.g_dtype].push_back(LogicalGemm{b.G, om, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
-        gtq[b.g_dtype].push_back(LogicalGemm{b.G, b.Y, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
-        gtqa[b.g_dtype].push_back(LogicalGemm{b.G, b.Yalt, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
+        gtq[b.g_dtype].push_back(LogicalGemm{b.G, b.Yalt, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
         gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Zalt, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
-        uo.push_back(LogicalGemm{b.Y, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
-        vo.push_back(LogicalGemm{b.Z, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
-        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r, b.eig, b.R1});
+        uo.push_back(LogicalGemm{b.Yalt, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
+        vo.push_back(LogicalGemm{b.Zalt, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
+        // R = R3 (R2 R1): first R2 R1 into the (by then idle) Cholesky work area, then the small SVD's
+        // table with that product in the place of R1
+        rp.jac_pre.push_back(JacobiBlock{b.work, b.Rmid, nullptr, nullptr, nullptr, nullptr, b.k, b.r, nullptr, b.R1});
+        rp.jac.push_back(JacobiBlock{b.Rtot, b.Gacc, b.work, b.XrT, b.GrT, b.sigma, b.k, b.r, b.eig, b.work});
     }
     for (int d = 0; d < 2; ++d) {
-        build_stage(rp.sketch[d], variant(0, 1, d, 2, 2), sk[d], ar);
-        build_stage(rp.gtq[d], variant(1, 1, d, 2, 2), gtq[d], ar);
-        build_stage(rp.gtq_alt[d], variant(1, 1, d, 2, 2), gtqa[d], ar);
-        build_stage(rp.gq[d], variant(0, 1, d, 2, 2), gq[d], ar);
+        // an fp32 gradient keeps three bf16 pieces per operand (rounding at 2^-27, below its own
+        // 2^-24); a bf16 gradient is exact in one piece and meets the sketch at two pieces
+        const int pc = (d == TSR_F32) ? 3 : 2;
+        build_stage(rp.sketch[d], variant(0, 1, d, pc, pc), sk[d], ar);
+        build_stage(rp.gtq[d], variant(1, 1, d, pc, pc), gtq[d], ar);
+        build_stage(rp.gq[d], variant(0, 1, d, pc, pc), gq[d], ar);
     }
     build_orth(rp.orthY, rp.blocks, true, ar);
     build_orth(rp.orthZ, rp.blocks, false, ar);
@@ -355,36 +380,38 @@ void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena&
     build_stage(rp.vout, variant(0, 0, 0, 3, 3), vo, ar, 1);
 }
 
-// Sketch chain of one worker: leaves the final Q in Y and B^T = G^T Q in Z.  Inside the power
-// iteration the bases are normalised by one Cholesky pass (run_orth, passes = 1), the final Q by
-// CholeskyQR2: right-multiplying a sketch by an upper-triangular factor changes neither its span
-// nor the Q factor of anything computed from it.
+// Sketch chain of one worker: leaves the final Q in Yalt and B^T = G^T Q in Z.  Inside the power
+// iteration the bases are normalised by one shifted Cholesky pass (run_orth, passes = 1), the final
+// Q by three: right-multiplying a sketch by an upper-triangular factor changes neither its span nor
+// the Q factor of anything computed from it.
 int run_refresh_front(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.sketch[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     for (int it = 0; it < q; ++it) {
         TSR_TRY(run_orth(rp.orthY, grouped, cx, 1));                                    // Q' in Yalt
-        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq_alt[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
+        for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
         TSR_TRY(run_orth(rp.orthZ, grouped, cx, 1));                                    // Q'row in Zalt
         for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     }
-    TSR_TRY(run_orth(rp.orthY, grouped, cx));
+    TSR_TRY(run_orth(rp.orthY, grouped, cx, 3));                                        // Q in Yalt
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     return TSR_OK;
 }
 
-// From Q (in Y) and B^T (in Z):  B^T = Q_B R ; SVD of R ; U = Q X_r ; V = Q_B Gacc_r^T
+// From Q (in Yalt) and B^T (in Z):  B^T = Q_B R (Q_B in Zalt) ; SVD of R ; U = Q X_r ; V = Q_B Gacc_r^T
 int run_refresh_back(const RefreshProgram& rp, bool grouped, Ctx& cx) {
-    TSR_TRY(run_orth(rp.orthZ, grouped, cx));
+    TSR_TRY(run_orth(rp.orthZ, grouped, cx, 3));
     {
         Timed timed(cx, TSR_PROF_JACOBI);
         int max_k = 0;
         for (const JacobiBlock& jb : rp.jac) max_k = std::max(max_k, jb.k);
-        TSR_HIP(launch_rtot_product(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
+        const int nb = (int)rp.jac.size();
+        TSR_HIP(launch_rtot_product(grouped ? rp.d_jac_pre : nullptr, grouped ? nullptr : &rp.jac_pre[0], nb, max_k, cx.s));
+        TSR_HIP(launch_rtot_product(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], nb, max_k, cx.s));
         static const bool chain = [] { const char* e = getenv("TSR_TUNE_EIG_CHAIN"); return !(e && e[0] == '0'); }();
         if (chain && max_k <= EIG_MAXK)
-            TSR_HIP(launch_eig_svd(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
+            TSR_HIP(launch_eig_svd(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], nb, max_k, cx.s));
         else
-            TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], (int)rp.jac.size(), max_k, cx.s));
+            TSR_HIP(launch_jacobi(grouped ? rp.d_jac : nullptr, grouped ? nullptr : &rp.jac[0], nb, max_k, cx.s));
     }
     TSR_TRY(run_stage(rp.uout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM));
     return run_stage(rp.vout, grouped, 1.0f, 0.0f, cx, TSR_PROF_BASIS_GEMM);
@@ -407,15 +434,16 @@ int check_refresh_shape(int m, int n, int r, int p) {
 
 void upload_refresh(RefreshProgram& rp, Arena& ar, Uploader& up) {
     for (int d = 0; d < 2; ++d) {
-        upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gtq_alt[d], ar, up);
-        upload_stage(rp.gq[d], ar, up);
+        upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gq[d], ar, up);
     }
     for (OrthProgram* op : {&rp.orthY, &rp.orthZ}) {
-        upload_stage(op->gram1, ar, up); upload_stage(op->q1, ar, up);
-        upload_stage(op->gram2, ar, up); upload_stage(op->q2, ar, up);
-        op->d_chol1 = up.put(op->chol1, ar); op->d_chol2 = up.put(op->chol2, ar);
+        upload_stage(op->gramA, ar, up); upload_stage(op->qA, ar, up);
+        upload_stage(op->gramE, ar, up); upload_stage(op->qE, ar, up);
+        upload_stage(op->gramB, ar, up); upload_stage(op->qB, ar, up);
+        op->d_cholA = up.put(op->cholA, ar); op->d_cholE = up.put(op->cholE, ar); op->d_cholB = up.put(op->cholB, ar);
     }
     rp.d_jac = up.put(rp.jac, ar);
+    rp.d_jac_pre = up.put(rp.jac_pre, ar);
     upload_stage(rp.uout, ar, up); upload_stage(rp.vout, ar, up);
 }
 
@@ -720,12 +748,124 @@ int tsr_refresh_rsvd_workers(const void* G, int g_dtype, int m, int n, long long
         build_refresh(rp, v, oms, p, sigs, sub);
         TSR_TRY(run_refresh_front(rp, false, q, cx));
         const RefreshBlock& b = rp.blocks[0];
-        TSR_HIP(hipMemcpyAsync(Qs + (size_t)w * m * k, b.Y, (size_t)m * k * sizeof(float), hipMemcpyDeviceToDevice, cx.s));
+        TSR_HIP(hipMemcpyAsync(Qs + (size_t)w * m * k, b.Yalt, (size_t)m * k * sizeof(float), hipMemcpyDeviceToDevice, cx.s));
         TSR_HIP(hipMemcpyAsync(Bs + (size_t)w * n * k, b.Z, (size_t)n * k * sizeof(float), hipMemcpyDeviceToDevice, cx.s));
     }
     const RefreshBlock& b = rp.blocks[0];
-    TSR_HIP(launch_average(Qs, n_workers, (long long)m * (long long)k, b.Y, cx.s));      // Qbar
+    TSR_HIP(launch_average(Qs, n_workers, (long long)m * (long long)k, b.Yalt, cx.s));   // Qbar
     TSR_HIP(launch_average(Bs, n_workers, (long long)n * (long long)k, b.Z, cx.s));      // Bbar^T
+    return run_refresh_back(rp, false, cx);
+}
+
+// ---------------------------------------------------------------- comparison paths of the ablations
+// One-sided projection and lift on the grouped GEMM family, exact-SVD refresh on the back end of
+// the randomized one (no sketch: the orthonormal basis of the short side is the identity).
+}  // extern "C"
+
+namespace {
+struct OneSidedProgram { GemmStage proj[2], lift; };
+
+// Ct (n x r) = alpha G^T U (+ Ct): the r x n one-sided object, stored transposed
+void build_one_sided_project(OneSidedProgram& op, const void* G, int g_dtype, int m, int n, long long ldg, const float* U,
+                             int r, float* Ct, int prec, Arena& ar) {
+    std::vector<LogicalGemm> g{LogicalGemm{G, U, ldg, r, n, r, m, Ct, r}};
+    const int pv = (prec == TSR_PREC_BF16) ? 1 : 2;
+    build_stage(op.proj[g_dtype], variant(1, 1, g_dtype, pv, pv), g, ar);
+}
+
+// W = beta W + alpha U Dt^T with Dt (n x r) the transposed one-sided update
+void build_one_sided_lift(OneSidedProgram& op, float* W, int m, int n, long long ldw, const float* U, const float* Dt,
+                          int r, int prec, Arena& ar) {
+    std::vector<LogicalGemm> g{LogicalGemm{U, Dt, r, r, m, n, r, W, ldw}};
+    const int pv = (prec == TSR_PREC_BF16) ? 1 : 2;
+    build_stage(op.lift, variant(0, 0, 0, pv, pv), g, ar, /*want_tiles=*/1);
+}
+}  // namespace
+
+extern "C" {
+
+size_t tsr_one_sided_workspace_bytes(int m, int n, int r) {
+    if (m <= 0 || n <= 0 || r <= 0 || r > m) return 0;
+    Arena ar(nullptr);
+    OneSidedProgram op;
+    build_one_sided_project(op, nullptr, TSR_F32, m, n, n, nullptr, r, nullptr, TSR_PREC_SPLIT, ar);
+    build_one_sided_lift(op, nullptr, m, n, n, nullptr, nullptr, r, TSR_PREC_SPLIT, ar);
+    return ar.used();
+}
+
+int tsr_project_one_sided(const void* G, int g_dtype, int m, int n, long long ldg, const float* U, int r, float alpha,
+                          int accumulate, float* Ct, int precision, void* ws, size_t ws_bytes, void* stream) {
+    if (m <= 0 || n <= 0 || r <= 0 || r > m) return TSR_BAD_SHAPE;
+    TSR_TRY(check_dtype(g_dtype));
+    TSR_TRY(check_prec(precision));
+    if (!G || !U || !Ct || !ws) return TSR_INVALID_ARG;
+    if (ldg < n) return TSR_BAD_SHAPE;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_one_sided_workspace_bytes(m, n, r)) return TSR_WORKSPACE_TOO_SMALL;
+    Arena ar(ws);
+    OneSidedProgram op;
+    build_one_sided_project(op, G, g_dtype, m, n, ldg, U, r, Ct, precision, ar);
+    Ctx cx{(hipStream_t)stream, nullptr};
+    return run_stage(op.proj[g_dtype], false, alpha, accumulate ? 1.0f : 0.0f, cx, TSR_PROF_GV);
+}
+
+int tsr_backproject_one_sided(float* W, int m, int n, long long ldw, const float* U, const float* Dt, int r, float lr,
+                              float wd, float scale, int precision, void* ws, size_t ws_bytes, void* stream) {
+    if (m <= 0 || n <= 0 || r <= 0 || r > m) return TSR_BAD_SHAPE;
+    TSR_TRY(check_prec(precision));
+    if (!W || !U || !Dt || !ws) return TSR_INVALID_ARG;
+    if (ldw < n) return TSR_BAD_SHAPE;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_one_sided_workspace_bytes(m, n, r)) return TSR_WORKSPACE_TOO_SMALL;
+    Arena ar(ws);
+    OneSidedProgram op;
+    build_one_sided_lift(op, W, m, n, ldw, U, Dt, r, precision, ar);
+    Ctx cx{(hipStream_t)stream, nullptr};
+    return run_stage(op.lift, false, -lr * scale, 1.0f - lr * wd, cx, TSR_PROF_TVT);
+}
+
+// Exact SVD through the refresh back end: with s = min(m, n) the short side's basis is the s x s
+// identity and the "reduced matrix" is the gradient itself, held as a tall (long side x s) fp32
+// matrix T (G^T if m <= n, else G); then T = Q_T R, SVD of R, short-side vectors = X_r and
+// long-side vectors = Q_T Gacc_r^T.  The short side plays the role of U's side in the block.
+static int exact_svd_view(std::vector<BlockView>& v, int m, int n, int r, float* U, float* V) {
+    const bool wide = (m <= n);            // short side = rows
+    one_block_view(v, nullptr, TSR_F32, wide ? m : n, wide ? n : m, r, wide ? n : m, nullptr, 1, wide ? U : V, wide ? V : U,
+                   nullptr, nullptr);
+    return wide ? 1 : 0;
+}
+
+size_t tsr_refresh_exact_workspace_bytes(int m, int n, int r) {
+    const int s = std::min(m, n);
+    if (check_refresh_shape(m, n, r, s - r) != TSR_OK) return 0;
+    std::vector<BlockView> v;
+    exact_svd_view(v, m, n, r, nullptr, nullptr);
+    Arena ar(nullptr);
+    RefreshProgram rp;
+    build_refresh(rp, v, nullptr, s - r, nullptr, ar);
+    return ar.used();
+}
+
+int tsr_refresh_exact_svd(const void* G, int g_dtype, int m, int n, long long ldg, int r, float* U, float* V,
+                          float* sigma, void* ws, size_t ws_bytes, void* stream) {
+    TSR_TRY(check_block(m, n, r));
+    const int s = std::min(m, n);
+    TSR_TRY(check_refresh_shape(m, n, r, s - r));       // min(m, n) <= 1024: the small-SVD kernels' limit
+    TSR_TRY(check_dtype(g_dtype));
+    if (!G || !U || !V || !ws) return TSR_INVALID_ARG;
+    if (ldg < n) return TSR_BAD_SHAPE;
+    if (!aligned256(ws)) return TSR_INVALID_ARG;
+    if (ws_bytes < tsr_refresh_exact_workspace_bytes(m, n, r)) return TSR_WORKSPACE_TOO_SMALL;
+    std::vector<BlockView> v;
+    const int transpose = exact_svd_view(v, m, n, r, U, V);
+    Arena ar(ws);
+    RefreshProgram rp;
+    float* sigs[1] = {sigma};
+    build_refresh(rp, v, nullptr, s - r, sigs, ar);
+    const RefreshBlock& b = rp.blocks[0];
+    Ctx cx{(hipStream_t)stream, nullptr};
+    TSR_HIP(launch_identity(b.Yalt, s, cx.s));                                          // Q = I (s x s)
+    TSR_HIP(launch_tall_copy(G, g_dtype == TSR_BF16, ldg, m, n, transpose, b.Z, cx.s)); // B^T, tall
     return run_refresh_back(rp, false, cx);
 }
 

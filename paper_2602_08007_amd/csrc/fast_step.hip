@@ -114,8 +114,13 @@ void persistent_lists(std::vector<NtTile>& tiles, std::vector<NtRange>& ranges, 
     tiles.swap(out);
 }
 
+// group_m: order of a problem's output tiles within one k split.  0: row of tiles after row of
+// tiles.  g > 0: bands of g tile rows, and inside a band column after column (the g tiles of a
+// column are neighbours).  The workgroups resident on an XCD at one time then cover a compact patch
+// of the output: they share g row panels of A, which stay in that XCD's L2 for the whole band, and
+// each column panel of B is fetched once per band instead of once per tile row.
 void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogical>& gemms, int n_blocks, Arena& ar,
-                    int want_tiles, bool persistent = false) {
+                    int want_tiles, bool persistent = false, int group_m = 0) {
     st = NtStageH{};
     st.var = var;
     if (gemms.empty()) return;
@@ -171,13 +176,16 @@ void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogi
                 prefix += ksplit[j];
             }
             const int tmn = cdiv(g.M, TM), tnn = cdiv(g.N, TN);
+            const int band = (group_m > 0) ? group_m : 1;
             for (int ks = 0; ks < ksplit[j]; ++ks)
-                for (int tm = 0; tm < tmn; ++tm)
-                    for (int tn = 0; tn < tnn; ++tn) {
-                        st.tiles.push_back(NtTile{(int)j, tm, tn, ks});
-                        tile_block.push_back(g.block);
-                        tile_work.push_back(std::min(p.kchunk, g.K) + 64);
-                    }
+                for (int tb = 0; tb < tmn; tb += band)
+                    for (int t2 = 0; t2 < (group_m > 0 ? tnn : 1); ++t2)
+                        for (int tm = tb; tm < std::min(tmn, tb + band); ++tm)
+                            for (int t3 = 0; t3 < (group_m > 0 ? 1 : tnn); ++t3) {
+                                st.tiles.push_back(NtTile{(int)j, tm, (group_m > 0) ? t2 : t3, ks});
+                                tile_block.push_back(g.block);
+                                tile_work.push_back(std::min(p.kchunk, g.K) + 64);
+                            }
         }
         i = e;
     }
@@ -360,14 +368,17 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
     // persistent launches pay off for the many short tiles of U^T P, not for the G V stage
     const bool gv_persist = tune_int("TSR_TUNE_GV_PERSIST", 0, 0, 1) != 0;
     const bool utp_persist = tune_int("TSR_TUNE_UTP_PERSIST", 1, 0, 1) != 0;
-    build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1, gv_persist);
-    build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1, gv_persist);
+    // P^T = V^T G^T has r / 128 tile rows over every panel of G: all of them side by side, so that the
+    // panel comes from memory once; W = beta W + T V^T in bands of eight tile rows
+    const int gv_band = tune_int("TSR_TUNE_GV_BAND", 8, 0, 64), tvt_band = tune_int("TSR_TUNE_TVT_BAND", 8, 0, 64);
+    build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1, gv_persist, gv_band);
+    build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1, gv_persist, gv_band);
     // cores up to 256 x 256 are cut into 64 x 64 tiles (enough of them to fill the chip without
     // splitting k); larger cores have enough 128 x 128 tiles
     build_nt_stage(fs.utp, NtVariant{tune("TSR_TUNE_UTP", r_max >= 512 ? NT_128x128 : NT_64x64), 0, 0}, utp, nb, ar,
                    tune_int("TSR_TUNE_UTP_TILES", 2048, 1, 65536), utp_persist);
     build_nt_stage(fs.ud, NtVariant{tune("TSR_TUNE_UD", NT_128x128), 0, 1}, ud, nb, ar, 1);
-    build_nt_stage(fs.tvt, NtVariant{tune("TSR_TUNE_TVT", NT_128x128), 0, 0}, tvt, nb, ar, 1);
+    build_nt_stage(fs.tvt, NtVariant{tune("TSR_TUNE_TVT", NT_128x128), 0, 0}, tvt, nb, ar, 1, false, tvt_band);
 }
 
 void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {

@@ -29,6 +29,12 @@ hipError_t launch_adam_t(const AdamTBlock* table_dev, int blocks, int max_r, con
 hipError_t launch_sgd(const float* C, float* M, float* D, long long count, float beta, hipStream_t stream);
 hipError_t launch_average(const float* Cs, int K, long long count, float* out, hipStream_t stream);
 
+// ---- helpers of the exact-SVD refresh: a k x k fp32 identity; the gradient (rows x cols, fp32 or
+// bf16, leading dimension ldg) as a contiguous fp32 matrix, transposed (cols x rows) or not
+hipError_t launch_identity(float* out, int k, hipStream_t stream);
+hipError_t launch_tall_copy(const void* G, int g_bf16, long long ldg, int rows, int cols, int transpose, float* out,
+                            hipStream_t stream);
+
 // ---- plain streaming kernel dst[i] = scale * src[i] (dst may equal src): the measured HBM
 // rate of the machine and the calibration of the memory-traffic counters
 hipError_t launch_stream(float* dst, const float* src, long long count, float scale, hipStream_t stream);
@@ -38,7 +44,11 @@ hipError_t launch_stream(float* dst, const float* src, long long count, float sc
 //   Rinv (fp32, k x k upper) = R^-1, so that Y Rinv has orthonormal columns,
 //   Rtot (fp64, k x k upper, optional) = R.
 // Only the lower triangle of S is read.  A pivot at or below tol * S[j][j] marks column j as
-// dependent: row/column j of Rinv and row j of Rtot become zero.  work = 2 k x k doubles per matrix.
+// dependent: row/column j of Rinv and row j of Rtot become zero.  shift_rel > 0 factors
+// S + shift_rel * max_j S[j][j] * I instead (shifted Cholesky QR: the factor exists whatever the
+// rounding of S, no column is dropped, and Y Rinv has a condition number reduced to about
+// 1 / sqrt(shift_rel); a following unshifted pass finishes the orthonormalisation).
+// work = 2 k x k doubles per matrix.
 struct CholBlock {
     const float* S; float* Rinv;
     double* Rtot;
@@ -46,7 +56,7 @@ struct CholBlock {
     int k;
 };
 hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, int blocks, int max_k,
-                           double tol, hipStream_t stream);
+                           double tol, double shift_rel, hipStream_t stream);
 
 // ---- SVD of the k x k upper-triangular factor R (fp64): an orthogonal Gacc with
 // Gacc R = diag(sigma) X^T (rows mutually orthogonal), from the symmetric eigenproblem of R R^T.

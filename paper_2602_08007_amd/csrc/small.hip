@@ -119,6 +119,60 @@ hipError_t launch_average(const float* Cs, int K, long long count, float* out, h
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ helpers of the exact-SVD refresh
+// out (k x k fp32) = identity
+__global__ __launch_bounds__(256) void identity_kernel(float* out, int k) {
+    const long long n = (long long)k * k;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+        out[i] = (i / k == i % k) ? 1.0f : 0.0f;
+}
+
+hipError_t launch_identity(float* out, int k, hipStream_t stream) {
+    if (k <= 0) return hipSuccess;
+    long long bx = ((long long)k * k + 255) / 256;
+    if (bx > 4096) bx = 4096;
+    hipLaunchKernelGGL(identity_kernel, dim3((unsigned)bx), dim3(256), 0, stream, out, k);
+    return hipGetLastError();
+}
+
+// The gradient as a tall contiguous fp32 matrix: out = G (rows x cols -> rows x cols) or, with
+// transpose, out = G^T (cols x rows), through a 32 x 33 LDS tile so that both sides are coalesced.
+template <bool BF16>
+__global__ __launch_bounds__(256) void tall_copy_kernel(const void* G, long long ldg, int rows, int cols, int transpose,
+                                                        float* out) {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    for (int i = ty; i < 32; i += 8) {
+        const int r = r0 + i, c = c0 + tx;
+        float v = 0.0f;
+        if (r < rows && c < cols) {
+            if constexpr (BF16) v = __uint_as_float(((unsigned)((const unsigned short*)G)[(long long)r * ldg + c]) << 16);
+            else v = ((const float*)G)[(long long)r * ldg + c];
+        }
+        tile[i][tx] = v;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        if (transpose) {
+            const int c = c0 + i, r = r0 + tx;             // out[c][r]
+            if (c < cols && r < rows) out[(long long)c * rows + r] = tile[tx][i];
+        } else {
+            const int r = r0 + i, c = c0 + tx;
+            if (r < rows && c < cols) out[(long long)r * cols + c] = tile[i][tx];
+        }
+    }
+}
+
+hipError_t launch_tall_copy(const void* G, int g_bf16, long long ldg, int rows, int cols, int transpose, float* out,
+                            hipStream_t stream) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    dim3 grid((cols + 31) / 32, (rows + 31) / 32);
+    if (g_bf16) hipLaunchKernelGGL(tall_copy_kernel<true>, grid, dim3(256), 0, stream, G, ldg, rows, cols, transpose, out);
+    else hipLaunchKernelGGL(tall_copy_kernel<false>, grid, dim3(256), 0, stream, G, ldg, rows, cols, transpose, out);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ stream calibration
 typedef __attribute__((ext_vector_type(4))) float f32x4_s;
 __global__ __launch_bounds__(256) void stream_kernel(f32x4_s* dst, const f32x4_s* src, long long n4, float scale) {
@@ -143,8 +197,27 @@ hipError_t launch_stream(float* dst, const float* src, long long count, float sc
 constexpr int SMALL_THREADS = 1024;
 constexpr int SMALL_MAXK = 1024;
 
+// shift_rel * (largest diagonal entry of the k x k fp32 matrix S), computed by the whole workgroup
+__device__ inline double diagonal_shift(const float* S, int k, double shift_rel) {
+    __shared__ double s_wave_max[SMALL_THREADS / 64];
+    __shared__ double s_shift;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    double mx = 0.0;
+    for (int j = tid; j < k; j += nt) mx = fmax(mx, (double)S[(size_t)j * k + j]);
+    for (int off = 32; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off));
+    if ((tid & 63) == 0) s_wave_max[tid >> 6] = mx;
+    __syncthreads();
+    if (tid == 0) {
+        double m = 0.0;
+        for (int w = 0; w < (nt >> 6); ++w) m = fmax(m, s_wave_max[w]);
+        s_shift = shift_rel * m;
+    }
+    __syncthreads();
+    return s_shift;
+}
+
 __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_kernel(const CholBlock* table, const CholBlock single,
-                                                                 const double tol) {
+                                                                 const double tol, const double shift_rel) {
     const CholBlock* blk = table ? table + blockIdx.x : &single;
     const int k = blk->k;
     const float* S = blk->S;
@@ -155,7 +228,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_kernel(const CholBlock
     __shared__ double colj[SMALL_MAXK];
     __shared__ double s_invd;
 
-    for (int idx = tid; idx < k * k; idx += nt) A[idx] = (double)S[idx];
+    const double shift = diagonal_shift(S, k, shift_rel);
+    for (int idx = tid; idx < k * k; idx += nt) A[idx] = (double)S[idx] + ((idx / k == idx % k) ? shift : 0.0);
     __syncthreads();
 
     for (int j = 0; j < k; ++j) {
@@ -237,7 +311,7 @@ constexpr int CHB_P = CHB + 1;
 constexpr int CHB_MAXK = 544;
 
 __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const CholBlock* table, const CholBlock single,
-                                                                         const double tol) {
+                                                                         const double tol, const double shift_rel) {
     const CholBlock* blk = table ? table + blockIdx.x : &single;
     const int k = blk->k;
     const float* S = blk->S;
@@ -253,7 +327,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void chol_inv_blocked_kernel(const C
     extern __shared__ double Pn[];             // [block rows * CHB][CHB_P]
 
     // (X is written where it is read: diagonal blocks whole, the blocks below them in the inverse phase)
-    for (int idx = tid; idx < k * k; idx += SMALL_THREADS) A[idx] = (double)S[idx];
+    const double shift = diagonal_shift(S, k, shift_rel);
+    for (int idx = tid; idx < k * k; idx += SMALL_THREADS) A[idx] = (double)S[idx] + ((idx / k == idx % k) ? shift : 0.0);
     __syncthreads();
 
     for (int J = 0; J < k; J += CHB) {
@@ -527,7 +602,7 @@ __global__ __launch_bounds__(256) void chol_output_kernel(const CholBlock* table
 }
 
 hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, int blocks, int max_k, double tol,
-                           hipStream_t stream) {
+                           double shift_rel, hipStream_t stream) {
     if (blocks <= 0) return hipSuccess;
     CholBlock sb{};
     if (single) sb = *single;
@@ -542,7 +617,7 @@ hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, 
             if (e != hipSuccess) return e;
             configured = true;
         }
-        hipLaunchKernelGGL(chol_inv_blocked_kernel, dim3(blocks), dim3(SMALL_THREADS), lds, stream, table_dev, sb, tol);
+        hipLaunchKernelGGL(chol_inv_blocked_kernel, dim3(blocks), dim3(SMALL_THREADS), lds, stream, table_dev, sb, tol, shift_rel);
         static thread_local bool configured2 = false;
         if (!configured2) {
             hipError_t e = hipFuncSetAttribute((const void*)chol_inverse_kernel,
@@ -554,7 +629,7 @@ hipError_t launch_chol_inv(const CholBlock* table_dev, const CholBlock* single, 
         const int tiles = (max_k + CHB - 1) / CHB;
         hipLaunchKernelGGL(chol_output_kernel, dim3(blocks * tiles * tiles), dim3(256), 0, stream, table_dev, sb, blocks, tiles);
     } else {
-        hipLaunchKernelGGL(chol_inv_kernel, dim3(blocks), dim3(SMALL_THREADS), 0, stream, table_dev, sb, tol);
+        hipLaunchKernelGGL(chol_inv_kernel, dim3(blocks), dim3(SMALL_THREADS), 0, stream, table_dev, sb, tol, shift_rel);
     }
     return hipGetLastError();
 }

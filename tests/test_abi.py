@@ -84,6 +84,15 @@ def test_argument_validation_happens_on_the_host(tsr):
     assert r(fake, 0, 64, 32, 32, fake, 30, 4, 1, fake, fake, null, ws, 1 << 30, null) == -2
     assert r(fake, 0, 64, 32, 32, fake, 16, 4, -1, fake, fake, null, ws, 1 << 30, null) == -1
     assert r(fake, 0, 64, 32, 32, fake, 16, 4, 1, fake, fake, null, ws, 64, null) == -4
+    # comparison paths: one-sided needs r <= m only; exact SVD needs min(m, n) <= 1024
+    o = lib.tsr_project_one_sided
+    assert o(fake, 0, 8, 64, 64, fake, 9, 1.0, 0, fake, 0, ws, 1 << 30, null) == -2
+    assert o(fake, 0, 4096, 8, 8, fake, 32, 1.0, 0, fake, 0, ws, 16, null) == -4      # k-split partials do not fit
+    assert tsr.tsr_one_sided_workspace_bytes(4096, 8, 32) > 16 and tsr.tsr_one_sided_workspace_bytes(8, 64, 9) == 0
+    x = lib.tsr_refresh_exact_svd
+    assert x(fake, 0, 2048, 2048, 2048, 64, fake, fake, null, ws, 1 << 30, null) == -2
+    assert x(fake, 0, 64, 32, 32, 16, fake, fake, null, ws, 64, null) == -4
+    assert tsr.tsr_refresh_exact_workspace_bytes(2048, 2048, 64) == 0 and tsr.tsr_refresh_exact_workspace_bytes(512, 1376, 64) > 0
     # plan
     assert lib.tsr_plan_workspace_bytes(None, 0, 1, 0, 0, 0) == 0
     assert lib.tsr_step_batched(None, 1, None, null) == -1

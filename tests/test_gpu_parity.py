@@ -231,6 +231,40 @@ def test_refresh_repeated_singular_values(tsr, m, n):
     assert rel_fro(sigma[:r], so[:r]) < TOL_F32
 
 
+@pytest.mark.parametrize("g_dtype", [torch.float32, torch.bfloat16])
+def test_refresh_steep_full_rank_spectrum(tsr, g_dtype):
+    # full-rank gradient with a steep spectrum, sigma_i = 1 / i^2, noise 1e-7: sigma_r / sigma_1 =
+    # 6e-4 lies INSIDE the retained rank, and the sketch's Gram matrix has a condition number of
+    # about 1e9, far beyond what an unshifted Cholesky QR survives.  The bases must come out
+    # orthonormal with no direction dropped; singular values and captured energy are well posed
+    # (Weyl); the top-r projector is limited by the gap sigma_r - sigma_{r+1} = 3e-5 sigma_1 (its bar
+    # scales with the oracle's gap, as for configuration 1), the leading directions are not.
+    m, n, r, p, q = 300, 260, 40, 8, 1
+    s_min = min(m, n)
+    A = si.orthonormal(m, s_min, si.stream_key(541, 1)); B = si.orthonormal(n, s_min, si.stream_key(541, 2))
+    sv = 1.0 / torch.arange(1, s_min + 1, dtype=torch.float64) ** 2
+    G = ((A * sv[None, :]) @ B.T + 1e-7 * si.normal((m, n), si.stream_key(541, 3), dtype=torch.float64)).float().to(g_dtype)
+    Om = si.omega(n, r + p, si.stream_key(541, 4))
+    U_ref, V_ref, S_ref = orc.refresh_rsvd(G, Om, r, p, q)
+    U, V, sigma = run_refresh(tsr, G, Om, r, p, q)
+    check_orthonormal(U); check_orthonormal(V)
+    assert float(orc.f64(U).std(axis=0).min()) > 0 and float(np.linalg.norm(orc.f64(U), axis=0).min()) > 0.999    # no zero column
+    assert float(np.linalg.norm(orc.f64(V), axis=0).min()) > 0.999
+    es = float(np.abs(orc.f64(sigma) - S_ref).max() / S_ref[0])
+    gap = (S_ref[r - 1] - S_ref[r]) / S_ref[0]
+    eu, ev = projector_err(U, U_ref), projector_err(V, V_ref)
+    eu8, ev8 = projector_err(U[:, :8], U_ref[:, :8]), projector_err(V[:, :8], V_ref[:, :8])
+    e_ref = np.linalg.norm(U_ref.T @ orc.f64(G) @ V_ref)
+    e_gpu = np.linalg.norm(orc.f64(U).T @ orc.f64(G) @ orc.f64(V))
+    parity_log("steep spectrum 1/i^2 %dx%d r=%d %s: relative gap %.2e sigma err / sigma_1 %.2e projector errors U %.2e V %.2e "
+               "leading-8 U %.2e V %.2e captured energy diff %.2e"
+               % (m, n, r, str(g_dtype)[6:], gap, es, eu, ev, eu8, ev8, abs(e_gpu - e_ref) / e_ref))
+    assert es < 1e-5
+    assert abs(e_gpu - e_ref) / e_ref < 1e-5
+    assert eu8 < 1e-3 and ev8 < 1e-3
+    assert eu < max(TOL_F32, 2e-7 / gap) and ev < max(TOL_F32, 2e-7 / gap)
+
+
 def test_refresh_zero_gradient_is_finite(tsr):
     # degenerate input: nothing to find.  Every sketch column is dropped as dependent, the
     # singular values are zero and the bases come out as zeros: finite, no NaN from 0 / 0
@@ -313,6 +347,80 @@ def test_refresh_workers_matches_oracle(tsr, workers, g_dtype, q):
     assert np.abs(Ug.T @ Ug - Ur.T @ Ur).max() < 5e-4          # columns oriented alike first
     if workers > 1:
         assert np.linalg.norm(U_ref.T @ U_ref - np.eye(r)) > 1e-4       # the defect is real and reproduced above
+
+
+# ------------------------------------------------------------------ comparison paths of the ablations
+@pytest.mark.parametrize("m,n,r,dtype,prec", [(200, 333, 17, torch.float32, "split"), (333, 200, 40, torch.float32, "split"),
+                                              (768, 2048, 256, torch.bfloat16, "bf16"), (512, 1376, 64, torch.bfloat16, "split")])
+def test_one_sided_project_adam_lift(tsr, m, n, r, dtype, prec):
+    # the one-sided variant (object U^T G, r x n) on the same kernels: two steps from a warm start,
+    # the oracle on its own trajectory; the GPU holds the object transposed (n x r)
+    key = si.stream_key(871, m, n, r)
+    sig = si.make_signal(m, n, min(r, 16), "1/i", key)
+    U = si.orthonormal(m, r, si.stream_key(key, 1)).float()
+    W0 = si.weights(m, n, si.stream_key(key, 4))
+    precision = tsr.TSR_PREC_SPLIT if prec == "split" else tsr.TSR_PREC_BF16
+    tol = TOL_F32 if prec == "split" else TOL_BF16
+    lr, wd = f32(1e-3), f32(0.01)
+    W = orc.f64(W0).copy(); M1 = np.zeros((r, n)); V1 = np.zeros((r, n))
+    U64 = orc.f64(U)
+    grads = [si.gradient(sig, 1e-3, si.stream_key(key, 10 + t), dtype=dtype) for t in range(1, 6)]
+    for t in (1, 2, 3):                                       # warm start: the oracle alone
+        orc.one_sided_adam_step(W, [grads[t - 1]], U64, M1, V1, t, lr=lr, wd=wd, beta1=B1, beta2=B2, eps=EPS)
+    Wd = dev(torch.from_numpy(W).float()); W = orc.f64(Wd).copy()
+    Md = dev(torch.from_numpy(M1.T.copy()).float()); Vd = dev(torch.from_numpy(V1.T.copy()).float())   # n x r on the GPU
+    M1[...] = orc.f64(Md).T; V1[...] = orc.f64(Vd).T
+    Ud = dev(U)
+    Ct = torch.full((n, r), float("nan"), device="cuda"); Dt = torch.empty(n, r, device="cuda")
+    for t in (4, 5):
+        G = grads[t - 1]
+        Wg0, Wo0 = orc.f64(Wd).copy(), W.copy()
+        C1, D1 = orc.one_sided_adam_step(W, [G], U64, M1, V1, t, lr=lr, wd=wd, beta1=B1, beta2=B2, eps=EPS)
+        tsr.tsr_project_one_sided(dev(G), Ud, Ct, precision=precision)
+        tsr.tsr_adam_core(Ct, Md, Vd, Dt, t)
+        tsr.tsr_backproject_one_sided(Wd, Ud, Dt, 1e-3, 0.01, precision=precision)
+        torch.cuda.synchronize()
+        ec, _ = check_close(Ct, C1.T, tol, "one-sided object t=%d" % t)
+        check_close(Md, M1.T, tol, "first moment"); check_close(Vd, V1.T, 2 * tol, "second moment")
+        ew, _ = check_close(Wd, W, tol, "weights t=%d" % t)
+        Wk = orc.backproject_one_sided(Wg0.copy(), U64, orc.f64(Dt).T, lr, wd)
+        check_close(Wd, Wk, tol, "weights from the GPU's own D")
+        emo, _ = check_close(orc.f64(Wd) - Wg0, Wk - Wg0, BAR_MOVE_OWN[prec], "movement from the GPU's own D")
+        ed, em = rel_fro(Dt, D1.T), rel_fro(orc.f64(Wd) - Wg0, W - Wo0)
+        parity_log("one-sided %dx%d r=%d %s t=%d: C=%.2e W=%.2e move_own=%.2e D=%.2e move=%.2e" % (m, n, r, prec, t, ec, ew, emo, ed, em))
+        assert ed < BAR_D[prec] and em < BAR_MOVE[prec], (t, ed, em)
+    # accumulate / alpha as in the two-sided call
+    ref = orc.project_one_sided(grads[4], U64).T
+    tsr.tsr_project_one_sided(dev(grads[4]), Ud, Ct, alpha=0.5, accumulate=True, precision=precision)
+    check_close(Ct, 1.5 * ref, tol, "accumulated one-sided object")
+
+
+@pytest.mark.parametrize("m,n,r,dtype", [(96, 160, 8, torch.float32), (160, 96, 8, torch.float32), (130, 131, 24, torch.bfloat16),
+                                         (512, 1376, 64, torch.float32)])
+def test_refresh_exact_svd_matches_oracle(tsr, m, n, r, dtype):
+    # well separated leading singular values (2 .. 1), then the noise floor
+    G64, A, B = si.exact_lowrank(m, n, r, si.stream_key(881, m, n))
+    G = (G64 + 1e-3 * si.normal((m, n), si.stream_key(882, m), dtype=torch.float64)).float().to(dtype)
+    U = torch.empty(m, r, device="cuda"); V = torch.empty(n, r, device="cuda"); sigma = torch.empty(min(m, n), device="cuda")
+    tsr.tsr_refresh_exact_svd(dev(G), r, U, V, sigma)
+    torch.cuda.synchronize()
+    check_orthonormal(U); check_orthonormal(V)
+    U_ref, V_ref, S_ref = orc.refresh_exact_svd(G, r)
+    eu, ev, es = projector_err(U, U_ref), projector_err(V, V_ref), rel_fro(sigma[:r], S_ref[:r])
+    parity_log("exact-SVD refresh %dx%d r=%d %s: projector errors U %.2e V %.2e sigma_r %.2e" % (m, n, r, str(dtype)[6:], eu, ev, es))
+    assert eu < TOL_F32 and ev < TOL_F32 and es < TOL_F32
+    # LAPACK agrees on what is unique (the leading values; the subspace through the projector)
+    u, s, vt = np.linalg.svd(orc.f64(G), full_matrices=False)
+    assert rel_fro(sigma[:r], s[:r]) < TOL_F32 and projector_err(U, u[:, :r]) < TOL_F32
+    # the whole spectrum: absolute accuracy relative to the largest value
+    assert np.abs(orc.f64(sigma) - S_ref).max() < 1e-4 * S_ref[0]
+    # the randomized refresh finds the same subspace (the comparison the ablation makes)
+    p, q = 8, 1
+    if r + p <= min(m, n):
+        Om = si.omega(n, r + p, si.stream_key(883, n))
+        Ur = torch.empty(m, r, device="cuda"); Vr = torch.empty(n, r, device="cuda")
+        tsr.tsr_refresh_rsvd(dev(G), dev(Om), r, p, q, Ur, Vr)
+        assert projector_err(Ur, U) < 1e-3 and projector_err(Vr, V) < 1e-3
 
 
 # ------------------------------------------------------------------ moment re-alignment
@@ -562,7 +670,7 @@ def test_step_batched_cold_start(tsr, prec):
     plan.close()
 
 
-@pytest.mark.parametrize("r", [64, 128, 256, 512])
+@pytest.mark.parametrize("r", [64, 128, 256, 512])       # 512: beyond the fused lift kernel, on the NT GEMM pair
 @pytest.mark.parametrize("workers", [1, 2])
 @pytest.mark.parametrize("rows16", [True, False, "padded"])
 def test_bf16_plan_fused_lift_ranks(tsr, r, workers, rows16):
