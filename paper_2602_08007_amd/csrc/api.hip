@@ -235,6 +235,11 @@ struct RefreshBlock {
     // workspace
     float *Y, *Yalt, *Z, *Zalt, *S, *Rinv, *XrT, *GrT;
     double *work, *R1, *Rmid, *Rtot, *Gacc, *eig;
+    // bf16 gradients of a plan: the products with G on the k-contiguous bf16 family (see NtRefresh)
+    bool nt = false;
+    unsigned short *Gt = nullptr, *Pn = nullptr, *Pm = nullptr;   // G^T (n x ldm); pieces of a k x n / k x m operand
+    unsigned short *Xp = nullptr, *Rt = nullptr;                  // pieces of a sketch (rows x ldk) and of R^-T (k x ldk)
+    long long ldm = 0, ldn = 0, ldk = 0;
 };
 
 // orth(X) for X (rows x k) by Cholesky QR; the result is always left in Xalt (X is scratch).
@@ -253,14 +258,46 @@ struct RefreshBlock {
 constexpr double ORTH_SHIFT = 1e-4;       // relative to the largest diagonal entry of the Gram matrix
 constexpr double ORTH_DROP = 1e-6;
 
+// A shifted pass (A or E) of the blocks with RefreshBlock::nt on the bf16 NT family.  The sketch X
+// enters as two bf16 pieces in both orientations (transposed for the Gram matrix, as stored for the
+// product with R^-1), R^-1 as two pieces of its transpose; every product keeps the three leading
+// cross terms: X^T X = Xh^T Xh + Xl^T Xh + Xh^T Xl (summed by the k-split reduction, lower tiles
+// only), X R^-1 = Xh (Rh + Rl) (one launch, two pieces of B) + Xl Rh (accumulated by a second).
+struct OrthNtPass {
+    std::vector<SplitBlock> st, sx, sr;       // X -> pieces of X^T; X -> pieces of X; R^-1 -> pieces of R^-T
+    const SplitBlock* d_st = nullptr; const SplitBlock* d_sx = nullptr; const SplitBlock* d_sr = nullptr;
+    NtStageH gram, ap1, ap2;
+    int max_rows = 0, max_k = 0;
+    bool empty() const { return st.empty(); }
+};
+
 struct OrthProgram {
+    OrthNtPass ntA, ntE;
     GemmStage gramA, qA, gramE, qE, gramB, qB;
     std::vector<CholBlock> cholA, cholE, cholB;
     const CholBlock* d_cholA = nullptr; const CholBlock* d_cholE = nullptr; const CholBlock* d_cholB = nullptr;
 };
 
+// The products with a bf16 gradient (Y = G Omega, Z = G^T Q, Y = G Qrow: Algorithm 1's sketch,
+// power-iteration and B lines) in the operand form of the bf16 NT family, C = A B^T with both
+// operands k-contiguous: A is the gradient itself, or a transposed copy made once per refresh; B is
+// the transpose of the small fp32 operand cut into two bf16 pieces (written by a split kernel before
+// each product), which the kernel multiplies with the same staged A tile.  The gradient is exact in
+// bf16, so the product is accurate to the two pieces of the small operand (2^-18 per element), as on
+// the general kernel.  One stage serves both products with G (their B pieces share a buffer).
+constexpr int NT_REFRESH_PIECES = 2;
+struct NtRefresh {
+    std::vector<TransposeBlock> gt;   const TransposeBlock* d_gt = nullptr;
+    std::vector<SplitBlock> s_om, s_q, s_qrow;
+    const SplitBlock* d_om = nullptr; const SplitBlock* d_q = nullptr; const SplitBlock* d_qrow = nullptr;
+    NtStageH g_stage, gt_stage;       // (m x k) = G (pieces over n)^T ; (n x k) = G^T (pieces over m)^T
+    int max_m = 0, max_n = 0, max_k = 0;
+    bool empty() const { return gt.empty(); }
+};
+
 struct RefreshProgram {
     std::vector<RefreshBlock> blocks;
+    NtRefresh nt;           // blocks with RefreshBlock::nt; the GemmStages below hold the others
     GemmStage sketch[2];    // Y = G Omega
     GemmStage gtq[2];       // Z = G^T Q    (Q = orth result, held in Yalt)
     GemmStage gq[2];        // Y = G Qrow   (Qrow = orth result, held in Zalt)
@@ -270,18 +307,56 @@ struct RefreshProgram {
     GemmStage uout, vout;
 };
 
+void build_orth_nt(OrthNtPass& pass, const std::vector<RefreshBlock>& blocks, bool on_rows_m, bool from_alt, Arena& ar) {
+    pass = OrthNtPass{};
+    std::vector<NtLogical> g, a1, a2;
+    for (size_t i = 0; i < blocks.size(); ++i) {
+        const RefreshBlock& b = blocks[i];
+        if (!b.nt) continue;
+        const int rows = on_rows_m ? b.m : b.n, k = b.k;
+        float* X = on_rows_m ? b.Y : b.Z;
+        float* Xalt = on_rows_m ? b.Yalt : b.Zalt;
+        const float* in = from_alt ? Xalt : X;
+        float* out = from_alt ? X : Xalt;
+        unsigned short* Xt = on_rows_m ? b.Pm : b.Pn;            // pieces of X^T (k x ldrows)
+        const long long ldrows = on_rows_m ? b.ldm : b.ldn, st_t = (long long)k * ldrows;
+        const long long st_x = (long long)rows * b.ldk, st_r = (long long)k * b.ldk;
+        pass.st.push_back(SplitBlock{in, Xt, ldrows, st_t, rows, k});
+        pass.sx.push_back(SplitBlock{in, b.Xp, b.ldk, st_x, rows, k});
+        pass.sr.push_back(SplitBlock{b.Rinv, b.Rt, b.ldk, st_r, k, k});
+        const int bi = (int)i;
+        g.push_back(NtLogical{Xt, Xt, b.S, ldrows, ldrows, k, k, k, rows, bi, bi});
+        g.push_back(NtLogical{Xt + st_t, Xt, b.S, ldrows, ldrows, k, k, k, rows, bi, bi});
+        g.push_back(NtLogical{Xt, Xt + st_t, b.S, ldrows, ldrows, k, k, k, rows, bi, bi});
+        a1.push_back(NtLogical{b.Xp, b.Rt, out, b.ldk, b.ldk, k, rows, k, k, bi, -1, st_r});
+        a2.push_back(NtLogical{b.Xp + st_x, b.Rt, out, b.ldk, b.ldk, k, rows, k, k, bi, -1});
+        pass.max_rows = std::max(pass.max_rows, rows); pass.max_k = std::max(pass.max_k, k);
+    }
+    if (g.empty()) return;
+    const int nb = (int)blocks.size();
+    build_nt_stage(pass.gram, NtVariant{NT_128x128, 0, 0}, g, nb, ar, 512, false, 0, /*lower_only=*/true);
+    NtVariant v2{};
+    v2.shape = NT_128x128_K32; v2.b_pieces = 2;
+    build_nt_stage(pass.ap1, v2, a1, nb, ar, 1);
+    build_nt_stage(pass.ap2, NtVariant{NT_128x128, 0, 0}, a2, nb, ar, 1);
+}
+
 void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool on_rows_m, Arena& ar) {
     std::vector<LogicalGemm> gA, qA, gE, qE, gB, qB;
     op.cholA.clear(); op.cholE.clear(); op.cholB.clear();
+    const char* e = getenv("TSR_TUNE_ORTH_NT");            // 0: the shifted passes of every block on the general kernel
+    const bool orth_nt = !(e && e[0] == '0');
     for (const RefreshBlock& b : blocks) {
         const int rows = on_rows_m ? b.m : b.n;
         float* X = on_rows_m ? b.Y : b.Z;
         float* Xalt = on_rows_m ? b.Yalt : b.Zalt;
         const int k = b.k;
-        gA.push_back(LogicalGemm{X, X, k, k, k, k, rows, b.S, k});
-        qA.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
-        gE.push_back(LogicalGemm{Xalt, Xalt, k, k, k, k, rows, b.S, k});
-        qE.push_back(LogicalGemm{Xalt, b.Rinv, k, k, rows, k, k, X, k});
+        if (!(b.nt && orth_nt)) {
+            gA.push_back(LogicalGemm{X, X, k, k, k, k, rows, b.S, k});
+            qA.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
+            gE.push_back(LogicalGemm{Xalt, Xalt, k, k, k, k, rows, b.S, k});
+            qE.push_back(LogicalGemm{Xalt, b.Rinv, k, k, rows, k, k, X, k});
+        }
         gB.push_back(LogicalGemm{X, X, k, k, k, k, rows, b.S, k});
         qB.push_back(LogicalGemm{X, b.Rinv, k, k, rows, k, k, Xalt, k});
         // the three triangular factors (X = Q R3 R2 R1) go to R1, Rmid and Gacc (free until the small
@@ -289,6 +364,12 @@ void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool o
         op.cholA.push_back(CholBlock{b.S, b.Rinv, b.R1, b.work, k});
         op.cholE.push_back(CholBlock{b.S, b.Rinv, b.Rmid, b.work, k});
         op.cholB.push_back(CholBlock{b.S, b.Rinv, b.Gacc, b.work, k});
+    }
+    if (orth_nt) {
+        build_orth_nt(op.ntA, blocks, on_rows_m, false, ar);
+        build_orth_nt(op.ntE, blocks, on_rows_m, true, ar);
+    } else {
+        op.ntA = OrthNtPass{}; op.ntE = OrthNtPass{};
     }
     // The first pass meets the sketch at its raw scaling, where a rounding of X moves the span of
     // the result: with an fp32 gradient X keeps three bf16 pieces there, as in the products with G.
@@ -312,12 +393,36 @@ int run_orth(const OrthProgram& op, bool grouped, Ctx& cx, int passes) {
         TSR_HIP(launch_chol_inv(grouped ? dev : nullptr, grouped ? nullptr : &host[0], nb, max_k, tol, shift, cx.s));
         return TSR_OK;
     };
+    // a shifted pass: Gram matrices (NT family for the blocks it takes, general kernel for the rest),
+    // Cholesky of all of them, then the products with R^-1
+    auto nt_gram = [&](const OrthNtPass& p) -> int {
+        if (p.empty()) return TSR_OK;
+        {
+            Timed timed(cx, TSR_PROF_ORTH_GEMM);
+            TSR_HIP(launch_split_transpose(p.d_st, (int)p.st.size(), p.max_rows, p.max_k, 2, cx.s));
+        }
+        return run_nt_stage(p.gram, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM);
+    };
+    auto nt_apply = [&](const OrthNtPass& p) -> int {
+        if (p.empty()) return TSR_OK;
+        {
+            Timed timed(cx, TSR_PROF_ORTH_GEMM);
+            TSR_HIP(launch_split_rows(p.d_sx, (int)p.sx.size(), p.max_rows, p.max_k, 2, cx.s));
+            TSR_HIP(launch_split_transpose(p.d_sr, (int)p.sr.size(), p.max_k, p.max_k, 2, cx.s));
+        }
+        TSR_TRY(run_nt_stage(p.ap1, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
+        return run_nt_stage(p.ap2, 1.0f, 1.0f, cx, TSR_PROF_ORTH_GEMM);
+    };
+    TSR_TRY(nt_gram(op.ntA));
     TSR_TRY(run_stage(op.gramA, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     TSR_TRY(chol(op.d_cholA, op.cholA, ORTH_DROP, ORTH_SHIFT));
+    TSR_TRY(nt_apply(op.ntA));
     TSR_TRY(run_stage(op.qA, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     if (passes == 1) return TSR_OK;
+    TSR_TRY(nt_gram(op.ntE));
     TSR_TRY(run_stage(op.gramE, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     TSR_TRY(chol(op.d_cholE, op.cholE, ORTH_DROP, ORTH_SHIFT));
+    TSR_TRY(nt_apply(op.ntE));
     TSR_TRY(run_stage(op.qE, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     TSR_TRY(run_stage(op.gramB, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
     TSR_TRY(chol(op.d_cholB, op.cholB, ORTH_DROP, 0.0));
@@ -326,10 +431,24 @@ int run_orth(const OrthProgram& op, bool grouped, Ctx& cx, int passes) {
 
 void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena& ar);
 
+// A bf16 gradient the NT family can read: 16-byte aligned base and rows, a row pitch that covers the
+// width rounded up to 8 elements, every operand addressable with 31-bit byte offsets.
+bool nt_refresh_eligible(const BlockView& v, int k) {
+    const char* e = getenv("TSR_TUNE_REFRESH_NT");         // read when a plan is built
+    if ((e && e[0] == '0') || v.g_dtype != TSR_BF16) return false;
+    if (((uintptr_t)v.G) % 16 != 0 || (v.ldg * 2) % 16 != 0 || v.ldg < (v.n + 7) / 8 * 8) return false;
+    const long long lim = 1LL << 31, big = std::max(v.m, v.n);
+    if ((long long)(v.m + 256) * v.ldg * 2 >= lim) return false;                 // G
+    if ((long long)(v.n + 256) * ((v.m + 7) / 8 * 8) * 2 >= lim) return false;   // G^T
+    if ((long long)NT_REFRESH_PIECES * (k + 256) * ((big + 7) / 8 * 8) * 2 >= lim) return false;   // pieces
+    if ((big + 256) * (long long)k * 4 >= lim) return false;                     // fp32 outputs
+    return true;
+}
+
 // Carves every refresh buffer from `ar` and builds all stages.  Omega pointers may be null
 // at build time (they are patched in before the launch).
 void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, const float* const* omegas, int p,
-                   float* const* sigmas, Arena& ar) {
+                   float* const* sigmas, Arena& ar, bool allow_nt = false) {
     rp.blocks.clear();
     for (size_t i = 0; i < views.size(); ++i) {
         const BlockView& v = views[i];
@@ -344,6 +463,16 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
         b.work = ar.take<double>(2 * k * k + 64); b.R1 = ar.take<double>(k * k); b.Rmid = ar.take<double>(k * k);
         b.Rtot = ar.take<double>(k * k); b.Gacc = ar.take<double>(k * k);
         b.eig = (b.k <= EIG_MAXK) ? ar.take<double>(3 * k * k + 3 * k + 8) : nullptr;
+        if (allow_nt && nt_refresh_eligible(v, b.k)) {
+            b.nt = true;
+            b.ldm = (b.m + 7) / 8 * 8; b.ldn = (b.n + 7) / 8 * 8;
+            b.Gt = ar.take<unsigned short>((size_t)b.n * b.ldm);
+            b.Pn = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * k * b.ldn);
+            b.Pm = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * k * b.ldm);
+            b.ldk = (b.k + 7) / 8 * 8;
+            b.Xp = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * std::max(b.m, b.n) * b.ldk);
+            b.Rt = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * k * b.ldk);
+        }
         rp.blocks.push_back(b);
     }
     build_refresh_stages(rp, omegas, ar);
@@ -352,13 +481,27 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
 // Stages and tables of the refresh of rp.blocks (whose buffers are already carved).
 void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena& ar) {
     std::vector<LogicalGemm> sk[2], gtq[2], gq[2], uo, vo;
+    std::vector<NtLogical> ntg, ntgt;
+    rp.nt = NtRefresh{};
     rp.jac.clear(); rp.jac_pre.clear();
     for (size_t i = 0; i < rp.blocks.size(); ++i) {
         const RefreshBlock& b = rp.blocks[i];
         const float* om = omegas ? omegas[i] : nullptr;
-        sk[b.g_dtype].push_back(LogicalGemm{b.G, om, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
-        gtq[b.g_dtype].push_back(LogicalGemm{b.G, b.Yalt, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
-        gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Zalt, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
+        if (b.nt) {
+            NtRefresh& f = rp.nt;
+            const long long sn = (long long)b.k * b.ldn, sm = (long long)b.k * b.ldm;
+            f.gt.push_back(TransposeBlock{b.G, b.Gt, b.ldg, b.ldm, b.m, b.n});
+            f.s_om.push_back(SplitBlock{om, b.Pn, b.ldn, sn, b.n, b.k});
+            f.s_qrow.push_back(SplitBlock{b.Zalt, b.Pn, b.ldn, sn, b.n, b.k});
+            f.s_q.push_back(SplitBlock{b.Yalt, b.Pm, b.ldm, sm, b.m, b.k});
+            ntg.push_back(NtLogical{b.G, b.Pn, b.Y, b.ldg, b.ldn, b.k, b.m, b.k, b.n, (int)i, -1, sn});
+            ntgt.push_back(NtLogical{b.Gt, b.Pm, b.Z, b.ldm, b.ldm, b.k, b.n, b.k, b.m, (int)i, -1, sm});
+            f.max_m = std::max(f.max_m, b.m); f.max_n = std::max(f.max_n, b.n); f.max_k = std::max(f.max_k, b.k);
+        } else {
+            sk[b.g_dtype].push_back(LogicalGemm{b.G, om, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
+            gtq[b.g_dtype].push_back(LogicalGemm{b.G, b.Yalt, b.ldg, b.k, b.n, b.k, b.m, b.Z, b.k});
+            gq[b.g_dtype].push_back(LogicalGemm{b.G, b.Zalt, b.ldg, b.k, b.m, b.k, b.n, b.Y, b.k});
+        }
         uo.push_back(LogicalGemm{b.Yalt, b.XrT, b.k, b.k, b.m, b.r, b.k, b.U, b.r});
         vo.push_back(LogicalGemm{b.Zalt, b.GrT, b.k, b.k, b.n, b.r, b.k, b.V, b.r});
         // R = R3 (R2 R1): first R2 R1 into the (by then idle) Cholesky work area, then the small SVD's
@@ -374,6 +517,14 @@ void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena&
         build_stage(rp.gtq[d], variant(1, 1, d, pc, pc), gtq[d], ar);
         build_stage(rp.gq[d], variant(0, 1, d, pc, pc), gq[d], ar);
     }
+    {
+        // 128 x 128 tiles, two workgroups per compute unit; TSR_TUNE_REFRESH_WIDE=1: the wide-tile kernel
+        const char* e = getenv("TSR_TUNE_REFRESH_WIDE");
+        NtVariant var{};
+        var.shape = (e && e[0] == '1') ? (int)NT_256x128_K32 : (int)NT_128x128_K32; var.b_pieces = NT_REFRESH_PIECES;
+        build_nt_stage(rp.nt.g_stage, var, ntg, (int)rp.blocks.size(), ar, 512);
+        build_nt_stage(rp.nt.gt_stage, var, ntgt, (int)rp.blocks.size(), ar, 512);
+    }
     build_orth(rp.orthY, rp.blocks, true, ar);
     build_orth(rp.orthZ, rp.blocks, false, ar);
     build_stage(rp.uout, variant(0, 0, 0, 3, 3), uo, ar, 1);
@@ -385,14 +536,33 @@ void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena&
 // Q by three: right-multiplying a sketch by an upper-triangular factor changes neither its span nor
 // the Q factor of anything computed from it.
 int run_refresh_front(const RefreshProgram& rp, bool grouped, int q, Ctx& cx) {
+    const NtRefresh& f = rp.nt;
+    const bool nt = !f.empty();           // only in programs with device tables (grouped)
+    // a product with G or G^T on the NT family: the small operand cut into pieces, then the GEMM
+    auto nt_product = [&](const SplitBlock* split, const NtStageH& stage, int rows) -> int {
+        if (!nt) return TSR_OK;
+        {
+            Timed timed(cx, TSR_PROF_SKETCH_GEMM);
+            TSR_HIP(launch_split_transpose(split, (int)f.gt.size(), rows, f.max_k, NT_REFRESH_PIECES, cx.s));
+        }
+        return run_nt_stage(stage, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM);
+    };
+    if (nt) {
+        Timed timed(cx, TSR_PROF_SKETCH_GEMM);
+        TSR_HIP(launch_transpose_bf16(f.d_gt, (int)f.gt.size(), f.max_m, f.max_n, cx.s));
+    }
+    TSR_TRY(nt_product(f.d_om, f.g_stage, f.max_n));
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.sketch[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     for (int it = 0; it < q; ++it) {
         TSR_TRY(run_orth(rp.orthY, grouped, cx, 1));                                    // Q' in Yalt
+        TSR_TRY(nt_product(f.d_q, f.gt_stage, f.max_m));
         for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
         TSR_TRY(run_orth(rp.orthZ, grouped, cx, 1));                                    // Q'row in Zalt
+        TSR_TRY(nt_product(f.d_qrow, f.g_stage, f.max_n));
         for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     }
     TSR_TRY(run_orth(rp.orthY, grouped, cx, 3));                                        // Q in Yalt
+    TSR_TRY(nt_product(f.d_q, f.gt_stage, f.max_m));
     for (int d = 0; d < 2; ++d) TSR_TRY(run_stage(rp.gtq[d], grouped, 1.0f, 0.0f, cx, TSR_PROF_SKETCH_GEMM));
     return TSR_OK;
 }
@@ -437,6 +607,11 @@ void upload_refresh(RefreshProgram& rp, Arena& ar, Uploader& up) {
         upload_stage(rp.sketch[d], ar, up); upload_stage(rp.gtq[d], ar, up); upload_stage(rp.gq[d], ar, up);
     }
     for (OrthProgram* op : {&rp.orthY, &rp.orthZ}) {
+        for (OrthNtPass* p : {&op->ntA, &op->ntE}) {
+            if (p->empty()) continue;
+            p->d_st = up.put(p->st, ar); p->d_sx = up.put(p->sx, ar); p->d_sr = up.put(p->sr, ar);
+            upload_nt_stage(p->gram, ar, up); upload_nt_stage(p->ap1, ar, up); upload_nt_stage(p->ap2, ar, up);
+        }
         upload_stage(op->gramA, ar, up); upload_stage(op->qA, ar, up);
         upload_stage(op->gramE, ar, up); upload_stage(op->qE, ar, up);
         upload_stage(op->gramB, ar, up); upload_stage(op->qB, ar, up);
@@ -444,6 +619,13 @@ void upload_refresh(RefreshProgram& rp, Arena& ar, Uploader& up) {
     }
     rp.d_jac = up.put(rp.jac, ar);
     rp.d_jac_pre = up.put(rp.jac_pre, ar);
+    if (!rp.nt.empty()) {
+        NtRefresh& f = rp.nt;
+        f.d_gt = up.put(f.gt, ar);
+        f.d_om = up.put(f.s_om, ar); f.d_q = up.put(f.s_q, ar); f.d_qrow = up.put(f.s_qrow, ar);
+        upload_nt_stage(f.g_stage, ar, up);
+        upload_nt_stage(f.gt_stage, ar, up);
+    }
     upload_stage(rp.uout, ar, up); upload_stage(rp.vout, ar, up);
 }
 
@@ -961,7 +1143,7 @@ static void build_plan(tsr_plan& pl, Arena& ar) {
     }
     pl.groups.clear(); pl.group_blocks.clear();
     if (pl.with_refresh) {
-        build_refresh(pl.refresh, pl.blocks, nullptr, pl.p, nullptr, ar);
+        build_refresh(pl.refresh, pl.blocks, nullptr, pl.p, nullptr, ar, /*allow_nt=*/!pl.force_generic);
         const int ng = refresh_group_count((int)pl.blocks.size());
         if (ng > 1) {
             // heaviest blocks first onto the lightest group
@@ -1090,10 +1272,11 @@ int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream) {
 // Points the sketch stage of `rp` at this call's Omegas (om[i] belongs to rp.blocks[i]) and
 // refreshes the device copy of those tables on `st`.
 static int patch_omegas(RefreshProgram& rp, const std::vector<const float*>& om, hipStream_t st) {
-    size_t cursor[2] = {0, 0};
+    size_t cursor[2] = {0, 0}, nt_cursor = 0;
     for (size_t i = 0; i < rp.blocks.size(); ++i) {
         const int d = rp.blocks[i].g_dtype;
-        rp.sketch[d].probs[cursor[d]++].B = om[i];
+        if (rp.blocks[i].nt) rp.nt.s_om[nt_cursor++].X = om[i];
+        else rp.sketch[d].probs[cursor[d]++].B = om[i];
     }
     for (int d = 0; d < 2; ++d) {
         GemmStage& sgm = rp.sketch[d];
@@ -1101,6 +1284,9 @@ static int patch_omegas(RefreshProgram& rp, const std::vector<const float*>& om,
         TSR_HIP(hipMemcpyAsync((void*)sgm.d_probs, sgm.probs.data(), sgm.probs.size() * sizeof(GemmProblem),
                                hipMemcpyHostToDevice, st));
     }
+    if (!rp.nt.empty())
+        TSR_HIP(hipMemcpyAsync((void*)rp.nt.d_om, rp.nt.s_om.data(), rp.nt.s_om.size() * sizeof(SplitBlock),
+                               hipMemcpyHostToDevice, st));
     return TSR_OK;
 }
 
@@ -1131,14 +1317,20 @@ int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void*
     }
     // fork: the side streams start after everything queued on the caller's stream so far
     TSR_HIP(hipEventRecord(plan->fork, st));
+    // From here on an error does not return early: whatever was queued on a side stream is still
+    // joined to the caller's stream, so that the caller's later work never overtakes it.
     int rc = TSR_OK;
+    auto note = [&](hipError_t e) { if (e != hipSuccess && rc == TSR_OK) rc = hip_fail(e); };
+    std::vector<char> forked(plan->groups.size(), 0);
     for (size_t g = 1; g < plan->groups.size(); ++g) {
         hipStream_t sg = plan->side[g - 1];
-        TSR_HIP(hipStreamWaitEvent(sg, plan->fork, 0));
+        const hipError_t e = hipStreamWaitEvent(sg, plan->fork, 0);
+        note(e);
+        if (e != hipSuccess) continue;                       // nothing queued on this side stream
+        forked[g] = 1;
         Ctx cg{sg, nullptr};
         const int r = run_refresh(plan->groups[g], true, q, cg);
         if (rc == TSR_OK) rc = r;
-        TSR_HIP(hipEventRecord(plan->joined[g - 1], sg));
     }
     {
         Ctx c0{st, nullptr};
@@ -1146,7 +1338,13 @@ int tsr_refresh_batched(tsr_plan* plan, const float* const* Omegas, int q, void*
         if (rc == TSR_OK) rc = r;
     }
     // join: the caller's stream continues when every group is done
-    for (size_t g = 1; g < plan->groups.size(); ++g) TSR_HIP(hipStreamWaitEvent(st, plan->joined[g - 1], 0));
+    for (size_t g = 1; g < plan->groups.size(); ++g) {
+        if (!forked[g]) continue;
+        const hipError_t e = hipEventRecord(plan->joined[g - 1], plan->side[g - 1]);
+        note(e);
+        if (e == hipSuccess) note(hipStreamWaitEvent(st, plan->joined[g - 1], 0));
+        else note(hipStreamSynchronize(plan->side[g - 1]));   // no event to wait on: drain the side stream here
+    }
     return rc;
 }
 

@@ -25,12 +25,31 @@ struct NtStageH {
     bool empty() const { return probs.empty(); }
 };
 
+// One GEMM of a stage, C = A B^T in the NT family's operand form.
+struct NtLogical {
+    const void* A; const void* B; void* out;
+    long long lda, ldb, ldc;
+    int M, N, K;
+    int block;      // owning matrix block (tiles of one block stay on one XCD)
+    int group;      // consecutive entries with the same group >= 0 are summed into `out`
+    long long b_piece_stride = 0;   // NtVariant::b_pieces > 1: elements between the pieces of B
+};
+
+// Tile lists, k splits and partial buffers of one launch (want_tiles: split k while the launch has
+// fewer tiles; persistent: one list of tiles per workgroup; group_m: see the definition), its device
+// tables, and the launch itself (plus the fixed-order reduction of k-split partials).
+// lower_only: symmetric outputs of which only the tiles on or below the diagonal are computed.
+void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogical>& gemms, int n_blocks, Arena& ar,
+                    int want_tiles, bool persistent = false, int group_m = 0, bool lower_only = false);
+void upload_nt_stage(NtStageH& st, Arena& ar, Uploader& up);
+int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind, const AdamScalars* adam = nullptr);
+
 struct FastStep {
     std::vector<ShadowBlock> shadows;  const ShadowBlock* d_shadows = nullptr;
     int max_rows = 0, max_r = 0;
     NtStageH gv[2];      // P^T = V^T G^T   (index: dtype of G), blocks the projection kernel cannot take
     struct ProjGroup {   // bf16 gradients of one rank handled by the projection kernel
-        int r = 0, panel_rows = 128, variant = 0;
+        int r = 0, panel_rows = 128, depth = 2;
         std::vector<ProjItem> items;  const ProjItem* d_items = nullptr;
     };
     std::vector<ProjGroup> projs;

@@ -14,25 +14,18 @@ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 inline long long round8(long long x) { return (x + 7) / 8 * 8; }
 constexpr int N_XCD = 8;
 
-struct NtLogical {
-    const void* A; const void* B; void* out;
-    long long lda, ldb, ldc;
-    int M, N, K;
-    int block;      // owning matrix block (tiles of one block stay on one XCD)
-    int group;      // consecutive entries with the same group >= 0 are summed into `out`
-};
-
 // Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2:
 // give every block to one XCD (greedy by work) and interleave the per-XCD tile lists, so the
 // tiles that re-read a block's operands hit the L2 that already holds them.
 // Tuning knobs read from the environment at plan creation (integers; unset = the built-in,
-// measured-best choice): TSR_TUNE_GV / UTP / UD / TVT select the NtShape of a stage,
-// TSR_TUNE_GV_PERSIST / UTP_PERSIST the persistent launch of that stage, TSR_TUNE_UTP_TILES the
-// tile count U^T P is split towards, TSR_TUNE_XCD=0 keeps the natural tile order,
-// TSR_TUNE_PROJ=0 routes G V through the NT family instead of the projection kernel
-// (TSR_TUNE_PROJ_ROWS, TSR_TUNE_PROJ_VARIANT: its panel height and pipeline depth),
-// TSR_TUNE_FUSED_LIFT=0 uses the two-GEMM lift, TSR_TUNE_LIFT_MODE / LIFT_SETUP / LIFT_CUS shape
-// the fused lift kernel's items and work lists.
+// measured-best choice): TSR_TUNE_XCD=0 keeps the natural tile order, TSR_TUNE_LPT=0 the block
+// order within an XCD, TSR_TUNE_GV_BAND / TVT_BAND the tile-row bands of those stages,
+// TSR_TUNE_GV_PERSIST / UTP_PERSIST the persistent launch of a stage, TSR_TUNE_UTP_TILES the tile
+// count U^T P is split towards, TSR_TUNE_PROJ=0 routes G V through the NT family instead of the
+// projection kernel (TSR_TUNE_PROJ_DEPTH: its pipeline depth), TSR_TUNE_FUSED_LIFT=0 uses the
+// two-GEMM lift, TSR_TUNE_LIFT_MODE / LIFT_SETUP / LIFT_CUS shape the fused lift kernel's items
+// and work lists, TSR_TUNE_ADAM_FUSED=0 keeps Adam out of the U^T P epilogue.  Which tile shape a
+// stage runs on is a rule of the rank, not a knob.
 int tune_int(const char* name, int dflt, int lo, int hi) {
     const char* v = std::getenv(name);
     if (!v || !*v) return dflt;
@@ -58,8 +51,14 @@ void interleave_xcd(std::vector<TileT>& tiles, const std::vector<int>& tile_bloc
         xcd_of[b] = best;
         load[best] += work[b];
     }
+    // Within an XCD the tiles with the longest contraction go first (stable: the tiles of one block
+    // keep their order and stay neighbours), so that the launch does not end on its longest tiles.
+    std::vector<size_t> idx(tiles.size());
+    std::iota(idx.begin(), idx.end(), (size_t)0);
+    if (tune("TSR_TUNE_LPT", 1) != 0)
+        std::stable_sort(idx.begin(), idx.end(), [&](size_t a, size_t b) { return tile_work[a] > tile_work[b]; });
     std::vector<TileT> lists[N_XCD];
-    for (size_t i = 0; i < tiles.size(); ++i) lists[xcd_of[tile_block[i]]].push_back(tiles[i]);
+    for (size_t i : idx) lists[xcd_of[tile_block[i]]].push_back(tiles[i]);
     size_t longest = 0;
     for (auto& l : lists) longest = std::max(longest, l.size());
     std::vector<TileT> out;
@@ -114,13 +113,15 @@ void persistent_lists(std::vector<NtTile>& tiles, std::vector<NtRange>& ranges, 
     tiles.swap(out);
 }
 
+}  // namespace
+
 // group_m: order of a problem's output tiles within one k split.  0: row of tiles after row of
 // tiles.  g > 0: bands of g tile rows, and inside a band column after column (the g tiles of a
 // column are neighbours).  The workgroups resident on an XCD at one time then cover a compact patch
 // of the output: they share g row panels of A, which stay in that XCD's L2 for the whole band, and
 // each column panel of B is fetched once per band instead of once per tile row.
 void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogical>& gemms, int n_blocks, Arena& ar,
-                    int want_tiles, bool persistent = false, int group_m = 0) {
+                    int want_tiles, bool persistent, int group_m, bool lower_only) {
     st = NtStageH{};
     st.var = var;
     if (gemms.empty()) return;
@@ -167,6 +168,7 @@ void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogi
             const NtLogical& g = gemms[j];
             NtProblem& p = st.probs[j];
             p.A = g.A; p.B = g.B; p.lda = g.lda; p.ldb = g.ldb; p.M = g.M; p.N = g.N; p.K = g.K;
+            p.b_piece_stride = g.b_piece_stride;
             if (direct) {
                 p.C = g.out; p.ldc = g.ldc; p.c_split_stride = 0; p.kchunk = std::max(64, cdiv(g.K, 64) * 64);
                 ksplit[j] = 1;
@@ -182,6 +184,7 @@ void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogi
                     for (int t2 = 0; t2 < (group_m > 0 ? tnn : 1); ++t2)
                         for (int tm = tb; tm < std::min(tmn, tb + band); ++tm)
                             for (int t3 = 0; t3 < (group_m > 0 ? 1 : tnn); ++t3) {
+                                if (lower_only && ((group_m > 0) ? t2 : t3) * TN > tm * TM + TM - 1) continue;
                                 st.tiles.push_back(NtTile{(int)j, tm, (group_m > 0) ? t2 : t3, ks});
                                 tile_block.push_back(g.block);
                                 tile_work.push_back(std::min(p.kchunk, g.K) + 64);
@@ -196,7 +199,7 @@ void build_nt_stage(NtStageH& st, const NtVariant& var, const std::vector<NtLogi
         interleave_xcd(st.tiles, tile_block, tile_work, n_blocks, NtTile{-1, 0, 0, 0});
 }
 
-int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind, const AdamScalars* adam = nullptr) {
+int run_nt_stage(const NtStageH& st, float alpha, float beta, Ctx& cx, int kind, const AdamScalars* adam) {
     if (st.empty()) return TSR_OK;
     Timed timed(cx, kind);
     NtLaunch L{};
@@ -223,8 +226,6 @@ void upload_nt_stage(NtStageH& st, Arena& ar, Uploader& up) {
     if (!st.ranges.empty()) st.d_ranges = up.put(st.ranges, ar);
 }
 
-}  // namespace
-
 // The NT kernels fetch 16-byte chunks through 32-bit buffer offsets: every gradient needs a
 // 16-byte aligned base, a row pitch (and worker stride) that is a multiple of 16 bytes and covers
 // the column count rounded up to 8 elements, and tiles past the last row must still be
@@ -248,13 +249,18 @@ bool fast_step_eligible(const std::vector<BlockView>& blocks, int n_workers) {
 void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_workers, Arena& ar) {
     fs.shadows.clear(); fs.adam.clear(); fs.lifts.clear(); fs.projs.clear();
     const bool use_proj_kernel = tune_int("TSR_TUNE_PROJ", 1, 0, 1) != 0;
-    const int proj_rows = tune_int("TSR_TUNE_PROJ_ROWS", 128, 64, 128) == 64 ? 64 : 128;
-    // 1 (measured best): two k-tiles in flight, two workgroups per CU; 0: four in flight, one per CU
-    const int proj_variant = tune_int("TSR_TUNE_PROJ_VARIANT", 1, 0, 1);
+    const int proj_rows = 128;
+    // gradient tiles in flight per workgroup: 2 (measured best: two workgroups per compute unit) or 4 (one)
+    const int proj_depth = tune_int("TSR_TUNE_PROJ_DEPTH", 2, 2, 4) == 4 ? 4 : 2;
     std::map<int, std::vector<int>> proj_block;
     std::map<int, std::vector<long long>> proj_work;
     fs.max_rows = 0; fs.max_r = 0;
     const bool fused_lift = tune_int("TSR_TUNE_FUSED_LIFT", 1, 0, 1) != 0;
+    int r_all = 0;
+    for (const BlockView& b : blocks) r_all = std::max(r_all, b.r);
+    // ranks above 256: the wide-tile kernel for the two products with a bf16 output
+    const int s1_shape = r_all > 256 ? NT_256x256_K32 : (r_all > 64 ? NT_128x128 : NT_64x256);
+    const int ud_shape = r_all > 256 ? NT_256x256_K32 : NT_128x128, tvt_shape = NT_128x128;
     const int lift_cus = tune_int("TSR_TUNE_LIFT_CUS", 256, 8, 4096);       // compute units of the target
     const int lift_setup = tune_int("TSR_TUNE_LIFT_SETUP", 2, 0, 16);       // cost of an item's setup, in tiles
     const int lift_mode = tune_int("TSR_TUNE_LIFT_MODE", 2, 0, 2);
@@ -289,7 +295,7 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
             if (use_proj) {
                 FastStep::ProjGroup* pg = nullptr;
                 for (auto& g : fs.projs) if (g.r == b.r) pg = &g;
-                if (!pg) { fs.projs.emplace_back(); pg = &fs.projs.back(); pg->r = b.r; pg->panel_rows = proj_rows; pg->variant = (proj_rows == 128) ? proj_variant : 0; }
+                if (!pg) { fs.projs.emplace_back(); pg = &fs.projs.back(); pg->r = b.r; pg->panel_rows = proj_rows; pg->depth = proj_depth; }
                 for (int row0 = 0; row0 < b.m; row0 += proj_rows) {
                     pg->items.push_back(ProjItem{Gw, VTf, PT, b.ldg, ldm, b.m, b.n, row0});
                     proj_block[b.r].push_back(bi);
@@ -364,21 +370,22 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
         ProjItem idle{};
         interleave_xcd(g.items, blk, wk, nb, idle);
     }
-    const int s1_shape = tune("TSR_TUNE_GV", (r_max > 64) ? NT_128x128 : NT_64x256);
     // persistent launches pay off for the many short tiles of U^T P, not for the G V stage
     const bool gv_persist = tune_int("TSR_TUNE_GV_PERSIST", 0, 0, 1) != 0;
     const bool utp_persist = tune_int("TSR_TUNE_UTP_PERSIST", 1, 0, 1) != 0;
     // P^T = V^T G^T has r / 128 tile rows over every panel of G: all of them side by side, so that the
     // panel comes from memory once; W = beta W + T V^T in bands of eight tile rows
     const int gv_band = tune_int("TSR_TUNE_GV_BAND", 8, 0, 64), tvt_band = tune_int("TSR_TUNE_TVT_BAND", 8, 0, 64);
-    build_nt_stage(fs.gv[TSR_F32], NtVariant{s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1, gv_persist, gv_band);
-    build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1, gv_persist, gv_band);
+    // the shapes without a persistent form (wide tiles) always launch one tile per workgroup
+    const bool gv_p = gv_persist && s1_shape != NT_256x256_K32;
+    build_nt_stage(fs.gv[TSR_F32], NtVariant{(s1_shape == NT_256x256_K32) ? (int)NT_128x128 : s1_shape, 1, 1}, gv[TSR_F32], nb, ar, 1, gv_p, gv_band);
+    build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1, gv_p, gv_band);
     // cores up to 256 x 256 are cut into 64 x 64 tiles (enough of them to fill the chip without
     // splitting k); larger cores have enough 128 x 128 tiles
-    build_nt_stage(fs.utp, NtVariant{tune("TSR_TUNE_UTP", r_max >= 512 ? NT_128x128 : NT_64x64), 0, 0}, utp, nb, ar,
+    build_nt_stage(fs.utp, NtVariant{r_max >= 512 ? NT_128x128 : NT_64x64, 0, 0}, utp, nb, ar,
                    tune_int("TSR_TUNE_UTP_TILES", 2048, 1, 65536), utp_persist);
-    build_nt_stage(fs.ud, NtVariant{tune("TSR_TUNE_UD", NT_128x128), 0, 1}, ud, nb, ar, 1);
-    build_nt_stage(fs.tvt, NtVariant{tune("TSR_TUNE_TVT", NT_128x128), 0, 0}, tvt, nb, ar, 1, false, tvt_band);
+    build_nt_stage(fs.ud, NtVariant{ud_shape, 0, 1}, ud, nb, ar, 1);
+    build_nt_stage(fs.tvt, NtVariant{tvt_shape, 0, 0}, tvt, nb, ar, 1, false, tvt_band);
 }
 
 void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {
@@ -424,7 +431,7 @@ int run_fast_step(FastStep& fs, int n_workers, const AdamScalars& s, float lr, f
     TSR_TRY(run_nt_stage(fs.gv[TSR_BF16], 1.0f, 0.0f, cx, TSR_PROF_GV));
     for (const auto& g : fs.projs) {
         Timed timed(cx, TSR_PROF_GV);
-        TSR_HIP(launch_proj(g.d_items, (int)g.items.size(), g.r, g.panel_rows + g.variant, cx.s));
+        TSR_HIP(launch_proj(g.d_items, (int)g.items.size(), g.r, g.depth, cx.s));
     }
     TSR_TRY(run_nt_stage(fs.utp, 1.0f / (float)n_workers, 0.0f, cx, TSR_PROF_UTP, fs.adam_fused ? &s : nullptr));
     if (!fs.adam_fused) {

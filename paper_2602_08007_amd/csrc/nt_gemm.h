@@ -22,6 +22,7 @@ struct NtProblem {
     int M, N, K;
     int kchunk;             // multiple of 64
     const AdamTBlock* adam; // fused Adam epilogue (NtVariant::fused_adam): this core's moment arrays
+    long long b_piece_stride;   // NtVariant::b_pieces > 1: elements between the bf16 pieces of B
 };
 
 struct NtTile { int prob, tm, tn, ks; };     // prob < 0: idle workgroup
@@ -41,16 +42,20 @@ struct NtLaunch {
 };
 
 enum NtShape {
-    NT_128x128 = 0, NT_256x64 = 1, NT_64x256 = 2, NT_64x64 = 3,               // 64-deep k-tiles
-    NT_128x128_K32 = 4, NT_256x64_K32 = 5, NT_256x128_K32 = 6, NT_128x256_K32 = 7,   // 32-deep
-    NT_256x128 = 8, NT_SHAPES = 9
+    NT_128x128 = 0,         // 64-deep k-tiles, two workgroups per compute unit
+    NT_64x256 = 1,          // P^T of ranks up to 64
+    NT_64x64 = 2,           // cores up to 256 x 256
+    NT_128x128_K32 = 3,     // 32-deep k-tiles; with two pieces of B: the refresh products
+    NT_256x128_K32 = 4,     // wide-tile kernel, two pieces of B only
+    NT_256x256_K32 = 5,     // wide-tile kernel, one workgroup per compute unit
+    NT_SHAPES = 6
 };
 inline int nt_tile_m(int s) {
-    static const int tm[NT_SHAPES] = {128, 256, 64, 64, 128, 256, 256, 128, 256};
+    static const int tm[NT_SHAPES] = {128, 64, 64, 128, 256, 256};
     return tm[s];
 }
 inline int nt_tile_n(int s) {
-    static const int tn[NT_SHAPES] = {128, 64, 256, 64, 128, 64, 128, 256, 128};
+    static const int tn[NT_SHAPES] = {128, 256, 64, 128, 128, 256};
     return tn[s];
 }
 
@@ -60,6 +65,8 @@ struct NtVariant {
     int out_bf16;   // C stored as bf16 (beta ignored)
     int fused_adam; // persistent launches only: C (an r x r core, ldc = r) is final after this GEMM and
                     // the epilogue runs Adam on it (C, M, Vm, D and the bf16 D^T written there)
+    int b_pieces;   // 0 or 1: B is one bf16 (or fp32) array; 2, 3: B is the sum of that many bf16 arrays
+                    // (fp32 output, no read-modify-write, one tile per workgroup only)
 };
 
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream);
@@ -88,7 +95,32 @@ struct ProjItem {
     int m, n, row0;
 };
 bool proj_supports_rank(int r);
-hipError_t launch_proj(const ProjItem* items_dev, int n_items, int r, int panel_rows, hipStream_t stream);   // panel_rows: 128 or 64
+// depth: gradient tiles in flight per workgroup: 2 (two workgroups per compute unit) or 4 (one)
+hipError_t launch_proj(const ProjItem* items_dev, int n_items, int r, int depth, hipStream_t stream);
+
+// ---- operands of the refresh GEMMs in the k-contiguous bf16 form of this family
+// Transposed bf16 copy of a gradient: dst (cols x rows, leading dimension ldd >= rows rounded up to 8,
+// the padding written as zeros) = src^T for src (rows x cols bf16, leading dimension lds, even).
+struct TransposeBlock {
+    const void* src; void* dst;
+    long long ld_src, ld_dst;
+    int rows, cols;
+};
+hipError_t launch_transpose_bf16(const TransposeBlock* table_dev, int blocks, int max_rows, int max_cols, hipStream_t stream);
+
+// An fp32 matrix X (rows x k, contiguous) as `pieces` bf16 matrices of its transpose: piece p
+// (k x ld_dst, at dst + p * piece_stride elements) holds the p-th term of x = x0 + x1 (+ x2) with
+// x0 = bf16(x), x1 = bf16(x - x0), ...; the padding columns rows .. ld_dst - 1 are written as zeros.
+struct SplitBlock {
+    const float* X; void* dst;
+    long long ld_dst, piece_stride;
+    int rows, k;
+};
+hipError_t launch_split_transpose(const SplitBlock* table_dev, int blocks, int max_rows, int max_k, int pieces,
+                                  hipStream_t stream);
+// The same pieces without the transposition: piece p (rows x ld_dst, at dst + p * piece_stride) of
+// X (rows x k, contiguous); the padding columns k .. ld_dst - 1 are written as zeros.
+hipError_t launch_split_rows(const SplitBlock* table_dev, int blocks, int max_rows, int max_k, int pieces, hipStream_t stream);
 
 hipError_t launch_shadows(const ShadowBlock* table_dev, int blocks, int max_rows, int max_r, hipStream_t stream);
 

@@ -31,51 +31,58 @@ __device__ inline nt_rsrc_t nt_make_rsrc(const void* p, long long bytes) {
 }
 
 // rows x K operand, k contiguous; tile rows row0.., k0..k0+BK-1.  Thread t owns chunks
-// c = t + 256*it: row c/(BK/8), k offset (c%(BK/8))*8.  `tail`: this k-tile crosses kend.
+// c = t + 256*it: row c/(BK/8), k offset (c%(BK/8))*8 (the same k offset for every chunk of a
+// thread, since 256 is a multiple of BK/8).  `live` = false (wave-uniform): the whole tile reads
+// as zero without touching memory (poisoned offsets), which lets the pipeline issue its loads
+// unconditionally.  The k guard of a partial last k-tile is applied by nt_store.
 template <int ROWS, int BK, bool F32>
 __device__ inline void nt_load(NtStage<ROWS * BK / 8 / NT_THREADS, F32>& s, nt_rsrc_t rs, unsigned ld_bytes, int row0,
-                               int k0, int kend, bool tail, int tid) {
+                               int k0, bool live, int tid) {
     constexpr int CPR = BK / 8;
     constexpr int ESZ = F32 ? 4 : 2;
     constexpr int CH = ROWS * CPR / NT_THREADS;
+    const unsigned poison = live ? 0u : 0x80000000u;       // in-range offsets stay below 2^31 (checked on the host)
 #pragma unroll
     for (int it = 0; it < CH; ++it) {
         const int c = tid + NT_THREADS * it;
         const unsigned grow = row0 + c / CPR;
         const int gk = k0 + (c % CPR) * 8;
-        const unsigned voff = grow * ld_bytes + (unsigned)gk * ESZ;
+        const unsigned voff = (grow * ld_bytes + (unsigned)gk * ESZ) | poison;
         if constexpr (F32) {
             s.v[it][0] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, 0, 0));
-            s.v[it][1] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(voff + 16), 0, 0));
+            s.v[it][1] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, 16, 0));
         } else {
             s.v[it] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, 0, 0));
         }
     }
-    if (tail) {                                             // wave-uniform: last k-tile only
-#pragma unroll
-        for (int it = 0; it < CH; ++it) {
-            const int c = tid + NT_THREADS * it;
-            const int valid = kend - (k0 + (c % CPR) * 8);  // elements of this chunk inside [.., kend)
-            if constexpr (F32) {
-                u32x4 m0, m1;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) { m0[j] = (j < valid) ? 0xffffffffu : 0u; m1[j] = (4 + j < valid) ? 0xffffffffu : 0u; }
-                s.v[it][0] = __builtin_bit_cast(f32x4, __builtin_bit_cast(u32x4, s.v[it][0]) & m0);
-                s.v[it][1] = __builtin_bit_cast(f32x4, __builtin_bit_cast(u32x4, s.v[it][1]) & m1);
-            } else {
-                u32x4 m;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    m[j] = ((2 * j < valid) ? 0x0000ffffu : 0u) | ((2 * j + 1 < valid) ? 0xffff0000u : 0u);
-                s.v[it] = s.v[it] & m;
-            }
-        }
-    }
 }
 
+// Stage -> LDS.  `valid` = elements of this thread's chunks that lie before the end of the k range
+// (8 or more: all of them; only the last k-tile of a range has fewer); the rest is stored as zero.
 template <int ROWS, int BK, bool F32>
-__device__ inline void nt_store(const NtStage<ROWS * BK / 8 / NT_THREADS, F32>& s, unsigned short* lds, int tid) {
+__device__ inline void nt_store(const NtStage<ROWS * BK / 8 / NT_THREADS, F32>& s, unsigned short* lds, int tid, int valid,
+                                bool tail) {
     constexpr int CPR = BK / 8, KP = BK + 8;
+    if (!tail) {                                            // wave-uniform: every k-tile but the last of a range
+#pragma unroll
+        for (int it = 0; it < ROWS * CPR / NT_THREADS; ++it) {
+            const int c = tid + NT_THREADS * it;
+            unsigned short* dst = lds + (c / CPR) * KP + (c % CPR) * 8;
+            if constexpr (F32) {
+                bf16x8 h;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) h[j] = (__bf16)s.v[it][j >> 2][j & 3];
+                *(bf16x8*)dst = h;
+            } else {
+                *(u32x4*)dst = s.v[it];
+            }
+        }
+        return;
+    }
+    u32x4 m;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        m[j] = ((2 * j < valid) ? 0x0000ffffu : 0u) | ((2 * j + 1 < valid) ? 0xffff0000u : 0u);
 #pragma unroll
     for (int it = 0; it < ROWS * CPR / NT_THREADS; ++it) {
         const int c = tid + NT_THREADS * it;
@@ -84,9 +91,9 @@ __device__ inline void nt_store(const NtStage<ROWS * BK / 8 / NT_THREADS, F32>& 
             bf16x8 h;
 #pragma unroll
             for (int j = 0; j < 8; ++j) h[j] = (__bf16)s.v[it][j >> 2][j & 3];
-            *(bf16x8*)dst = h;
+            *(u32x4*)dst = __builtin_bit_cast(u32x4, h) & m;
         } else {
-            *(u32x4*)dst = s.v[it];
+            *(u32x4*)dst = s.v[it] & m;
         }
     }
 }
@@ -97,7 +104,11 @@ __device__ inline unsigned short f32_to_bf16_bits(float f) {
 }
 
 // OUT: 0 = fp32 store (alpha only), 1 = bf16 store (alpha only), 2 = fp32 read-modify-write
-template <int TM, int TN, int WM, int WN, int NT_BK, bool B_F32, int OUT, int MINB>
+// NP: B is the sum of NP bf16 arrays of the same shape (an fp32 operand cut into pieces, piece p at
+// B + p * b_piece_stride elements, smallest piece last): every A fragment meets the fragments of
+// all pieces, so the product carries the fp32-grade operand at NP MFMAs per tile product while A is
+// staged and read once.
+template <int TM, int TN, int WM, int WN, int NT_BK, bool B_F32, int OUT, int MINB, int NP = 1>
 __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunch L) {
     constexpr bool OUT_BF16 = (OUT == 1);
     constexpr bool RMW = (OUT == 2);
@@ -105,7 +116,8 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
     constexpr int NT_KP = NT_BK + 8;
     constexpr int FM = TM / WM / 32, FN = TN / WN / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
-    constexpr int A_ELEMS = TM * NT_KP, B_ELEMS = TN * NT_KP, BUF = A_ELEMS + B_ELEMS;
+    constexpr int A_ELEMS = TM * NT_KP, B_ELEMS = TN * NT_KP, BUF = A_ELEMS + NP * B_ELEMS;
+    static_assert(NP == 1 || !B_F32, "pieces are bf16");
 
     const NtTile t = L.tiles[blockIdx.x];
     if (t.prob < 0) return;
@@ -127,7 +139,10 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
     // then either wholly inside the operand's extent or wholly outside it.
     const long long k8 = (K + 7) & ~7;
     const nt_rsrc_t rA = nt_make_rsrc(A, ((long long)(M - 1) * lda + k8) * 2);
-    const nt_rsrc_t rB = nt_make_rsrc(B, ((long long)(N - 1) * ldb + k8) * (B_F32 ? 4 : 2));
+    nt_rsrc_t rB[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+        rB[p] = nt_make_rsrc((const char*)B + (long long)p * pp->b_piece_stride * 2, ((long long)(N - 1) * ldb + k8) * (B_F32 ? 4 : 2));
     const unsigned lda_b = (unsigned)lda * 2u, ldb_b = (unsigned)ldb * (B_F32 ? 4u : 2u);
 
     // For the read-modify-write epilogue the C tile is fetched into registers before the k-loop
@@ -169,19 +184,29 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
     // short and its registers hold the C tile).
     constexpr int NSTAGE = RMW ? 1 : 2;
     NtStage<TM * NT_BK / 8 / NT_THREADS, false> stA[NSTAGE];
-    NtStage<TN * NT_BK / 8 / NT_THREADS, B_F32> stB[NSTAGE];
+    NtStage<TN * NT_BK / 8 / NT_THREADS, B_F32> stB[NSTAGE][NP];
     const int nk = (kend > kbeg && !skip_products) ? (kend - kbeg + NT_BK - 1) / NT_BK : 0;
 
+    // Loads are issued for every slot of the pipeline whether or not the k range still has a tile for
+    // it (tiles at or beyond nk read as zero without a memory access), and every stage is stored: the
+    // loop body is then free of branches around memory instructions, and the waits the compiler
+    // places before a stage is stored let the younger stage's loads stay in flight.
+    const int k_in_tile = (tid % (NT_BK / 8)) * 8;          // k offset of this thread's chunks within a k-tile
     auto load = [&](int slot, int tile) {
         const int k0 = kbeg + tile * NT_BK;
-        const bool tail = k0 + NT_BK > kend;
-        nt_load<TM, NT_BK, false>(stA[slot], rA, lda_b, row0, k0, kend, tail, tid);
-        nt_load<TN, NT_BK, B_F32>(stB[slot], rB, ldb_b, col0, k0, kend, tail, tid);
+        const bool live = tile < nk;
+        nt_load<TM, NT_BK, false>(stA[slot], rA, lda_b, row0, k0, live, tid);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) nt_load<TN, NT_BK, B_F32>(stB[slot][p], rB[p], ldb_b, col0, k0, live, tid);
     };
-    auto store = [&](int slot, int buf) {
+    auto store = [&](int slot, int buf, int tile) {
         unsigned short* d = lds + buf * BUF;
-        nt_store<TM, NT_BK, false>(stA[slot], d, tid);
-        nt_store<TN, NT_BK, B_F32>(stB[slot], d + A_ELEMS, tid);
+        const int k0 = kbeg + tile * NT_BK;
+        const bool tail = k0 + NT_BK > kend;
+        nt_store<TM, NT_BK, false>(stA[slot], d, tid, kend - (k0 + k_in_tile), tail);
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+            nt_store<TN, NT_BK, B_F32>(stB[slot][p], d + A_ELEMS + p * B_ELEMS, tid, kend - (k0 + k_in_tile), tail);
     };
     auto compute = [&](int buf) {
         const unsigned short* sA = lds + buf * BUF;
@@ -189,56 +214,60 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
 #pragma unroll
         for (int kk = 0; kk < NT_BK / 16; ++kk) {
             const int kofs = kk * 16 + (lane >> 5) * 8;
-            bf16x8 fa[FM], fb[FN];
+            bf16x8 fa[FM], fb[NP][FN];
 #pragma unroll
             for (int i = 0; i < FM; ++i)
                 fa[i] = *(const bf16x8*)(sA + (wm * (FM * 32) + i * 32 + (lane & 31)) * NT_KP + kofs);
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                fb[j] = *(const bf16x8*)(sB + (wn * (FN * 32) + j * 32 + (lane & 31)) * NT_KP + kofs);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
+            for (int p = 0; p < NP; ++p)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    fb[p][j] = *(const bf16x8*)(sB + p * B_ELEMS + (wn * (FN * 32) + j * 32 + (lane & 31)) * NT_KP + kofs);
+#pragma unroll
+            for (int p = NP - 1; p >= 0; --p)               // smallest piece first
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[p][j], acc[i][j], 0, 0, 0);
         }
     };
 
-    if constexpr (NSTAGE == 2) {
-        // prologue: tile 0 -> LDS buffer 0; tiles 1 and 2 -> register stages 1 and 0
-        if (nk > 0) {
+    if (nk > 0) {
+        if constexpr (NSTAGE == 2) {
+            // prologue: tile 0 -> LDS buffer 0; tiles 1 and 2 -> register stages 1 and 0
             load(0, 0);
-            store(0, 0);
+            store(0, 0, 0);
             __syncthreads();
-            if (nk > 1) load(1, 1);
-            if (nk > 2) load(0, 2);
-        }
-        // iteration `it` multiplies LDS buffer it&1, moves tile it+1 (register stage (it+1)&1) into
-        // the other buffer and refills that stage with tile it+3
-        for (int it = 0; it < nk; it += 2) {
-            compute(0);
-            if (it + 1 < nk) store(1, 1);
-            __syncthreads();
-            if (it + 3 < nk) load(1, it + 3);
-            if (it + 1 < nk) {
-                compute(1);
-                if (it + 2 < nk) store(0, 0);
+            load(1, 1);
+            __builtin_amdgcn_sched_barrier(0);               // keep the issue order: the loop waits for the older stage only
+            load(0, 2);
+            // the pair (it, it + 1): multiply LDS buffer 0, move tile it + 1 (stage 1) into buffer 1 and
+            // refill that stage with tile it + 3; then the same with the roles exchanged.  With an odd
+            // nk the last half-step multiplies a tile of zeros.
+            for (int it = 0; it < nk; it += 2) {
+                compute(0);
+                store(1, 1, it + 1);
                 __syncthreads();
-                if (it + 4 < nk) load(0, it + 4);
+                load(1, it + 3);
+                compute(1);
+                store(0, 0, it + 2);
+                __syncthreads();
+                load(0, it + 4);
             }
-        }
-    } else {
-        if (nk > 0) {
+        } else {
+            // one stage: every load is waited for at the next store anyway, so the steps past the last
+            // k-tile are simply skipped
             load(0, 0);
-            store(0, 0);
+            store(0, 0, 0);
             __syncthreads();
             if (nk > 1) load(0, 1);
-        }
-        for (int it = 0; it < nk; ++it) {
-            compute(it & 1);
-            if (it + 1 < nk) store(0, (it + 1) & 1);
-            __syncthreads();
-            if (it + 2 < nk) load(0, it + 2);
+            for (int it = 0; it < nk; ++it) {
+                compute(it & 1);
+                if (it + 1 < nk) store(0, (it + 1) & 1, it + 1);
+                __syncthreads();
+                if (it + 2 < nk) load(0, it + 2);
+            }
         }
     }
 
@@ -257,6 +286,171 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
                     if constexpr (RMW) v += beta * cold[i][j][e];
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rC, (int)vo, 0, 0);
                 }
+            }
+}
+
+// ------------------------------------------------------------------ wide-tile variant
+// One workgroup per compute unit, four waves in a 2 x 2 layout, each wave FM x FN fragments of
+// 32 x 32 (256 x 256 outputs per workgroup with FM = FN = 4), 32-deep k-tiles.  What bounds the
+// 128 x 128 kernels above is the traffic between the L2 and the compute unit (each staged byte
+// serves 64 flops there); a tile twice as wide halves that traffic, but leaves one wave per SIMD,
+// so nothing hides a wave's own LDS and memory latencies unless its instruction stream does.  The
+// loop below is therefore scheduled by hand (scheduling barriers pin the order): the fragments of
+// the next k step are read from LDS while the MFMAs of the current one issue, the next k-tile moves
+// from its register stage into the other LDS buffer under the first k step, the barrier sits inside
+// the second k step, and the loads of the k-tile three ahead and the first fragments of the next
+// k-tile follow it, under the remaining MFMAs.
+// OUT: 0 = fp32 store, 1 = bf16 store.  NP: pieces of B (see nt_gemm_kernel).
+template <int FM, int FN, int NP, int OUT>
+__global__ __launch_bounds__(NT_THREADS, 1) void nt_wide_kernel(const NtLaunch L) {
+    constexpr bool OUT_BF16 = (OUT == 1);
+    constexpr int BK = 32, KP = BK + 8;
+    constexpr int TM = 2 * FM * 32, TN = 2 * FN * 32;
+    constexpr int A_ELEMS = TM * KP, B_ELEMS = TN * KP, BUF = A_ELEMS + NP * B_ELEMS;
+    constexpr int CHA = TM * BK / 8 / NT_THREADS, CHB = TN * BK / 8 / NT_THREADS;
+    constexpr int NFRAG = FM + NP * FN;                     // fragment reads per k step
+    constexpr int NMFMA = FM * FN * NP;                     // MFMAs per k step
+    static_assert(NMFMA % 8 == 0 && NFRAG % 4 == 0, "the schedule issues the MFMAs of a k step in eight groups");
+    constexpr int GRP = NMFMA / 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+
+    const NtTile t = L.tiles[blockIdx.x];
+    if (t.prob < 0) return;
+    const NtProblem* pp = L.probs + t.prob;
+    const int M = pp->M, N = pp->N, K = pp->K;
+    const long long lda = pp->lda, ldb = pp->ldb, ldc = pp->ldc;
+    const int kbeg = t.ks * pp->kchunk;
+    const int kend = min(K, kbeg + pp->kchunk);
+    const int row0 = t.tm * TM, col0 = t.tn * TN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const long long k8 = (K + 7) & ~7;
+    const nt_rsrc_t rA = nt_make_rsrc(pp->A, ((long long)(M - 1) * lda + k8) * 2);
+    nt_rsrc_t rB[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+        rB[p] = nt_make_rsrc((const char*)pp->B + (long long)p * pp->b_piece_stride * 2, ((long long)(N - 1) * ldb + k8) * 2);
+    const unsigned lda_b = (unsigned)lda * 2u, ldb_b = (unsigned)ldb * 2u;
+    const int nk = (kend > kbeg) ? (kend - kbeg + BK - 1) / BK : 0;
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    NtStage<CHA, false> stA[2];
+    NtStage<CHB, false> stB[2][NP];
+    const int k_in_tile = (tid % (BK / 8)) * 8;
+    auto load = [&](int slot, int tile) {                   // unconditional: tiles at or beyond nk read as zero
+        const int k0 = kbeg + tile * BK;
+        const bool live = tile < nk;
+        nt_load<TM, BK, false>(stA[slot], rA, lda_b, row0, k0, live, tid);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) nt_load<TN, BK, false>(stB[slot][p], rB[p], ldb_b, col0, k0, live, tid);
+    };
+    auto store = [&](int slot, int buf, int tile) {
+        unsigned short* d = lds + buf * BUF;
+        const int k0 = kbeg + tile * BK;
+        const bool tail = k0 + BK > kend;
+        nt_store<TM, BK, false>(stA[slot], d, tid, kend - (k0 + k_in_tile), tail);
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+            nt_store<TN, BK, false>(stB[slot][p], d + A_ELEMS + p * B_ELEMS, tid, kend - (k0 + k_in_tile), tail);
+    };
+    // fragment f of k step kk of LDS buffer buf: f < FM: A rows; else piece (f - FM) / FN, column group (f - FM) % FN
+    const int a_off = (wm * (FM * 32) + (lane & 31)) * KP + (lane >> 5) * 8;
+    const int b_off = A_ELEMS + (wn * (FN * 32) + (lane & 31)) * KP + (lane >> 5) * 8;
+    auto frag = [&](int buf, int kk, int f) -> bf16x8 {
+        const unsigned short* base = lds + buf * BUF + kk * 16;
+        if (f < FM) return *(const bf16x8*)(base + a_off + f * 32 * KP);
+        const int g = f - FM;
+        return *(const bf16x8*)(base + b_off + (g / FN) * B_ELEMS + (g % FN) * 32 * KP);
+    };
+    bf16x8 F[2][NFRAG];
+    // MFMA number q of a k step: pieces from the smallest to the largest, then rows, then columns
+    auto mfma = [&](const bf16x8* f, int q) {
+        const int p = NP - 1 - q / (FM * FN), i = (q / FN) % FM, j = q % FN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[FM + p * FN + j], acc[i][j], 0, 0, 0);
+    };
+#define NT_SB __builtin_amdgcn_sched_barrier(0)
+
+    if (nk > 0) {
+        load(0, 0);
+        store(0, 0, 0);
+        __syncthreads();
+        load(1, 1);
+        NT_SB;
+        load(0, 2);
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) F[0][f] = frag(0, 0, f);
+        // tile `it` sits in LDS buffer it & 1, tile it + 1 in register stage (it + 1) & 1, tile it + 2 in
+        // the other stage; F[0] holds the fragments of k step 0 of tile `it`
+        auto step = [&](int cur, int it) {
+            const int oth = cur ^ 1;
+            // ---- k step 0: MFMAs from F[0]; fragments of k step 1 -> F[1]; stage -> LDS buffer `oth`
+            NT_SB;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+#pragma unroll
+                for (int u = 0; u < GRP; ++u) mfma(F[0], g * GRP + u);
+                NT_SB;
+                if (g < 4) {                                  // early, so that the second half of the k step covers their latency
+#pragma unroll
+                    for (int f = g * NFRAG / 4; f < (g + 1) * NFRAG / 4; ++f) F[1][f] = frag(cur, 1, f);
+                    NT_SB;
+                }
+            }
+            store(oth, oth, it + 1);                          // register stage (it + 1) & 1 == oth
+            NT_SB;
+            // ---- k step 1: MFMAs from F[1]; barrier; loads of tile it + 3; fragments of the next tile -> F[0]
+#pragma unroll
+            for (int u = 0; u < 2 * GRP; ++u) mfma(F[1], u);
+            NT_SB;
+            __syncthreads();
+            NT_SB;
+            load(oth, it + 3);
+            NT_SB;
+#pragma unroll
+            for (int g = 2; g < 8; ++g) {
+#pragma unroll
+                for (int u = 0; u < GRP; ++u) mfma(F[1], g * GRP + u);
+                NT_SB;
+                if (g < 6) {
+#pragma unroll
+                    for (int f = (g - 2) * NFRAG / 4; f < (g - 1) * NFRAG / 4; ++f) F[0][f] = frag(oth, 0, f);
+                    NT_SB;
+                }
+            }
+        };
+        for (int it = 0; it < nk; it += 2) {
+            step(0, it);
+            step(1, it + 1);                                  // with an odd nk: a tile of zeros
+        }
+    }
+#undef NT_SB
+
+    constexpr int CSZ = OUT_BF16 ? 2 : 4;
+    const nt_rsrc_t rC = nt_make_rsrc((const char*)pp->C + (long long)t.ks * pp->c_split_stride * CSZ,
+                                      ((long long)(M - 1) * ldc + N) * CSZ);
+    const unsigned ldc_b = (unsigned)ldc * CSZ;
+    const float alpha = L.alpha;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int col = col0 + wn * (FN * 32) + j * 32 + (lane & 31);
+                const int row = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4 + (e >> 2) * 8 + (e & 3);
+                const unsigned vo = (row < M && col < N) ? (unsigned)row * ldc_b + (unsigned)col * CSZ : 0x80000000u;
+                if constexpr (OUT_BF16)
+                    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_bits(alpha * acc[i][j][e]), rC, (int)vo, 0, 0);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, alpha * acc[i][j][e]), rC, (int)vo, 0, 0);
             }
 }
 
@@ -312,17 +506,25 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
     open_tile(lt);
     NtStage<TM * NT_BK / 8 / NT_THREADS, false> stA[2];
     NtStage<TN * NT_BK / 8 / NT_THREADS, B_F32> stB[2];
+    // Loads are unconditional (beyond the end of the list they read as zero without a memory access)
+    // and every stage is stored, so that the loop has no branch around a load: the compiler's waits
+    // before a stage is stored then leave the younger stage's loads in flight.
+    const int k_in_tile = (tid % (NT_BK / 8)) * 8;
+    int st_valid[2] = {0, 0};                                // per stage: elements before the end of its k range
+    bool st_tail[2] = {true, true};
     auto load_next = [&](int slot) {
+        const bool live = lt < range.end;
         const int k0 = l_kbeg + lk * NT_BK;
-        const bool tail = k0 + NT_BK > l_kend;
-        nt_load<TM, NT_BK, false>(stA[slot], rA, lda_b, l_row0, k0, l_kend, tail, tid);
-        nt_load<TN, NT_BK, B_F32>(stB[slot], rB, ldb_b, l_col0, k0, l_kend, tail, tid);
-        if (++lk == l_nk) { lk = 0; if (++lt < range.end) open_tile(lt); }
+        st_tail[slot] = !live || k0 + NT_BK > l_kend;
+        st_valid[slot] = live ? l_kend - (k0 + k_in_tile) : 0;
+        nt_load<TM, NT_BK, false>(stA[slot], rA, lda_b, l_row0, k0, live, tid);
+        nt_load<TN, NT_BK, B_F32>(stB[slot], rB, ldb_b, l_col0, k0, live, tid);
+        if (live && ++lk == l_nk) { lk = 0; if (++lt < range.end) open_tile(lt); }
     };
     auto store = [&](int slot, int buf) {
         unsigned short* d = lds + buf * BUF;
-        nt_store<TM, NT_BK, false>(stA[slot], d, tid);
-        nt_store<TN, NT_BK, B_F32>(stB[slot], d + A_ELEMS, tid);
+        nt_store<TM, NT_BK, false>(stA[slot], d, tid, st_valid[slot], st_tail[slot]);
+        nt_store<TN, NT_BK, B_F32>(stB[slot], d + A_ELEMS, tid, st_valid[slot], st_tail[slot]);
     };
 
     // ---- compute cursor
@@ -424,21 +626,22 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
     load_next(0);
     store(0, 0);
     __syncthreads();
-    if (total > 1) load_next(1);
-    if (total > 2) load_next(0);
+    load_next(1);
+    __builtin_amdgcn_sched_barrier(0);                       // keep the issue order: the loop waits for the older stage only
+    load_next(0);
     for (int g = 0; g < total; g += 2) {
         compute(0);
         finish_step();
-        if (g + 1 < total) store(1, 1);
+        store(1, 1);
         __syncthreads();
-        if (g + 3 < total) load_next(1);
-        if (g + 1 < total) {
+        load_next(1);
+        if (g + 1 < total) {                                 // no memory instruction of the pipeline depends on this branch
             compute(1);
             finish_step();
-            if (g + 2 < total) store(0, 0);
-            __syncthreads();
-            if (g + 4 < total) load_next(0);
         }
+        store(0, 0);
+        __syncthreads();
+        load_next(0);
     }
 }
 
@@ -485,9 +688,13 @@ __device__ __forceinline__ void proj_panel(const ProjItem& it, unsigned short* l
     NtStage<TN * BK / 8 / NT_THREADS, false> st[DEPTH];
     auto load_g = [&](int slot, int kt) {
         const int k0 = kt * BK;
-        nt_load<TN, BK, false>(st[slot], rG, ldg_b, row0, k0, n, k0 + BK > n, tid);
+        nt_load<TN, BK, false>(st[slot], rG, ldg_b, row0, k0, true, tid);
     };
-    auto store_g = [&](int slot, int buf) { nt_store<TN, BK, false>(st[slot], lds + buf * (TN * KP), tid); };
+    const int k_in_tile = (tid % (BK / 8)) * 8;
+    auto store_g = [&](int slot, int buf, int kt) {         // kt: the k-tile held by that stage
+        const int k0 = kt * BK;
+        nt_store<TN, BK, false>(st[slot], lds + buf * (TN * KP), tid, n - (k0 + k_in_tile), k0 + BK > n);
+    };
     auto compute = [&](int buf, int slot) {
         const unsigned short* sB = lds + buf * (TN * KP);
 #pragma unroll
@@ -512,7 +719,7 @@ __device__ __forceinline__ void proj_panel(const ProjItem& it, unsigned short* l
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
         if (d < nk) { load_g(d, d); load_a(d, d); }
-    store_g(0, 0);
+    store_g(0, 0, 0);
     __syncthreads();
     if (DEPTH < nk) load_g(0, DEPTH);
     for (int kt = 0; kt < nk; kt += DEPTH) {
@@ -522,7 +729,7 @@ __device__ __forceinline__ void proj_panel(const ProjItem& it, unsigned short* l
             if (t < nk) {
                 compute(u & 1, u);
                 if (t + DEPTH < nk) load_a(u, t + DEPTH);
-                if (t + 1 < nk) store_g((u + 1) % DEPTH, (u + 1) & 1);
+                if (t + 1 < nk) store_g((u + 1) % DEPTH, (u + 1) & 1, t + 1);
                 __syncthreads();
                 if (t + 1 + DEPTH < nk) load_g((u + 1) % DEPTH, t + 1 + DEPTH);
             }
@@ -556,20 +763,18 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void proj_kernel(const ProjItem* 
 
 bool proj_supports_rank(int r) { return r == 128 || r == 256; }
 
-hipError_t launch_proj(const ProjItem* items_dev, int n_items, int r, int panel_rows, hipStream_t stream) {
+hipError_t launch_proj(const ProjItem* items_dev, int n_items, int r, int depth, hipStream_t stream) {
     if (n_items <= 0) return hipSuccess;
-    if (r == 256 && panel_rows == 128) hipLaunchKernelGGL((proj_kernel<8, 128, 4, 1>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
-    else if (r == 256 && panel_rows == 129) hipLaunchKernelGGL((proj_kernel<8, 128, 2, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
-    else if (r == 256 && panel_rows == 64) hipLaunchKernelGGL((proj_kernel<8, 64, 4, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
-    else if (r == 128 && panel_rows >= 128) hipLaunchKernelGGL((proj_kernel<4, 128, 4, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
-    else if (r == 128 && panel_rows == 64) hipLaunchKernelGGL((proj_kernel<4, 64, 4, 3>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    if (r == 256 && depth == 4) hipLaunchKernelGGL((proj_kernel<8, 128, 4, 1>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    else if (r == 256 && depth == 2) hipLaunchKernelGGL((proj_kernel<8, 128, 2, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
+    else if (r == 128) hipLaunchKernelGGL((proj_kernel<4, 128, 4, 2>), dim3(n_items), dim3(NT_THREADS), 0, stream, items_dev);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ dispatch
 typedef void (*nt_fn)(const NtLaunch);
-struct NtEntry { int shape, b_f32, out; nt_fn fn; nt_fn persistent; int lds_bytes; int minb; };
+struct NtEntry { int shape, b_f32, out; nt_fn fn; nt_fn persistent; int lds_bytes; int minb; int pieces; };
 
 template <int TM, int TN, int WM, int WN, int BK, bool BF32, int OUT, int MINB>
 constexpr nt_fn nt_persistent_fn() {
@@ -578,11 +783,14 @@ constexpr nt_fn nt_persistent_fn() {
 }
 // out = 3 (fused Adam) exists as a persistent kernel only, for bf16 operands
 #define NT_ENTRY_ADAM(shape, TM, TN, WM, WN, BK, MINB) \
-    { shape, 0, 3, nullptr, nt_gemm_persistent_kernel<TM, TN, WM, WN, BK, false, 3, MINB>, 2 * (TM + TN) * (BK + 8) * 2, MINB }
+    { shape, 0, 3, nullptr, nt_gemm_persistent_kernel<TM, TN, WM, WN, BK, false, 3, MINB>, 2 * (TM + TN) * (BK + 8) * 2, MINB, 1 }
 
 #define NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, bf32, out) \
     { shape, bf32, out, nt_gemm_kernel<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>, \
-      nt_persistent_fn<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>(), 2 * (TM + TN) * (BK + 8) * 2, MINB }
+      nt_persistent_fn<TM, TN, WM, WN, BK, (bf32) != 0, out, MINB>(), 2 * (TM + TN) * (BK + 8) * 2, MINB, 1 }
+// fp32 output, B in NP bf16 pieces
+#define NT_ENTRY_PIECES(shape, TM, TN, WM, WN, BK, MINB, NP) \
+    { shape, 0, 0, nt_gemm_kernel<TM, TN, WM, WN, BK, false, 0, MINB, NP>, nullptr, 2 * (TM + (NP) * TN) * (BK + 8) * 2, MINB, NP }
 // MINB / MINB_RMW: workgroups per CU the register allocation must allow (the read-modify-write
 // variant also holds the C tile in registers)
 #define NT_SHAPE(shape, TM, TN, WM, WN, BK, MINB, MINB_RMW)                                                   \
@@ -591,19 +799,20 @@ constexpr nt_fn nt_persistent_fn() {
     NT_ENTRY(shape, TM, TN, WM, WN, BK, MINB, 1, 1)
 
 static const NtEntry kNt[] = {
-    NT_SHAPE(NT_128x128, 128, 128, 2, 2, 64, 2, 1), NT_SHAPE(NT_256x64, 256, 64, 4, 1, 64, 1, 1),
-    NT_SHAPE(NT_64x256, 64, 256, 1, 4, 64, 1, 1),   NT_SHAPE(NT_64x64, 64, 64, 2, 2, 64, 4, 4),
-    NT_SHAPE(NT_128x128_K32, 128, 128, 2, 2, 32, 3, 2), NT_SHAPE(NT_256x64_K32, 256, 64, 4, 1, 32, 3, 2),
-    NT_SHAPE(NT_256x128_K32, 256, 128, 2, 2, 32, 2, 1), NT_SHAPE(NT_128x256_K32, 128, 256, 2, 2, 32, 2, 1),
-    NT_SHAPE(NT_256x128, 256, 128, 2, 2, 64, 1, 1),
+    NT_SHAPE(NT_128x128, 128, 128, 2, 2, 64, 2, 1), NT_SHAPE(NT_64x256, 64, 256, 1, 4, 64, 1, 1),
+    NT_SHAPE(NT_64x64, 64, 64, 2, 2, 64, 4, 4),
     NT_ENTRY_ADAM(NT_64x64, 64, 64, 2, 2, 64, 4),
+    { NT_256x256_K32, 0, 0, nt_wide_kernel<4, 4, 1, 0>, nullptr, 2 * (256 + 256) * 40 * 2, 1, 1 },
+    { NT_256x256_K32, 0, 1, nt_wide_kernel<4, 4, 1, 1>, nullptr, 2 * (256 + 256) * 40 * 2, 1, 1 },
+    { NT_256x128_K32, 0, 0, nt_wide_kernel<4, 2, 2, 0>, nullptr, 2 * (256 + 2 * 128) * 40 * 2, 1, 2 },
+    NT_ENTRY_PIECES(NT_128x128_K32, 128, 128, 2, 2, 32, 2, 2),
 };
 
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream) {
     if (L.n_tiles <= 0) return hipSuccess;
     const int out = v.fused_adam ? 3 : (v.out_bf16 ? 1 : (L.beta != 0.0f ? 2 : 0));
     for (const NtEntry& e : kNt) {
-        if (e.shape == v.shape && e.b_f32 == v.b_f32 && e.out == out) {
+        if (e.shape == v.shape && e.b_f32 == v.b_f32 && e.out == out && e.pieces == (v.b_pieces > 1 ? v.b_pieces : 1)) {
             const nt_fn fn = L.ranges ? e.persistent : e.fn;
             if (fn == nullptr) return hipErrorInvalidValue;
             static thread_local const void* configured[256] = {nullptr};
@@ -623,7 +832,7 @@ hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t str
 }
 
 int nt_wgs_per_cu(int shape) {
-    for (const NtEntry& e : kNt) if (e.shape == shape && e.out == 0) return e.minb;
+    for (const NtEntry& e : kNt) if (e.shape == shape && e.out == 0 && e.pieces == 1) return e.minb;
     return 1;
 }
 
@@ -665,6 +874,113 @@ hipError_t launch_shadows(const ShadowBlock* table_dev, int blocks, int max_rows
     if (blocks <= 0) return hipSuccess;
     dim3 grid((max_r + 8 + 63) / 64, (max_rows + 8 + 63) / 64, blocks);
     hipLaunchKernelGGL(shadow_kernel, grid, dim3(256), 0, stream, table_dev);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ operands of the refresh GEMMs
+// 64 x 64 patches through LDS; element pairs (4 bytes) on both sides.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeBlock* table) {
+    const TransposeBlock b = table[blockIdx.z];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    if (r0 >= (int)b.ld_dst || c0 >= b.cols) return;
+    __shared__ unsigned short tile[64][66];
+    const unsigned short* src = (const unsigned short*)b.src;
+    unsigned short* dst = (unsigned short*)b.dst;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 pairs across, 8 rows per pass
+    for (int i = ty; i < 64; i += 8) {
+        const int r = r0 + i, c = c0 + 2 * tx;
+        unsigned v = 0u;
+        if (r < b.rows) {
+            if (c + 1 < b.cols) v = *(const unsigned*)(src + (long long)r * b.ld_src + c);
+            else if (c < b.cols) v = src[(long long)r * b.ld_src + c];
+        }
+        tile[i][2 * tx] = (unsigned short)(v & 0xffffu);
+        tile[i][2 * tx + 1] = (unsigned short)(v >> 16);
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 8) {
+        const int c = c0 + i, r = r0 + 2 * tx;                       // dst[c][r], dst[c][r + 1]
+        if (c < b.cols && r < (int)b.ld_dst)
+            *(unsigned*)(dst + (long long)c * b.ld_dst + r) = (unsigned)tile[2 * tx][i] | ((unsigned)tile[2 * tx + 1][i] << 16);
+    }
+}
+
+hipError_t launch_transpose_bf16(const TransposeBlock* table_dev, int blocks, int max_rows, int max_cols, hipStream_t stream) {
+    if (blocks <= 0) return hipSuccess;
+    dim3 grid((max_cols + 63) / 64, (max_rows + 8 + 63) / 64, blocks);
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, stream, table_dev);
+    return hipGetLastError();
+}
+
+template <int PIECES>
+__global__ __launch_bounds__(256) void split_transpose_kernel(const SplitBlock* table) {
+    const SplitBlock b = table[blockIdx.z];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    if (r0 >= (int)b.ld_dst || c0 >= b.k) return;
+    __shared__ unsigned short tile[PIECES][64][66];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        const int r = r0 + i, c = c0 + tx;
+        float x = (r < b.rows && c < b.k) ? b.X[(long long)r * b.k + c] : 0.0f;
+#pragma unroll
+        for (int p = 0; p < PIECES; ++p) {
+            const __bf16 h = (__bf16)x;
+            tile[p][i][tx] = __builtin_bit_cast(unsigned short, h);
+            x -= (float)h;
+        }
+    }
+    __syncthreads();
+    unsigned short* dst = (unsigned short*)b.dst;
+    const int px = threadIdx.x & 31, py = threadIdx.x >> 5;
+    for (int i = py; i < 64; i += 8) {
+        const int c = c0 + i, r = r0 + 2 * px;                       // piece[c][r], piece[c][r + 1]
+        if (c < b.k && r < (int)b.ld_dst) {
+#pragma unroll
+            for (int p = 0; p < PIECES; ++p)
+                *(unsigned*)(dst + (long long)p * b.piece_stride + (long long)c * b.ld_dst + r) =
+                    (unsigned)tile[p][2 * px][i] | ((unsigned)tile[p][2 * px + 1][i] << 16);
+        }
+    }
+}
+
+hipError_t launch_split_transpose(const SplitBlock* table_dev, int blocks, int max_rows, int max_k, int pieces,
+                                  hipStream_t stream) {
+    if (blocks <= 0) return hipSuccess;
+    dim3 grid((max_k + 63) / 64, (max_rows + 8 + 63) / 64, blocks);
+    if (pieces == 2) hipLaunchKernelGGL(split_transpose_kernel<2>, grid, dim3(256), 0, stream, table_dev);
+    else if (pieces == 3) hipLaunchKernelGGL(split_transpose_kernel<3>, grid, dim3(256), 0, stream, table_dev);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+template <int PIECES>
+__global__ __launch_bounds__(256) void split_rows_kernel(const SplitBlock* table) {
+    const SplitBlock b = table[blockIdx.z];
+    const int ldp = (int)b.ld_dst / 2;                                  // element pairs per output row
+    const long long pairs = (long long)b.rows * ldp;
+    unsigned* dst = (unsigned*)b.dst;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < pairs; i += (long long)gridDim.x * 256) {
+        const int r = (int)(i / ldp), c = (int)(i % ldp) * 2;
+        float x0 = (c < b.k) ? b.X[(long long)r * b.k + c] : 0.0f;
+        float x1 = (c + 1 < b.k) ? b.X[(long long)r * b.k + c + 1] : 0.0f;
+#pragma unroll
+        for (int p = 0; p < PIECES; ++p) {
+            const __bf16 h0 = (__bf16)x0, h1 = (__bf16)x1;
+            dst[((long long)p * b.piece_stride + (long long)r * b.ld_dst + c) / 2] =
+                (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16);
+            x0 -= (float)h0; x1 -= (float)h1;
+        }
+    }
+}
+
+hipError_t launch_split_rows(const SplitBlock* table_dev, int blocks, int max_rows, int max_k, int pieces, hipStream_t stream) {
+    if (blocks <= 0) return hipSuccess;
+    long long bx = ((long long)max_rows * ((max_k + 8) / 2) + 255) / 256;
+    if (bx > 2048) bx = 2048;
+    dim3 grid((unsigned)bx, 1, blocks);
+    if (pieces == 2) hipLaunchKernelGGL(split_rows_kernel<2>, grid, dim3(256), 0, stream, table_dev);
+    else if (pieces == 3) hipLaunchKernelGGL(split_rows_kernel<3>, grid, dim3(256), 0, stream, table_dev);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

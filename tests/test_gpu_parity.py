@@ -770,6 +770,35 @@ def test_refresh_batched_matches_single(tsr):
     plan.close()
 
 
+@pytest.mark.parametrize("nt", ["1", "0"])
+def test_refresh_batched_bf16_gradients(tsr, nt, monkeypatch):
+    # the plan's refresh on bf16 gradients: the products with G run on the k-contiguous bf16 family
+    # (transposed copy of G, small operand in two bf16 pieces) or, with the knob off or a gradient
+    # that family cannot read (unaligned row pitch), on the general kernel; ragged shapes, a row
+    # pitch padded with NaN, power iterations 0..2; every block against the oracle
+    monkeypatch.setenv("TSR_TUNE_REFRESH_NT", nt)
+    shapes = [(192, 256), (333, 200), (130, 264), (264, 131), (520, 1000), (200, 333)]
+    r, p = 24, 8
+    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, 721, noise=1e-3, pad_g=True)
+    for i, (b, h, (m, n)) in enumerate(zip(blocks, host, shapes)):
+        G64, _, _ = si.exact_lowrank(m, n, r, si.stream_key(722, i))
+        h["G"] = (G64.float() + si.normal((m, n), si.stream_key(723, i), std=1e-3)).to(torch.bfloat16)[None]
+        b["G"].copy_(h["G"][0])
+    plan = tsr.Plan(blocks, with_refresh=True, p=p)
+    omegas = [si.omega(n, r + p, si.stream_key(724, i)) for i, (m, n) in enumerate(shapes)]
+    dev_om = [dev(o) for o in omegas]
+    for q in (1, 0, 2):
+        plan.tsr_refresh_batched(dev_om, q)
+        torch.cuda.synchronize()
+        for b, h, om, (m, n) in zip(blocks, host, omegas, shapes):
+            U_ref, V_ref, _ = orc.refresh_rsvd(h["G"][0], om, r, p, q)
+            eu, ev = projector_err(b["U"], U_ref), projector_err(b["V"], V_ref)
+            parity_log("plan refresh bf16 G (nt=%s) %dx%d q=%d: projector errors U %.2e V %.2e" % (nt, m, n, q, eu, ev))
+            assert eu < TOL_F32 and ev < TOL_F32, (m, n, q, eu, ev)
+            check_orthonormal(b["U"]); check_orthonormal(b["V"])
+    plan.close()
+
+
 @pytest.mark.parametrize("groups", [1, 2, 3])
 def test_refresh_batched_in_groups(tsr, groups, monkeypatch):
     # twelve blocks of mixed shapes and dtypes: the batched refresh cuts them into groups that run
