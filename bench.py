@@ -184,18 +184,19 @@ def run_workload(tsr, name, args, dev, with_cpu_baseline):
         k = w.r + w.p
         gemm_flops = sum((2 * w.q + 2) * 2 * m * n * k for m, n in w.shapes)
         gemm_ms = prof["sketch_gemm"][0]
-        pieces = plan.refresh_gemm_pieces() if hasattr(plan, "refresh_gemm_pieces") else None
+        # MFMA products issued per useful product in the G-touching GEMMs: a bf16 gradient is exact in
+        # one piece and meets two bf16 pieces of the small fp32 operand; an fp32 gradient and its
+        # partner keep three pieces each, of which the six leading cross products are issued
+        pieces = 2 if w.g_dtype == torch.bfloat16 else 6
         refresh = dict(ms_total=refresh_ms, ms_per_matrix=refresh_ms / len(w.shapes),
                        ms_total_one_stream=refresh_single_ms,
                        gemm_ms=gemm_ms, gemm_tflops=gemm_flops / gemm_ms / 1e9,
                        gemm_mfma_frac=gemm_flops / gemm_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                       gemm_mfma_products_per_useful_product=pieces,
+                       gemm_issued_mfma_frac=pieces * gemm_flops / gemm_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                       gemm_ms_includes="transposed copy of G and splitting of the small operands (bf16 gradients)",
                        stages_ms={kk: round(v[0], 3) for kk, v in prof.items() if v[1]},
                        p=w.p, q=w.q)
-        if pieces:
-            # every useful product is issued as `pieces` bf16 MFMA products (fp32-grade operands)
-            refresh["gemm_bf16_pieces"] = pieces
-            refresh["gemm_issued_tflops"] = pieces * refresh["gemm_tflops"]
-            refresh["gemm_issued_mfma_frac"] = pieces * refresh["gemm_mfma_frac"]
 
     # ---- the timed step loop
     hyper = dict(lr=float(os.environ.get("TSR_BENCH_LR", "1e-3")), wd=0.0, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0)

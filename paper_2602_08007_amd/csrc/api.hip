@@ -262,11 +262,13 @@ constexpr double ORTH_DROP = 1e-6;
 // enters as two bf16 pieces in both orientations (transposed for the Gram matrix, as stored for the
 // product with R^-1), R^-1 as two pieces of its transpose; every product keeps the three leading
 // cross terms: X^T X = Xh^T Xh + Xl^T Xh + Xh^T Xl (summed by the k-split reduction, lower tiles
-// only), X R^-1 = Xh (Rh + Rl) (one launch, two pieces of B) + Xl Rh (accumulated by a second).
+// only); X R^-1 as ONE product over a doubled contraction: the rows [Xh | Xl] against the two pieces
+// [Rh | Rh] and [Rl | Rl] of the transposed factor, i.e. (Xh + Xl)(Rh + Rl).
 struct OrthNtPass {
-    std::vector<SplitBlock> st, sx, sr;       // X -> pieces of X^T; X -> pieces of X; R^-1 -> pieces of R^-T
+    std::vector<SplitBlock> st, sx, sr, sr2;  // X -> pieces of X^T; X -> [Xh | Xl]; R^-1 -> the two halves of the pieces of R^-T
     const SplitBlock* d_st = nullptr; const SplitBlock* d_sx = nullptr; const SplitBlock* d_sr = nullptr;
-    NtStageH gram, ap1, ap2;
+    const SplitBlock* d_sr2 = nullptr;
+    NtStageH gram, ap;
     int max_rows = 0, max_k = 0;
     bool empty() const { return st.empty(); }
 };
@@ -309,7 +311,7 @@ struct RefreshProgram {
 
 void build_orth_nt(OrthNtPass& pass, const std::vector<RefreshBlock>& blocks, bool on_rows_m, bool from_alt, Arena& ar) {
     pass = OrthNtPass{};
-    std::vector<NtLogical> g, a1, a2;
+    std::vector<NtLogical> g, a1;
     for (size_t i = 0; i < blocks.size(); ++i) {
         const RefreshBlock& b = blocks[i];
         if (!b.nt) continue;
@@ -320,16 +322,16 @@ void build_orth_nt(OrthNtPass& pass, const std::vector<RefreshBlock>& blocks, bo
         float* out = from_alt ? X : Xalt;
         unsigned short* Xt = on_rows_m ? b.Pm : b.Pn;            // pieces of X^T (k x ldrows)
         const long long ldrows = on_rows_m ? b.ldm : b.ldn, st_t = (long long)k * ldrows;
-        const long long st_x = (long long)rows * b.ldk, st_r = (long long)k * b.ldk;
+        const long long ld2 = 2 * b.ldk, st_r = (long long)k * ld2;      // rows of two pieces side by side
         pass.st.push_back(SplitBlock{in, Xt, ldrows, st_t, rows, k});
-        pass.sx.push_back(SplitBlock{in, b.Xp, b.ldk, st_x, rows, k});
-        pass.sr.push_back(SplitBlock{b.Rinv, b.Rt, b.ldk, st_r, k, k});
+        pass.sx.push_back(SplitBlock{in, b.Xp, ld2, b.ldk, rows, k});
+        pass.sr.push_back(SplitBlock{b.Rinv, b.Rt, ld2, st_r, k, k});
+        pass.sr2.push_back(SplitBlock{b.Rinv, b.Rt + b.ldk, ld2, st_r, k, k});
         const int bi = (int)i;
         g.push_back(NtLogical{Xt, Xt, b.S, ldrows, ldrows, k, k, k, rows, bi, bi});
         g.push_back(NtLogical{Xt + st_t, Xt, b.S, ldrows, ldrows, k, k, k, rows, bi, bi});
         g.push_back(NtLogical{Xt, Xt + st_t, b.S, ldrows, ldrows, k, k, k, rows, bi, bi});
-        a1.push_back(NtLogical{b.Xp, b.Rt, out, b.ldk, b.ldk, k, rows, k, k, bi, -1, st_r});
-        a2.push_back(NtLogical{b.Xp + st_x, b.Rt, out, b.ldk, b.ldk, k, rows, k, k, bi, -1});
+        a1.push_back(NtLogical{b.Xp, b.Rt, out, ld2, ld2, k, rows, k, (int)ld2, bi, -1, st_r});
         pass.max_rows = std::max(pass.max_rows, rows); pass.max_k = std::max(pass.max_k, k);
     }
     if (g.empty()) return;
@@ -337,8 +339,7 @@ void build_orth_nt(OrthNtPass& pass, const std::vector<RefreshBlock>& blocks, bo
     build_nt_stage(pass.gram, NtVariant{NT_128x128, 0, 0}, g, nb, ar, 512, false, 0, /*lower_only=*/true);
     NtVariant v2{};
     v2.shape = NT_128x128_K32; v2.b_pieces = 2;
-    build_nt_stage(pass.ap1, v2, a1, nb, ar, 1);
-    build_nt_stage(pass.ap2, NtVariant{NT_128x128, 0, 0}, a2, nb, ar, 1);
+    build_nt_stage(pass.ap, v2, a1, nb, ar, 1);
 }
 
 void build_orth(OrthProgram& op, const std::vector<RefreshBlock>& blocks, bool on_rows_m, Arena& ar) {
@@ -409,9 +410,9 @@ int run_orth(const OrthProgram& op, bool grouped, Ctx& cx, int passes) {
             Timed timed(cx, TSR_PROF_ORTH_GEMM);
             TSR_HIP(launch_split_rows(p.d_sx, (int)p.sx.size(), p.max_rows, p.max_k, 2, cx.s));
             TSR_HIP(launch_split_transpose(p.d_sr, (int)p.sr.size(), p.max_k, p.max_k, 2, cx.s));
+            TSR_HIP(launch_split_transpose(p.d_sr2, (int)p.sr2.size(), p.max_k, p.max_k, 2, cx.s));
         }
-        TSR_TRY(run_nt_stage(p.ap1, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
-        return run_nt_stage(p.ap2, 1.0f, 1.0f, cx, TSR_PROF_ORTH_GEMM);
+        return run_nt_stage(p.ap, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM);
     };
     TSR_TRY(nt_gram(op.ntA));
     TSR_TRY(run_stage(op.gramA, grouped, 1.0f, 0.0f, cx, TSR_PROF_ORTH_GEMM));
@@ -471,7 +472,7 @@ void build_refresh(RefreshProgram& rp, const std::vector<BlockView>& views, cons
             b.Pm = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * k * b.ldm);
             b.ldk = (b.k + 7) / 8 * 8;
             b.Xp = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * std::max(b.m, b.n) * b.ldk);
-            b.Rt = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * k * b.ldk);
+            b.Rt = ar.take<unsigned short>((size_t)NT_REFRESH_PIECES * k * 2 * b.ldk);       // each piece twice, side by side
         }
         rp.blocks.push_back(b);
     }
@@ -609,8 +610,8 @@ void upload_refresh(RefreshProgram& rp, Arena& ar, Uploader& up) {
     for (OrthProgram* op : {&rp.orthY, &rp.orthZ}) {
         for (OrthNtPass* p : {&op->ntA, &op->ntE}) {
             if (p->empty()) continue;
-            p->d_st = up.put(p->st, ar); p->d_sx = up.put(p->sx, ar); p->d_sr = up.put(p->sr, ar);
-            upload_nt_stage(p->gram, ar, up); upload_nt_stage(p->ap1, ar, up); upload_nt_stage(p->ap2, ar, up);
+            p->d_st = up.put(p->st, ar); p->d_sx = up.put(p->sx, ar); p->d_sr = up.put(p->sr, ar); p->d_sr2 = up.put(p->sr2, ar);
+            upload_nt_stage(p->gram, ar, up); upload_nt_stage(p->ap, ar, up);
         }
         upload_stage(op->gramA, ar, up); upload_stage(op->qA, ar, up);
         upload_stage(op->gramE, ar, up); upload_stage(op->qE, ar, up);

@@ -109,8 +109,9 @@ struct TransposeBlock {
 hipError_t launch_transpose_bf16(const TransposeBlock* table_dev, int blocks, int max_rows, int max_cols, hipStream_t stream);
 
 // An fp32 matrix X (rows x k, contiguous) as `pieces` bf16 matrices of its transpose: piece p
-// (k x ld_dst, at dst + p * piece_stride elements) holds the p-th term of x = x0 + x1 (+ x2) with
-// x0 = bf16(x), x1 = bf16(x - x0), ...; the padding columns rows .. ld_dst - 1 are written as zeros.
+// (k rows of pitch ld_dst, at dst + p * piece_stride elements) holds the p-th term of
+// x = x0 + x1 (+ x2) with x0 = bf16(x), x1 = bf16(x - x0), ...; columns rows .. up to the next
+// multiple of 8 are written as zeros, nothing beyond (pieces may sit side by side in one row).
 struct SplitBlock {
     const float* X; void* dst;
     long long ld_dst, piece_stride;
@@ -118,8 +119,8 @@ struct SplitBlock {
 };
 hipError_t launch_split_transpose(const SplitBlock* table_dev, int blocks, int max_rows, int max_k, int pieces,
                                   hipStream_t stream);
-// The same pieces without the transposition: piece p (rows x ld_dst, at dst + p * piece_stride) of
-// X (rows x k, contiguous); the padding columns k .. ld_dst - 1 are written as zeros.
+// The same pieces without the transposition: piece p (rows of pitch ld_dst, at dst + p * piece_stride) of
+// X (rows x k, contiguous); columns k .. up to the next multiple of 8 are written as zeros.
 hipError_t launch_split_rows(const SplitBlock* table_dev, int blocks, int max_rows, int max_k, int pieces, hipStream_t stream);
 
 hipError_t launch_shadows(const ShadowBlock* table_dev, int blocks, int max_rows, int max_r, hipStream_t stream);

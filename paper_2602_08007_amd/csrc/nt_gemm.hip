@@ -916,7 +916,8 @@ template <int PIECES>
 __global__ __launch_bounds__(256) void split_transpose_kernel(const SplitBlock* table) {
     const SplitBlock b = table[blockIdx.z];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    if (r0 >= (int)b.ld_dst || c0 >= b.k) return;
+    const int rows8 = (b.rows + 7) / 8 * 8;                         // written width of an output row (zeros beyond `rows`)
+    if (r0 >= rows8 || c0 >= b.k) return;
     __shared__ unsigned short tile[PIECES][64][66];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int i = ty; i < 64; i += 4) {
@@ -934,7 +935,7 @@ __global__ __launch_bounds__(256) void split_transpose_kernel(const SplitBlock* 
     const int px = threadIdx.x & 31, py = threadIdx.x >> 5;
     for (int i = py; i < 64; i += 8) {
         const int c = c0 + i, r = r0 + 2 * px;                       // piece[c][r], piece[c][r + 1]
-        if (c < b.k && r < (int)b.ld_dst) {
+        if (c < b.k && r < rows8) {
 #pragma unroll
             for (int p = 0; p < PIECES; ++p)
                 *(unsigned*)(dst + (long long)p * b.piece_stride + (long long)c * b.ld_dst + r) =
@@ -956,11 +957,11 @@ hipError_t launch_split_transpose(const SplitBlock* table_dev, int blocks, int m
 template <int PIECES>
 __global__ __launch_bounds__(256) void split_rows_kernel(const SplitBlock* table) {
     const SplitBlock b = table[blockIdx.z];
-    const int ldp = (int)b.ld_dst / 2;                                  // element pairs per output row
-    const long long pairs = (long long)b.rows * ldp;
+    const int wp = (b.k + 7) / 8 * 4;                                   // element pairs written per output row (zeros beyond k)
+    const long long pairs = (long long)b.rows * wp;
     unsigned* dst = (unsigned*)b.dst;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < pairs; i += (long long)gridDim.x * 256) {
-        const int r = (int)(i / ldp), c = (int)(i % ldp) * 2;
+        const int r = (int)(i / wp), c = (int)(i % wp) * 2;
         float x0 = (c < b.k) ? b.X[(long long)r * b.k + c] : 0.0f;
         float x1 = (c + 1 < b.k) ? b.X[(long long)r * b.k + c + 1] : 0.0f;
 #pragma unroll
