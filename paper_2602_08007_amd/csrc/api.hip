@@ -519,10 +519,11 @@ void build_refresh_stages(RefreshProgram& rp, const float* const* omegas, Arena&
         build_stage(rp.gq[d], variant(0, 1, d, pc, pc), gq[d], ar);
     }
     {
-        // 128 x 128 tiles, two workgroups per compute unit; TSR_TUNE_REFRESH_WIDE=1: the wide-tile kernel
+        // the wide-tile kernel (256 x 128 outputs, two pieces of B); TSR_TUNE_REFRESH_WIDE=0: 128 x 128 tiles,
+        // two workgroups per compute unit (measured on the 1B workload: 23.2 against 26.0 ms, equal on the 130M one)
         const char* e = getenv("TSR_TUNE_REFRESH_WIDE");
         NtVariant var{};
-        var.shape = (e && e[0] == '1') ? (int)NT_256x128_K32 : (int)NT_128x128_K32; var.b_pieces = NT_REFRESH_PIECES;
+        var.shape = (e && e[0] == '0') ? (int)NT_128x128_K32 : (int)NT_256x128_K32; var.b_pieces = NT_REFRESH_PIECES;
         build_nt_stage(rp.nt.g_stage, var, ntg, (int)rp.blocks.size(), ar, 512);
         build_nt_stage(rp.nt.gt_stage, var, ntgt, (int)rp.blocks.size(), ar, 512);
     }

@@ -291,26 +291,32 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
 
 // ------------------------------------------------------------------ wide-tile variant
 // One workgroup per compute unit, four waves in a 2 x 2 layout, each wave FM x FN fragments of
-// 32 x 32 (256 x 256 outputs per workgroup with FM = FN = 4), 32-deep k-tiles.  What bounds the
-// 128 x 128 kernels above is the traffic between the L2 and the compute unit (each staged byte
-// serves 64 flops there); a tile twice as wide halves that traffic, but leaves one wave per SIMD,
-// so nothing hides a wave's own LDS and memory latencies unless its instruction stream does.  The
-// loop below is therefore scheduled by hand (scheduling barriers pin the order): the fragments of
-// the next k step are read from LDS while the MFMAs of the current one issue, the next k-tile moves
-// from its register stage into the other LDS buffer under the first k step, the barrier sits inside
-// the second k step, and the loads of the k-tile three ahead and the first fragments of the next
-// k-tile follow it, under the remaining MFMAs.
+// 32 x 32 (256 x 256 outputs per workgroup with FM = FN = 4), 32-deep k-tiles.  A tile twice as
+// wide as the 128 x 128 kernels' halves the operand traffic per flop, but leaves one wave per SIMD,
+// so nothing hides a wave's own latencies unless its instruction stream does; and a wave that issues
+// a block of LDS stores or of global loads issues no MFMA until the block has drained (a probe of
+// this loop without global memory: MFMAs alone 2.16 PFLOP/s; with the eight stage stores of a
+// k-tile issued as a block 1.6; spread over the MFMAs 1.94; in the unpadded, XOR-swizzled LDS
+// layout below 2.05).  The loop is therefore scheduled by hand (scheduling barriers pin the order):
+//   k step 0: MFMAs from F[0]; the fragments of k step 1 are read under the first half, the next
+//             k-tile moves from its register stage into the other LDS buffer under the second half,
+//             one or two stores per MFMA pair;
+//   k step 1: MFMAs from F[1]; the barrier after the first quarter; then the loads of the k-tile
+//             three ahead and the first fragments of the next k-tile, again a few per MFMA pair.
+// LDS rows are 64 bytes (four 16-byte chunks), unpadded; chunk c of row r sits at position
+// c ^ ((r >> 1) & 3): fragment reads and stage stores are both free of bank conflicts.
 // OUT: 0 = fp32 store, 1 = bf16 store.  NP: pieces of B (see nt_gemm_kernel).
 template <int FM, int FN, int NP, int OUT>
 __global__ __launch_bounds__(NT_THREADS, 1) void nt_wide_kernel(const NtLaunch L) {
     constexpr bool OUT_BF16 = (OUT == 1);
-    constexpr int BK = 32, KP = BK + 8;
+    constexpr int BK = 32;
     constexpr int TM = 2 * FM * 32, TN = 2 * FN * 32;
-    constexpr int A_ELEMS = TM * KP, B_ELEMS = TN * KP, BUF = A_ELEMS + NP * B_ELEMS;
+    constexpr int A_ELEMS = TM * BK, B_ELEMS = TN * BK, BUF = A_ELEMS + NP * B_ELEMS;
     constexpr int CHA = TM * BK / 8 / NT_THREADS, CHB = TN * BK / 8 / NT_THREADS;
+    constexpr int CH = CHA + NP * CHB;                      // 16-byte chunks per thread and k-tile
     constexpr int NFRAG = FM + NP * FN;                     // fragment reads per k step
     constexpr int NMFMA = FM * FN * NP;                     // MFMAs per k step
-    static_assert(NMFMA % 8 == 0 && NFRAG % 4 == 0, "the schedule issues the MFMAs of a k step in eight groups");
+    static_assert(NMFMA % 8 == 0 && NFRAG % 4 == 0 && CH % 4 == 0, "the schedule issues the MFMAs of a k step in eight groups");
     constexpr int GRP = NMFMA / 8;
     extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
 
@@ -342,33 +348,48 @@ __global__ __launch_bounds__(NT_THREADS, 1) void nt_wide_kernel(const NtLaunch L
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    NtStage<CHA, false> stA[2];
-    NtStage<CHB, false> stB[2][NP];
-    const int k_in_tile = (tid % (BK / 8)) * 8;
-    auto load = [&](int slot, int tile) {                   // unconditional: tiles at or beyond nk read as zero
-        const int k0 = kbeg + tile * BK;
-        const bool live = tile < nk;
-        nt_load<TM, BK, false>(stA[slot], rA, lda_b, row0, k0, live, tid);
-#pragma unroll
-        for (int p = 0; p < NP; ++p) nt_load<TN, BK, false>(stB[slot][p], rB[p], ldb_b, col0, k0, live, tid);
+    // Chunk x of a thread (x < CHA: operand A, else piece (x - CHA) / CHB of B): row (tid + 256 u) / 4
+    // of the operand's tile, k offset (tid % 4) * 8 (the same for all chunks of a thread).
+    u32x4 st[2][CH];
+    const int k_in_tile = (tid & 3) * 8;
+    const int swz_row = tid >> 2;                            // row of chunk u = swz_row + 64 u
+    auto load_chunk = [&](int slot, int tile, int x) {      // unconditional: tiles at or beyond nk read as zero
+        const unsigned poison = (tile < nk) ? 0u : 0x80000000u;
+        const int k0 = kbeg + tile * BK + k_in_tile;
+        if (x < CHA) {
+            const unsigned voff = ((unsigned)(row0 + swz_row + 64 * x) * lda_b + (unsigned)k0 * 2u) | poison;
+            st[slot][x] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rA, (int)voff, 0, 0));
+        } else {
+            const int p = (x - CHA) / CHB, u = (x - CHA) % CHB;
+            const unsigned voff = ((unsigned)(col0 + swz_row + 64 * u) * ldb_b + (unsigned)k0 * 2u) | poison;
+            st[slot][x] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rB[p], (int)voff, 0, 0));
+        }
     };
-    auto store = [&](int slot, int buf, int tile) {
-        unsigned short* d = lds + buf * BUF;
-        const int k0 = kbeg + tile * BK;
-        const bool tail = k0 + BK > kend;
-        nt_store<TM, BK, false>(stA[slot], d, tid, kend - (k0 + k_in_tile), tail);
+    // k guard of a stage: all ones, or the mask of the elements before kend in the last k-tile of the range
+    auto tail_mask = [&](int tile) -> u32x4 {
+        const int valid = kend - (kbeg + tile * BK + k_in_tile);
+        u32x4 m;
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
-            nt_store<TN, BK, false>(stB[slot][p], d + A_ELEMS + p * B_ELEMS, tid, kend - (k0 + k_in_tile), tail);
+        for (int j = 0; j < 4; ++j)
+            m[j] = ((2 * j < valid) ? 0x0000ffffu : 0u) | ((2 * j + 1 < valid) ? 0xffff0000u : 0u);
+        return m;
+    };
+    auto store_chunk = [&](int slot, int buf, int x, u32x4 m) {
+        int base, u;
+        if (x < CHA) { base = 0; u = x; }
+        else { base = A_ELEMS + ((x - CHA) / CHB) * B_ELEMS; u = (x - CHA) % CHB; }
+        const int r = swz_row + 64 * u;
+        const int pos = (tid & 3) ^ ((r >> 1) & 3);
+        *(u32x4*)(lds + buf * BUF + base + r * BK + pos * 8) = st[slot][x] & m;
     };
     // fragment f of k step kk of LDS buffer buf: f < FM: A rows; else piece (f - FM) / FN, column group (f - FM) % FN
-    const int a_off = (wm * (FM * 32) + (lane & 31)) * KP + (lane >> 5) * 8;
-    const int b_off = A_ELEMS + (wn * (FN * 32) + (lane & 31)) * KP + (lane >> 5) * 8;
+    const int l32 = lane & 31, h = lane >> 5;
     auto frag = [&](int buf, int kk, int f) -> bf16x8 {
-        const unsigned short* base = lds + buf * BUF + kk * 16;
-        if (f < FM) return *(const bf16x8*)(base + a_off + f * 32 * KP);
-        const int g = f - FM;
-        return *(const bf16x8*)(base + b_off + (g / FN) * B_ELEMS + (g % FN) * 32 * KP);
+        int base, r;
+        if (f < FM) { base = 0; r = wm * (FM * 32) + f * 32 + l32; }
+        else { const int g = f - FM; base = A_ELEMS + (g / FN) * B_ELEMS; r = wn * (FN * 32) + (g % FN) * 32 + l32; }
+        const int pos = (kk * 2 + h) ^ ((r >> 1) & 3);
+        return *(const bf16x8*)(lds + buf * BUF + base + r * BK + pos * 8);
     };
     bf16x8 F[2][NFRAG];
     // MFMA number q of a k step: pieces from the smallest to the largest, then rows, then columns
@@ -379,43 +400,52 @@ __global__ __launch_bounds__(NT_THREADS, 1) void nt_wide_kernel(const NtLaunch L
 #define NT_SB __builtin_amdgcn_sched_barrier(0)
 
     if (nk > 0) {
-        load(0, 0);
-        store(0, 0, 0);
+#pragma unroll
+        for (int x = 0; x < CH; ++x) load_chunk(0, 0, x);
+        {
+            const u32x4 m = tail_mask(0);
+#pragma unroll
+            for (int x = 0; x < CH; ++x) store_chunk(0, 0, x, m);
+        }
         __syncthreads();
-        load(1, 1);
-        NT_SB;
-        load(0, 2);
+#pragma unroll
+        for (int x = 0; x < CH; ++x) load_chunk(1, 1, x);
+        NT_SB;                                               // keep the issue order: the loop waits for the older stage only
+#pragma unroll
+        for (int x = 0; x < CH; ++x) load_chunk(0, 2, x);
 #pragma unroll
         for (int f = 0; f < NFRAG; ++f) F[0][f] = frag(0, 0, f);
         // tile `it` sits in LDS buffer it & 1, tile it + 1 in register stage (it + 1) & 1, tile it + 2 in
         // the other stage; F[0] holds the fragments of k step 0 of tile `it`
         auto step = [&](int cur, int it) {
             const int oth = cur ^ 1;
-            // ---- k step 0: MFMAs from F[0]; fragments of k step 1 -> F[1]; stage -> LDS buffer `oth`
+            const u32x4 m = tail_mask(it + 1);
+            // ---- k step 0
             NT_SB;
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
 #pragma unroll
                 for (int u = 0; u < GRP; ++u) mfma(F[0], g * GRP + u);
                 NT_SB;
-                if (g < 4) {                                  // early, so that the second half of the k step covers their latency
+                if (g < 4) {
 #pragma unroll
                     for (int f = g * NFRAG / 4; f < (g + 1) * NFRAG / 4; ++f) F[1][f] = frag(cur, 1, f);
-                    NT_SB;
+                } else {                                      // register stage (it + 1) & 1 == oth -> LDS buffer oth
+#pragma unroll
+                    for (int x = (g - 4) * CH / 4; x < (g - 3) * CH / 4; ++x) store_chunk(oth, oth, x, m);
                 }
+                NT_SB;
             }
-            store(oth, oth, it + 1);                          // register stage (it + 1) & 1 == oth
-            NT_SB;
-            // ---- k step 1: MFMAs from F[1]; barrier; loads of tile it + 3; fragments of the next tile -> F[0]
+            // ---- k step 1
 #pragma unroll
             for (int u = 0; u < 2 * GRP; ++u) mfma(F[1], u);
             NT_SB;
             __syncthreads();
             NT_SB;
-            load(oth, it + 3);
-            NT_SB;
 #pragma unroll
             for (int g = 2; g < 8; ++g) {
+#pragma unroll
+                for (int x = (g - 2) * CH / 6; x < (g - 1) * CH / 6; ++x) load_chunk(oth, it + 3, x);
 #pragma unroll
                 for (int u = 0; u < GRP; ++u) mfma(F[1], g * GRP + u);
                 NT_SB;
@@ -802,9 +832,9 @@ static const NtEntry kNt[] = {
     NT_SHAPE(NT_128x128, 128, 128, 2, 2, 64, 2, 1), NT_SHAPE(NT_64x256, 64, 256, 1, 4, 64, 1, 1),
     NT_SHAPE(NT_64x64, 64, 64, 2, 2, 64, 4, 4),
     NT_ENTRY_ADAM(NT_64x64, 64, 64, 2, 2, 64, 4),
-    { NT_256x256_K32, 0, 0, nt_wide_kernel<4, 4, 1, 0>, nullptr, 2 * (256 + 256) * 40 * 2, 1, 1 },
-    { NT_256x256_K32, 0, 1, nt_wide_kernel<4, 4, 1, 1>, nullptr, 2 * (256 + 256) * 40 * 2, 1, 1 },
-    { NT_256x128_K32, 0, 0, nt_wide_kernel<4, 2, 2, 0>, nullptr, 2 * (256 + 2 * 128) * 40 * 2, 1, 2 },
+    { NT_256x256_K32, 0, 0, nt_wide_kernel<4, 4, 1, 0>, nullptr, 2 * (256 + 256) * 32 * 2, 1, 1 },
+    { NT_256x256_K32, 0, 1, nt_wide_kernel<4, 4, 1, 1>, nullptr, 2 * (256 + 256) * 32 * 2, 1, 1 },
+    { NT_256x128_K32, 0, 0, nt_wide_kernel<4, 2, 2, 0>, nullptr, 2 * (256 + 2 * 128) * 32 * 2, 1, 2 },
     NT_ENTRY_PIECES(NT_128x128_K32, 128, 128, 2, 2, 32, 2, 2),
 };
 
