@@ -62,22 +62,16 @@ def build_blocks(w: si.Workload, device):
                              for k in range(w.workers)])
         else:
             G = si.gradient(sig, w.noise, si.stream_key(key, 100), dtype=w.g_dtype)
-        pad = int(os.environ.get("TSR_BENCH_PAD", "0"))      # experiment: extra elements of row pitch for G and W
-        if n % 8 != 0 or pad:
+        if n % 8 != 0:
             # odd widths (5461 in the 1B shapes): row pitch padded to 8 elements, which the bf16
             # kernels' 16-byte loads need; the matrix itself stays m x n (a strided view)
-            ld = (n + 7) // 8 * 8 + pad
+            ld = (n + 7) // 8 * 8
             Gp = torch.zeros(*G.shape[:-1], ld, dtype=G.dtype, device=G.device)
             Gp[..., :n] = G
             G = Gp[..., :n]
         r = w.r
-        W = si.weights(m, n, si.stream_key(key, 7), device=device)
-        if pad:
-            Wp = torch.zeros(m, n + pad, dtype=W.dtype, device=W.device)
-            Wp[:, :n] = W
-            W = Wp[:, :n]
         blocks.append(dict(
-            G=G, W=W,
+            G=G, W=si.weights(m, n, si.stream_key(key, 7), device=device),
             U=torch.empty(m, r, device=device), V=torch.empty(n, r, device=device),
             M=torch.zeros(r, r, device=device), Vm=torch.zeros(r, r, device=device),
             C=torch.empty(r, r, device=device), D=torch.empty(r, r, device=device)))
