@@ -799,6 +799,39 @@ def test_refresh_batched_bf16_gradients(tsr, nt, monkeypatch):
     plan.close()
 
 
+def test_refresh_batched_mixed_gradient_types(tsr):
+    # one plan with bf16 gradients the NT family can read, a bf16 gradient it cannot (odd row pitch:
+    # general kernel) and fp32 gradients (general kernel, three pieces): every block against the oracle
+    shapes = [(192, 256), (256, 192), (333, 200), (200, 333), (320, 320), (130, 264)]
+    dtypes = [torch.bfloat16, torch.float32, torch.bfloat16, torch.float32, torch.bfloat16, torch.bfloat16]
+    r, p, q = 16, 8, 1
+    blocks, host = [], []
+    for i, ((m, n), dt) in enumerate(zip(shapes, dtypes)):
+        b, h = make_blocks([(m, n)], r, 1, dt, si.stream_key(731, i), noise=1e-3)
+        G64, _, _ = si.exact_lowrank(m, n, r, si.stream_key(732, i))
+        G = (G64.float() + si.normal((m, n), si.stream_key(733, i), std=1e-3)).to(dt)
+        if i == 4:
+            # row pitch n + 1 elements: rows are not 16-byte aligned, the block stays on the general kernel
+            Gp = torch.zeros(m, n + 1, dtype=dt, device="cuda")
+            Gp[:, :n] = dev(G)
+            b[0]["G"] = Gp[:, :n]
+        else:
+            b[0]["G"].copy_(G)
+        h[0]["G"] = G[None]
+        blocks += b; host += h
+    plan = tsr.Plan(blocks, with_refresh=True, p=p)
+    omegas = [si.omega(n, r + p, si.stream_key(734, i)) for i, (m, n) in enumerate(shapes)]
+    plan.tsr_refresh_batched([dev(o) for o in omegas], q)
+    torch.cuda.synchronize()
+    for b, h, om, (m, n), dt in zip(blocks, host, omegas, shapes, dtypes):
+        U_ref, V_ref, _ = orc.refresh_rsvd(h["G"][0], om, r, p, q)
+        eu, ev = projector_err(b["U"], U_ref), projector_err(b["V"], V_ref)
+        parity_log("plan refresh mixed types %dx%d %s: projector errors U %.2e V %.2e" % (m, n, str(dt)[6:], eu, ev))
+        assert eu < TOL_F32 and ev < TOL_F32, (m, n, dt, eu, ev)
+        check_orthonormal(b["U"]); check_orthonormal(b["V"])
+    plan.close()
+
+
 @pytest.mark.parametrize("groups", [1, 2, 3])
 def test_refresh_batched_in_groups(tsr, groups, monkeypatch):
     # twelve blocks of mixed shapes and dtypes: the batched refresh cuts them into groups that run
