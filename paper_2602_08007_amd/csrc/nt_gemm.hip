@@ -145,8 +145,9 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
         rB[p] = nt_make_rsrc((const char*)B + (long long)p * pp->b_piece_stride * 2, ((long long)(N - 1) * ldb + k8) * (B_F32 ? 4 : 2));
     const unsigned lda_b = (unsigned)lda * 2u, ldb_b = (unsigned)ldb * (B_F32 ? 4u : 2u);
 
-    // For the read-modify-write epilogue the C tile is fetched into registers before the k-loop
-    // and only consumed after it, so its HBM latency hides behind the whole loop.
+    // For the read-modify-write epilogue the C tile is fetched into registers before the last two
+    // k-tiles are multiplied (see the loop): by then the second register stage has nothing left to
+    // prefetch, so the tile takes its registers, and the k-loop keeps both stages up to that point.
     f32x16 cold[RMW ? FM : 1][RMW ? FN : 1];
     const float out_scale = alpha;
     const bool skip_products = RMW && alpha == 0.0f;
@@ -161,7 +162,7 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
         const int row = row0 + wm * (FM * 32) + i * 32 + (lane >> 5) * 4 + (e >> 2) * 8 + (e & 3);
         return (row < M && col < N) ? (unsigned)row * ldc_b + (unsigned)col * CSZ : 0x80000000u;
     };
-    if constexpr (RMW) {
+    auto load_c = [&]() {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     cold[i][j][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rC, (int)c_voff(i, j, e), 0, 0));
-    }
+    };
     f32x16 acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -180,9 +181,8 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
 
     // Two k-tiles travel in registers ahead of the one being multiplied (ring of two register
     // stages), one more sits in the other LDS buffer: global latency hides behind two k-tiles of
-    // MFMAs per workgroup.  The read-modify-write variant keeps one stage only (its k-loop is
-    // short and its registers hold the C tile).
-    constexpr int NSTAGE = RMW ? 1 : 2;
+    // MFMAs per workgroup.
+    constexpr int NSTAGE = 2;
     NtStage<TM * NT_BK / 8 / NT_THREADS, false> stA[NSTAGE];
     NtStage<TN * NT_BK / 8 / NT_THREADS, B_F32> stB[NSTAGE][NP];
     const int nk = (kend > kbeg && !skip_products) ? (kend - kbeg + NT_BK - 1) / NT_BK : 0;
@@ -245,30 +245,41 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_kernel(const NtLaunc
             // the pair (it, it + 1): multiply LDS buffer 0, move tile it + 1 (stage 1) into buffer 1 and
             // refill that stage with tile it + 3; then the same with the roles exchanged.  With an odd
             // nk the last half-step multiplies a tile of zeros.
-            for (int it = 0; it < nk; it += 2) {
+            if constexpr (!RMW) {
+                for (int it = 0; it < nk; it += 2) {
+                    compute(0);
+                    store(1, 1, it + 1);
+                    __syncthreads();
+                    load(1, it + 3);
+                    compute(1);
+                    store(0, 0, it + 2);
+                    __syncthreads();
+                    load(0, it + 4);
+                }
+            } else {
+                // the last pair is peeled: no loads any more (stage 0 is dead), the C tile is fetched instead
+                int it = 0;
+                for (; it + 2 < nk; it += 2) {
+                    compute(0);
+                    store(1, 1, it + 1);
+                    __syncthreads();
+                    load(1, it + 3);
+                    compute(1);
+                    store(0, 0, it + 2);
+                    __syncthreads();
+                    load(0, it + 4);
+                }
+                __builtin_amdgcn_sched_barrier(0);
                 compute(0);
                 store(1, 1, it + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                load_c();
                 __syncthreads();
-                load(1, it + 3);
                 compute(1);
-                store(0, 0, it + 2);
-                __syncthreads();
-                load(0, it + 4);
-            }
-        } else {
-            // one stage: every load is waited for at the next store anyway, so the steps past the last
-            // k-tile are simply skipped
-            load(0, 0);
-            store(0, 0, 0);
-            __syncthreads();
-            if (nk > 1) load(0, 1);
-            for (int it = 0; it < nk; ++it) {
-                compute(it & 1);
-                if (it + 1 < nk) store(0, (it + 1) & 1, it + 1);
-                __syncthreads();
-                if (it + 2 < nk) load(0, it + 2);
             }
         }
+    } else if constexpr (RMW) {
+        load_c();
     }
 
     // epilogue: lane holds column (lane & 31); rows 8*(e/4) + 4*(lane>>5) + e%4 of each 32x32 tile
