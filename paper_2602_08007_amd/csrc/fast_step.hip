@@ -383,8 +383,12 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
     build_nt_stage(fs.gv[TSR_BF16], NtVariant{s1_shape, 0, 1}, gv[TSR_BF16], nb, ar, 1, gv_p, gv_band);
     // cores up to 256 x 256 are cut into 64 x 64 tiles (enough of them to fill the chip without
     // splitting k); larger cores have enough 128 x 128 tiles
-    build_nt_stage(fs.utp, NtVariant{r_max >= 512 ? NT_128x128 : NT_64x64, 0, 0}, utp, nb, ar,
-                   tune_int("TSR_TUNE_UTP_TILES", 2048, 1, 65536), utp_persist);
+    // ... and above rank 256 the wide-tile kernel without a k split (four 256 x 256 tiles per core:
+    // 0.31 ms against 0.37 ms for 128 x 128 tiles split towards 2048 on the 1B workload; with a
+    // k split the wide tiles lose, 0.58 - 0.87 ms)
+    const bool utp_wide = r_max >= 512 && tune_int("TSR_TUNE_UTP_WIDE", 1, 0, 1) != 0;
+    build_nt_stage(fs.utp, NtVariant{utp_wide ? NT_256x256_K32 : (r_max >= 512 ? NT_128x128 : NT_64x64), 0, 0}, utp, nb, ar,
+                   utp_wide ? 1 : tune_int("TSR_TUNE_UTP_TILES", 2048, 1, 65536), utp_persist && !utp_wide);
     build_nt_stage(fs.ud, NtVariant{ud_shape, 0, 1}, ud, nb, ar, 1);
     build_nt_stage(fs.tvt, NtVariant{tvt_shape, 0, 0}, tvt, nb, ar, 1, false, tvt_band);
 }
