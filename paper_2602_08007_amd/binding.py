@@ -30,9 +30,17 @@ TSR_PREC_SPLIT, TSR_PREC_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(_HERE, "libtsr.so")
 if not os.path.exists(lib_path):
-    raise ImportError(
-        "libtsr.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
-        "(or `python paper_2602_08007_amd/build.py`) first; there is no fallback path")
+    # nothing built yet: compile the library in-tree (hipcc, gfx950); there is no other code path
+    import importlib.util as _ilu
+    _spec = _ilu.spec_from_file_location("_tsr_lib_build", os.path.join(_HERE, "build.py"))
+    _mod = _ilu.module_from_spec(_spec)
+    try:
+        _spec.loader.exec_module(_mod)
+        _mod.build()
+    except Exception as e:  # noqa: BLE001
+        raise ImportError(
+            "libtsr.so is not built and building it failed (%s): run `python -c 'import __graft_entry__ as g; g.build()'`; "
+            "there is no fallback path" % e)
 lib = ctypes.CDLL(lib_path)
 
 _vp, _i, _ll, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_float, ctypes.c_size_t
