@@ -266,7 +266,11 @@ int tsr_plan_bases_changed(tsr_plan* plan);
 int tsr_plan_kernel_path(const tsr_plan* plan);
 
 /* One TSR-Adam step (no refresh) for every block of the plan:
- * project all workers -> average -> Adam on the cores -> lift + apply.  t >= 1. */
+ * project all workers -> average -> Adam on the cores -> lift + apply.  t >= 1.
+ * Once the plan has run a step since its bases last changed (the first such step also rebuilds the
+ * bf16 copies of the bases), a step with stage timing off is kernel launches on `stream` only: no
+ * allocation, no copy, no host synchronisation; it may be recorded into a HIP graph (t and *h are
+ * then fixed in the recorded launches). */
 int tsr_step_batched(tsr_plan* plan, int t, const tsr_hyper* h, void* stream);
 
 /* Refresh (U, V) of every block from worker 0's gradient (randomized SVD, Algorithm 1's

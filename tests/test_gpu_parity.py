@@ -901,6 +901,49 @@ def _bf16_plan_run(tsr, steps, restart_at=None):
     return out
 
 
+def test_step_under_graph_capture_replays_bitwise(tsr):
+    # the batched step is kernel launches on the caller's stream and nothing else (no allocation, no
+    # copy, no host synchronisation), so it can be captured into a HIP graph; three replays, with
+    # eager work and synchronisations between them, must leave exactly what three eager steps leave
+    # (the step count and the hyper-parameters are baked into the captured launches)
+    shapes = [(320, 448), (448, 320), (256, 256), (130, 264)]
+    r = 64
+    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, si.stream_key(911))
+    plan = tsr.Plan(blocks, precision=tsr.TSR_PREC_BF16)
+    assert plan.tsr_plan_kernel_path() == 1
+    for t in (1, 2):                                            # warm: shadows of the bases built, kernels configured
+        plan.tsr_step_batched(t, lr=1e-3, wd=0.01)
+    torch.cuda.synchronize()
+    keys = ("W", "M", "Vm", "C", "D")
+    start = [{k: b[k].clone() for k in keys} for b in blocks]
+
+    def restore():
+        for b, sv in zip(blocks, start):
+            for k in keys:
+                b[k].copy_(sv[k])
+    for _ in range(3):
+        plan.tsr_step_batched(7, lr=1e-3, wd=0.01)
+    torch.cuda.synchronize()
+    eager = [{k: b[k].clone() for k in keys} for b in blocks]
+    restore()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        plan.tsr_step_batched(7, lr=1e-3, wd=0.01)              # binding: launches on torch's current (capturing) stream
+    restore()                                                   # (capture runs nothing; be sure of the start state anyway)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1024, device="cuda")
+    for rep in range(3):
+        graph.replay()
+        scratch.add_(1.0)                                       # eager work between the replays
+        torch.cuda.synchronize()
+    for b, ev in zip(blocks, eager):
+        for k in keys:
+            assert torch.equal(b[k], ev[k]), k
+    plan.close()
+
+
 def test_split_run_five_plus_five_equals_ten_bitwise(tsr):
     # all optimizer state is the caller's flat buffers (W, U, V, m, v and the step count): ten steps
     # in one go and five + checkpoint / restore / new plan + five give identical bits
