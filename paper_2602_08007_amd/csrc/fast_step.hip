@@ -390,7 +390,11 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
     build_nt_stage(fs.utp, NtVariant{utp_wide ? NT_256x256_K32 : (r_max >= 512 ? NT_128x128 : NT_64x64), 0, 0}, utp, nb, ar,
                    utp_wide ? 1 : tune_int("TSR_TUNE_UTP_TILES", 2048, 1, 65536), utp_persist && !utp_wide);
     build_nt_stage(fs.ud, NtVariant{ud_shape, 0, 1}, ud, nb, ar, 1);
-    build_nt_stage(fs.tvt, NtVariant{tvt_shape, 0, 0}, tvt, nb, ar, 1, false, tvt_band);
+    // At rank 512 the weight update runs on the wave-specialised kernel (persistent lists, one workgroup
+    // per compute unit) when every problem fits it: K = 512 and a last column tile of at least four columns.
+    bool tvt_ws = !tvt.empty() && tune_int("TSR_TUNE_TVT_WS", 1, 0, 1) != 0;
+    for (const NtLogical& g : tvt) tvt_ws = tvt_ws && g.K == 512 && (g.N % 128 == 0 || g.N % 128 >= 4);
+    build_nt_stage(fs.tvt, NtVariant{tvt_ws ? (int)NT_128x128_WS : tvt_shape, 0, 0}, tvt, nb, ar, 1, tvt_ws, tvt_band);
 }
 
 void upload_fast_step(FastStep& fs, Arena& ar, Uploader& up) {

@@ -31,7 +31,8 @@ struct NtRange { int begin, end; };          // tiles [begin, end) of one persis
 // With `ranges` set the launch is persistent: workgroup w walks tiles[ranges[w].begin ..
 // ranges[w].end) and keeps its load pipeline running across tile boundaries (the k-tiles of the
 // next tile are on their way while the current tile finishes and is written out); n_tiles is
-// then the number of workgroups.  Not available for the read-modify-write epilogue (beta != 0).
+// then the number of workgroups.  The read-modify-write epilogue (beta != 0) has one persistent
+// form only, NT_128x128_WS.
 struct NtLaunch {
     const NtProblem* probs;
     const NtTile* tiles;
@@ -48,14 +49,16 @@ enum NtShape {
     NT_128x128_K32 = 3,     // 32-deep k-tiles; with two pieces of B: the refresh products
     NT_256x128_K32 = 4,     // wide-tile kernel, two pieces of B only
     NT_256x256_K32 = 5,     // wide-tile kernel, one workgroup per compute unit
-    NT_SHAPES = 6
+    NT_128x128_WS = 6,      // wave-specialised read-modify-write kernel: persistent launches (ranges) of fp32
+                            // C = beta C + alpha A B^T with K == 512 in every problem, nothing else
+    NT_SHAPES = 7
 };
 inline int nt_tile_m(int s) {
-    static const int tm[NT_SHAPES] = {128, 64, 64, 128, 256, 256};
+    static const int tm[NT_SHAPES] = {128, 64, 64, 128, 256, 256, 128};
     return tm[s];
 }
 inline int nt_tile_n(int s) {
-    static const int tn[NT_SHAPES] = {128, 256, 64, 128, 128, 256};
+    static const int tn[NT_SHAPES] = {128, 256, 64, 128, 128, 256, 128};
     return tn[s];
 }
 

@@ -30,6 +30,22 @@ __device__ inline nt_rsrc_t nt_make_rsrc(const void* p, long long bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), (short)0, n, 0x00020000);
 }
 
+// The same from values that are equal in every lane but that the compiler cannot prove so (loaded after
+// the kernel's own global stores): taken from the first lane, so that the descriptor lives in SGPRs.
+__device__ inline int nt_uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ inline nt_rsrc_t nt_make_rsrc_uni(const void* p, long long bytes) {
+    const unsigned long long a = (unsigned long long)p;
+    const unsigned lo = (unsigned)nt_uni((int)(unsigned)a), hi = (unsigned)nt_uni((int)(unsigned)(a >> 32));
+    const int n = nt_uni((bytes > 0x7fffffffLL) ? 0x7fffffff : (int)bytes);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(((unsigned long long)hi << 32) | lo), (short)0, n, 0x00020000);
+}
+
+// Launch tables (written by the host before the launch, never by a kernel) read through the constant
+// address space: with a wave-uniform index these are scalar loads, which have a counter of their own
+// and do not wait for the vector loads in flight.
+#define NT_CONST __attribute__((address_space(4)))
+template <typename T> __device__ inline const NT_CONST T* nt_const(const T* p) { return (const NT_CONST T*)p; }
+
 // rows x K operand, k contiguous; tile rows row0.., k0..k0+BK-1.  Thread t owns chunks
 // c = t + 256*it: row c/(BK/8), k offset (c%(BK/8))*8 (the same k offset for every chunk of a
 // thread, since 256 is a multiple of BK/8).  `live` = false (wave-uniform): the whole tile reads
@@ -686,6 +702,229 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
     }
 }
 
+typedef void (*nt_fn)(const NtLaunch);
+
+// ------------------------------------------------------------------ wave-specialised read-modify-write kernel
+// C = beta C + alpha A B^T by 128 x 128 tiles for a weight matrix C that streams from and to HBM while
+// A and B come out of the L2.  A wave's vector-memory results return in the order the wave asked for
+// them, so a wave that mixes the HBM stream with the operand loads waits for HBM latency at every
+// operand tile.  Here each stream has waves of its own (twelve waves as launched, three per SIMD, one
+// workgroup per compute unit, every wave passes the same barriers):
+//   4 waves    multiply: fragments from LDS, MFMAs, the finished 128 x 128 accumulator tile goes to an
+//              fp32 staging tile in LDS and the waves go straight on to the next tile of the list;
+//   PW waves   stage the operands: global -> NST register stages -> two LDS buffers of 64-deep
+//              k-tiles, NST + 1 k-tiles ahead of the multiplication across tile boundaries;
+//   CW waves   own the C stream: while tile i is multiplied they combine the staged accumulators of
+//              tile i - 1 with that tile's C values (in registers since the pass before) in 16-byte
+//              row pieces, store them, and refill each register with the same piece of tile i's C, which
+//              then has a whole tile's time to arrive.
+// The steps of a tile are unrolled (NK k-tiles per tile, K == 64 NK for every problem of the launch), so
+// every wave's instruction stream is static and the waits count exactly the loads that may stay in flight.
+// Persistent: workgroup w walks tiles[ranges[w].begin .. ranges[w].end).
+constexpr int WS_BK = 64, WS_KP = WS_BK + 8, WS_SP = 132;
+constexpr int WS_OP_ELEMS = 2 * 128 * WS_KP;               // bf16 elements of one LDS operand buffer (A tile, B tile)
+constexpr int WS_LDS_BYTES = 2 * WS_OP_ELEMS * 2 + 128 * WS_SP * 4;
+
+// PW operand waves with NST register stages, CW waves on the C stream.
+template <int NK, int PW, int CW, int NST>
+__global__ __launch_bounds__((4 + PW + CW) * 64, 1) void nt_rmw_ws_kernel(const NtLaunch L) {
+    static_assert(NK >= 2 && NK % 2 == 0 && NK % NST == 0, "the C waves need NK - 1 steps; stage and buffer of a step are static");
+    static_assert((PW == 2 || PW == 4) && (CW == 2 || CW == 4), "row counts below");
+    extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+    float* S = (float*)(lds + 2 * WS_OP_ELEMS);             // staged accumulators, 128 rows of pitch WS_SP
+
+    NtRange range;
+    range.begin = nt_const(L.ranges)[blockIdx.x].begin;
+    range.end = nt_const(L.ranges)[blockIdx.x].end;
+    if (range.begin >= range.end) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ntiles = range.end - range.begin;
+
+    if (wave < 4) {
+        // ------------------------------------------------ multiply
+        const int wm = wave >> 1, wn = wave & 1;
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+        auto compute = [&](int buf) {
+            const unsigned short* sA = lds + buf * WS_OP_ELEMS;
+            const unsigned short* sB = sA + 128 * WS_KP;
+#pragma unroll
+            for (int kk = 0; kk < WS_BK / 16; ++kk) {
+                const int kofs = kk * 16 + (lane >> 5) * 8;
+                bf16x8 fa[2], fb[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) fa[i] = *(const bf16x8*)(sA + (wm * 64 + i * 32 + (lane & 31)) * WS_KP + kofs);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) fb[j] = *(const bf16x8*)(sB + (wn * 64 + j * 32 + (lane & 31)) * WS_KP + kofs);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+        };
+        __syncthreads();                                     // k-tile 0 is in LDS buffer 0
+        for (int ti = 0; ti < ntiles; ++ti) {
+#pragma unroll
+            for (int s = 0; s < NK; ++s) {
+                compute(s & 1);
+                if (s == NK - 1) {
+                    // lane holds column (lane & 31); rows 8 (e / 4) + 4 (lane >> 5) + e % 4 of each 32 x 32 tile
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) {
+                                const int row = wm * 64 + i * 32 + (lane >> 5) * 4 + (e >> 2) * 8 + (e & 3);
+                                S[row * WS_SP + wn * 64 + j * 32 + (lane & 31)] = acc[i][j][e];
+                                acc[i][j][e] = 0.0f;
+                            }
+                }
+                __syncthreads();
+            }
+        }
+    } else if (wave < 4 + PW) {
+        // ------------------------------------------------ operand stages
+        const int ptid = tid - 256;                          // 0 .. 64 PW - 1
+        constexpr int CHP = 16 / PW, RSTEP = 8 * PW;         // chunks per thread and operand; rows between them
+        int lt = range.begin, lk = 0;                        // loader cursor: tile of the list, k-tile of the tile
+        nt_rsrc_t rA, rB;
+        unsigned lda_b, ldb_b;
+        int row0, col0;
+        auto open_tile = [&](int t) {
+            const NT_CONST NtTile* tl = nt_const(L.tiles) + t;
+            const NT_CONST NtProblem* pp = nt_const(L.probs) + nt_uni(tl->prob);
+            const int K = nt_uni(pp->K);
+            rA = nt_make_rsrc_uni(pp->A, ((long long)(pp->M - 1) * pp->lda + K) * 2);
+            rB = nt_make_rsrc_uni(pp->B, ((long long)(pp->N - 1) * pp->ldb + K) * 2);
+            lda_b = (unsigned)nt_uni((int)pp->lda * 2);
+            ldb_b = (unsigned)nt_uni((int)pp->ldb * 2);
+            row0 = nt_uni(tl->tm * 128); col0 = nt_uni(tl->tn * 128);
+        };
+        open_tile(lt);
+        // chunk c = ptid + 64 PW u of an operand tile: row c / 8, k offset (c % 8) * 8 = (ptid % 8) * 8
+        u32x4 sa[NST][CHP], sb[NST][CHP];
+        const int crow = ptid >> 3, ck = (ptid & 7) * 8;
+        auto load_next = [&](int slot) {                     // unconditional: beyond the list the tile reads as zero
+            const unsigned poison = (lt < range.end) ? 0u : 0x80000000u;
+            const unsigned kb = (unsigned)(lk * WS_BK + ck) * 2u;
+#pragma unroll
+            for (int u = 0; u < CHP; ++u) {
+                const unsigned va = ((unsigned)(row0 + crow + RSTEP * u) * lda_b + kb) | poison;
+                sa[slot][u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rA, (int)va, 0, 0));
+            }
+#pragma unroll
+            for (int u = 0; u < CHP; ++u) {
+                const unsigned vb = ((unsigned)(col0 + crow + RSTEP * u) * ldb_b + kb) | poison;
+                sb[slot][u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rB, (int)vb, 0, 0));
+            }
+            if (lt < range.end && ++lk == NK) { lk = 0; if (++lt < range.end) open_tile(lt); }
+        };
+        auto store = [&](int slot, int buf) {
+            unsigned short* d = lds + buf * WS_OP_ELEMS + crow * WS_KP + ck;
+#pragma unroll
+            for (int u = 0; u < CHP; ++u) *(u32x4*)(d + RSTEP * u * WS_KP) = sa[slot][u];
+#pragma unroll
+            for (int u = 0; u < CHP; ++u) *(u32x4*)(d + (128 + RSTEP * u) * WS_KP) = sb[slot][u];
+        };
+        load_next(0);
+        store(0, 0);
+        __syncthreads();
+#pragma unroll
+        for (int q = 1; q <= NST; ++q) {                     // k-tiles 1 .. NST into stages 1 .. NST - 1, 0
+            load_next(q % NST);
+            __builtin_amdgcn_sched_barrier(0);               // keep the issue order: a store waits for the oldest stage only
+        }
+        // step g: k-tile g is multiplied from buffer g & 1; k-tile g + 1 moves from stage (g + 1) % NST
+        // into the other buffer, and that stage is refilled with k-tile g + 1 + NST
+        for (int ti = 0; ti < ntiles; ++ti) {
+#pragma unroll
+            for (int s = 0; s < NK; ++s) {
+                store((s + 1) % NST, (s + 1) & 1);
+                load_next((s + 1) % NST);
+                __syncthreads();
+            }
+        }
+    } else {
+        // ------------------------------------------------ C stream
+        const int wtid = tid - (4 + PW) * 64;                // 0 .. 64 CW - 1
+        constexpr int RP = 2 * CW, NPC = 128 / RP;           // rows per pass of the C waves; pieces per thread
+        const int cq = wtid & 31, rb = wtid >> 5;            // piece c of a thread: row rb + RP c, columns 4 cq .. 4 cq + 3
+        const float alpha = L.alpha, beta = L.beta;
+        // per tile: descriptor and scalars in SGPRs; base = byte offset of this thread's piece 0.  Every piece
+        // is one 16-byte load and one 16-byte store whatever the tile (the instruction stream stays static): in
+        // a tile on the right edge the piece that would cross column N starts at column N - 4 instead and
+        // overlaps its left neighbour, which computes the same values for the shared columns from the same
+        // inputs (N % 128 is 0 or at least 4: the host sends nothing else here); pieces wholly beyond N and
+        // rows beyond M are dropped through a poisoned offset.
+        struct CTile { nt_rsrc_t rc; unsigned base, rowstep; int rows, cs; bool edge; };
+        auto open_c = [&](int t, CTile& ct) {
+            const bool valid = t < range.end;
+            const NT_CONST NtTile* tl = nt_const(L.tiles) + (valid ? t : range.begin);
+            const NT_CONST NtProblem* pp = nt_const(L.probs) + nt_uni(tl->prob);
+            ct.rc = nt_make_rsrc_uni(pp->C, ((long long)(pp->M - 1) * pp->ldc + pp->N) * 4);
+            const unsigned ldc_b = (unsigned)nt_uni((int)pp->ldc * 4);
+            const int row0 = nt_uni(tl->tm * 128), col0 = nt_uni(tl->tn * 128);
+            const int cols = nt_uni(pp->N) - col0;           // columns of C from the tile's corner on
+            ct.edge = cols < 128;
+            const int left = cols - 4 * cq;                  // ... and from this thread's piece on
+            ct.cs = (left >= 4) ? 4 * cq : cols - 4;
+            ct.rows = (valid && left > 0) ? nt_uni(pp->M) - row0 : 0;
+            ct.base = (unsigned)(row0 + rb) * ldc_b + (unsigned)(col0 + ct.cs) * 4u;
+            ct.rowstep = (unsigned)RP * ldc_b;
+        };
+        f32x4 wv[NPC];
+#pragma unroll
+        for (int c = 0; c < NPC; ++c) wv[c] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        CTile prev, cur;
+        open_c(range.end, prev);                             // nothing before the first tile: every store is dropped
+        open_c(range.begin, cur);
+        auto load_piece = [&](const CTile& ct, int c) {
+            const unsigned off = (rb + RP * c < ct.rows) ? ct.base + (unsigned)c * ct.rowstep : 0x80000000u;
+            wv[c] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ct.rc, (int)off, 0, 0));
+        };
+        auto finish_piece = [&](const CTile& ct, int c) {    // staged accumulators + C values of piece c -> memory
+            const float* sp = S + (rb + RP * c) * WS_SP;
+            f32x4 a;
+            if (!ct.edge) {
+                a = *(const f32x4*)(sp + 4 * cq);
+            } else {                                         // a shifted piece is not 16-byte aligned in LDS
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[e] = sp[ct.cs + e];
+            }
+            f32x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (beta == 0.0f) ? alpha * a[e] : alpha * a[e] + beta * wv[c][e];
+            const unsigned off = (rb + RP * c < ct.rows) ? ct.base + (unsigned)c * ct.rowstep : 0x80000000u;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), ct.rc, (int)off, 0, 0);
+        };
+        constexpr int PER = (NPC + NK - 2) / (NK - 1);        // pieces per step, over the first NK - 1 steps of a tile
+        __syncthreads();
+        for (int ti = 0; ti < ntiles; ++ti) {
+#pragma unroll
+            for (int s = 0; s < NK; ++s) {
+#pragma unroll
+                for (int c = s * PER; c < (s + 1) * PER && c < NPC && s < NK - 1; ++c) {
+                    finish_piece(prev, c);
+                    load_piece(cur, c);
+                }
+                __syncthreads();
+            }
+            prev = cur;
+            open_c(range.begin + ti + 1, cur);
+        }
+#pragma unroll
+        for (int c = 0; c < NPC; ++c) finish_piece(prev, c); // the last tile of the list
+    }
+}
+
 // ------------------------------------------------------------------ projection kernel
 // RG: groups of 32 rows of V^T (r / 32); wave w owns groups w RG/4 .. and all TN gradient rows.
 // DEPTH: k-tiles in flight in registers (gradient tile stages and V^T fragment slots).  A
@@ -814,7 +1053,6 @@ hipError_t launch_proj(const ProjItem* items_dev, int n_items, int r, int depth,
 }
 
 // ------------------------------------------------------------------ dispatch
-typedef void (*nt_fn)(const NtLaunch);
 struct NtEntry { int shape, b_f32, out; nt_fn fn; nt_fn persistent; int lds_bytes; int minb; int pieces; };
 
 template <int TM, int TN, int WM, int WN, int BK, bool BF32, int OUT, int MINB>
@@ -851,6 +1089,19 @@ static const NtEntry kNt[] = {
 
 hipError_t launch_nt_gemm(const NtLaunch& L, const NtVariant& v, hipStream_t stream) {
     if (L.n_tiles <= 0) return hipSuccess;
+    if (v.shape == NT_128x128_WS) {
+        if (!L.ranges || v.b_f32 || v.out_bf16 || v.fused_adam || v.b_pieces > 1) return hipErrorInvalidValue;
+        const nt_fn fn = nt_rmw_ws_kernel<8, 4, 4, 4>;
+        constexpr int threads = (4 + 4 + 4) * 64;
+        static thread_local bool configured_ws = false;
+        if (!configured_ws) {
+            hipError_t er = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS_BYTES);
+            if (er != hipSuccess) return er;
+            configured_ws = true;
+        }
+        hipLaunchKernelGGL(fn, dim3(L.n_tiles), dim3(threads), WS_LDS_BYTES, stream, L);
+        return hipGetLastError();
+    }
     const int out = v.fused_adam ? 3 : (v.out_bf16 ? 1 : (L.beta != 0.0f ? 2 : 0));
     for (const NtEntry& e : kNt) {
         if (e.shape == v.shape && e.b_f32 == v.b_f32 && e.out == out && e.pieces == (v.b_pieces > 1 ? v.b_pieces : 1)) {

@@ -697,6 +697,29 @@ def test_bf16_plan_fused_lift_ranks(tsr, r, workers, rows16):
     plan.close()
 
 
+@pytest.mark.parametrize("guard", [True, False])
+def test_bf16_plan_rank512_weight_update_edges(tsr, guard):
+    # Rank 512: the weight update runs on the wave-specialised kernel, which moves W in 16-byte row
+    # pieces.  Column counts that are not multiples of four make the last piece of a row start at
+    # column n - 4 and overlap its neighbour (5461 is the width of the 1B workload; 517 leaves a last
+    # tile of five columns, 1085 one of 61); rows of W are then not 16-byte aligned either, and with
+    # guard = False they follow each other without a gap, so a piece that ran over the end of a row
+    # would corrupt the next one.  Partial row tiles as well (549 and 1541 rows).
+    r = 512
+    shapes = [(549, 1085), (1541, 517), (512, 512), (640, 5461)]
+    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, si.stream_key(633), guard_w=guard, pad_g=True)
+    plan = tsr.Plan(blocks, n_workers=1, precision=tsr.TSR_PREC_BF16)
+    assert plan.tsr_plan_kernel_path() == 1
+
+    def guards(i, t):
+        if guard:
+            assert guards_intact(host[i]["W_full"], *blocks[i]["W"].shape)
+    plan_trajectory(plan, blocks, range(len(shapes)), range(WARM + 1, WARM + 4), TOL_BF16, "rank512-edges-guard%d" % guard,
+                    wd=0.05, next_grads=fresh_gradients(blocks, host), warm_steps=WARM,
+                    bar_d=BAR_D["bf16"], bar_move=BAR_MOVE["bf16"], bar_move_own=BAR_MOVE_OWN["bf16"], after_block=guards)
+    plan.close()
+
+
 @pytest.mark.parametrize("r", [64, 96, 256])
 def test_bf16_plan_adam_in_core_epilogue(tsr, r, monkeypatch):
     # With one worker and cores that U^T P writes whole (no k split), Adam runs in the epilogue
