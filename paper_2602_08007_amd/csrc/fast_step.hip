@@ -275,7 +275,10 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
         bf* UTb = ar.take<bf>((size_t)b.r * ldm);
         bf* Vb = ar.take<bf>((size_t)b.n * ldr);
         bf* VTb = ar.take<bf>((size_t)b.r * ldn);
-        bf* Tb = ar.take<bf>((size_t)b.m * ldr);
+        // The normalized update meets the basis of the shorter side: T = alpha U D (m x r) when m <= n, else
+        // T = alpha V D^T (n x r), and the weight update is W <- beta W + T V^T resp. beta W + U T^T.
+        const bool t_on_v = b.n < b.m && tune_int("TSR_TUNE_T_SHORT_SIDE", 1, 0, 1) != 0;
+        bf* Tb = ar.take<bf>((size_t)(t_on_v ? b.n : b.m) * ldr);
         bf* DTb = ar.take<bf>((size_t)b.r * ldr);
         const bool fits32 = (long long)(b.m + 128) * b.ldw * 4 < (1LL << 31) && (long long)(std::max(b.m, b.n) + 128) * ldr * 2 < (1LL << 31);
         const bool use_lift = fused_lift && lift_supports_rank(b.r) && fits32;
@@ -307,7 +310,8 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
             utp.push_back(NtLogical{UTb, PT, b.C, ldm, ldm, b.r, b.r, b.r, b.m, bi, bi});
         }
         bf* DTf = use_lift ? ar.take<bf>((size_t)b.r * b.r) : nullptr;
-        fs.adam.push_back(AdamTBlock{b.C, b.M, b.Vm, b.D, DTb, DTf, b.r, ldr});
+        bf* Db = (!use_lift && t_on_v) ? ar.take<bf>((size_t)b.r * ldr) : nullptr;
+        fs.adam.push_back(AdamTBlock{b.C, b.M, b.Vm, b.D, DTb, DTf, b.r, ldr, Db});
         if (use_lift) {
             FastStep::LiftGroup* grp = nullptr;
             for (auto& g : fs.lifts) if (g.r == b.r) grp = &g;
@@ -318,8 +322,13 @@ void build_fast_step(FastStep& fs, const std::vector<BlockView>& blocks, int n_w
             for (int row0 = 0; row0 < b.m; row0 += lift_panel_rows(lift_mode))
                 grp->tiles.push_back(LiftTile{bidx, row0, 0, cdiv(b.n, 128)});
         } else {
-            ud.push_back(NtLogical{Ub, DTb, Tb, ldr, ldr, ldr, b.m, b.r, b.r, bi, -1});
-            tvt.push_back(NtLogical{Tb, Vb, b.W, ldr, ldr, b.ldw, b.m, b.n, b.r, bi, -1});
+            if (t_on_v) {
+                ud.push_back(NtLogical{Vb, Db, Tb, ldr, ldr, ldr, b.n, b.r, b.r, bi, -1});
+                tvt.push_back(NtLogical{Ub, Tb, b.W, ldr, ldr, b.ldw, b.m, b.n, b.r, bi, -1});
+            } else {
+                ud.push_back(NtLogical{Ub, DTb, Tb, ldr, ldr, ldr, b.m, b.r, b.r, bi, -1});
+                tvt.push_back(NtLogical{Tb, Vb, b.W, ldr, ldr, b.ldw, b.m, b.n, b.r, bi, -1});
+            }
         }
     }
     // Persistent launch: one list of work items per workgroup, all lists equally heavy (tiles

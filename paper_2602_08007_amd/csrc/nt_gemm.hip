@@ -657,6 +657,7 @@ __global__ __launch_bounds__(NT_THREADS, MINB) void nt_gemm_persistent_kernel(co
                                 d = (mm * sc.inv_c1) / (sqrtf(vv * sc.inv_c2) + sc.eps);
                                 ab.D[idx] = d;
                                 if (!ab.DTf) ((unsigned short*)ab.DTb)[(long long)col * ab.ldt + row] = f32_to_bf16_bits(d);
+                                if (ab.Db) ((unsigned short*)ab.Db)[(long long)row * ab.ldt + col] = f32_to_bf16_bits(d);
                             }
                             dq[e & 3] = f32_to_bf16_bits(d);
                             // D^T in fragment order: the four rows e & 3 = 0..3 of this lane are four

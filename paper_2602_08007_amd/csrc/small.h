@@ -23,6 +23,7 @@ hipError_t launch_adam(const CoreBlock* table_dev, const CoreBlock* single, int 
 struct AdamTBlock {
     const float* C; float* M; float* Vm; float* D;
     void* DTb; void* DTf; int r; long long ldt;
+    void* Db;       // optional: D itself as bf16, r rows of pitch ldt
 };
 hipError_t launch_adam_t(const AdamTBlock* table_dev, int blocks, int max_r, const AdamScalars& s,
                          hipStream_t stream);

@@ -62,6 +62,7 @@ __global__ __launch_bounds__(256) void adam_t_kernel(const AdamTBlock* table, co
         }
         __bf16 h = (__bf16)d;
         tile[i][tx] = __builtin_bit_cast(unsigned short, h);
+        if (b.Db && row < r && col < r) ((unsigned short*)b.Db)[(long long)row * b.ldt + col] = tile[i][tx];
     }
     __syncthreads();
     unsigned short* DT = (unsigned short*)b.DTb;
