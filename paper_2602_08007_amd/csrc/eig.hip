@@ -20,7 +20,8 @@ namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int EIG_THREADS = 1024;
-constexpr int EIG_PARTS = 4;
+constexpr int EIG_PARTS = 4;          // full-matrix pass of the tridiagonalization: pieces of a column sum
+constexpr int EIG_HALF_MIN_K = 384;   // from this size on the pass moves the lower triangle only
 constexpr double EIG_EPS = 2.220446049250313e-16;
 // Solves per eigenvector.  With an eigenvalue good to a few ulps of the spectral radius one solve
 // from a random start already carries the vector to the accuracy the gap allows (its component
@@ -160,7 +161,8 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
     __shared__ double s_w[EIG_MAXK];            //   consecutive reflectors (pending / being formed)
     __shared__ double s_vn[EIG_MAXK];
     __shared__ double s_wn[EIG_MAXK];
-    __shared__ double s_part[EIG_PARTS * EIG_MAXK];
+    __shared__ double s_part[(EIG_THREADS / 128) * EIG_MAXK];   // column sums of the waves, two waves per slot
+    __shared__ double s_prow[EIG_MAXK];                         // row sums
     __shared__ double s_red[EIG_THREADS / 64];
 
     auto block_sum = [&](double v) -> double {
@@ -178,10 +180,18 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
     // beta to T[t][t].  The rank-two update of reflector t-1,  T -= v w^T + w v^T, is still
     // pending when reflector t is formed: column t is corrected on the fly, and one pass over
     // the trailing matrix then applies the pending update and multiplies the updated matrix
-    // with the new v (T is read and written once per reflector; the pass runs at the rate one
-    // CU moves the matrix to and from L2).  That pass has only n1 output sums: each is cut into
-    // pieces so that all threads carry loads.  (v, w) are indexed from t for the pending pair
-    // and from t+1 for the new one.
+    // with the new v.  The pass runs at the rate one CU moves data to and from L2.  Small
+    // matrices (k < EIG_HALF_MIN_K) keep the full symmetric matrix up to date: a thread owns a
+    // piece of a column, whose sum has one target.  Larger ones keep and move the lower
+    // triangle only (half the matrix, half the time; for small ones the short rows make that
+    // form the slower one): the rows are dealt to the waves in turn, a wave sweeps its row up to the
+    // diagonal in strips of 64 columns, and an entry (c, i) below the diagonal adds to two sums
+    // of p = T v, p_i (kept per lane and strip over all rows of the wave, summed over the waves
+    // through LDS at the end) and p_c (summed over the lanes once per row); the upper triangle
+    // is then dead storage from the first pass on.  Either way row t receives reflector t.
+    // (v, w) are indexed from t for the pending pair and from t+1 for the new one.
+    constexpr int STRIPS = (EIG_MAXK + 63) / 64;
+    const bool half = k >= EIG_HALF_MIN_K;
     const int parts = EIG_PARTS;
     const int tpp = nt / parts;
     const int part = tid / tpp, li = tid % tpp;
@@ -192,10 +202,11 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
     for (int t = 0; t + 2 < k; ++t) {
         const int n1 = k - t - 1;
         const double v0 = pv_[0], w0 = pw_[0];
-        // column t below the diagonal, read along row t (T is kept symmetric in full storage)
+        // column t below the diagonal; with the full matrix kept, read along row t (coalesced)
         double psum = 0.0;
         for (int i = tid; i < n1; i += nt) {
-            const double x = T[(size_t)t * k + t + 1 + i] - v0 * pw_[1 + i] - w0 * pv_[1 + i];
+            const double tc = half ? T[(size_t)(t + 1 + i) * k + t] : T[(size_t)t * k + t + 1 + i];
+            const double x = tc - v0 * pw_[1 + i] - w0 * pv_[1 + i];
             nv_[i] = x;
             psum += x * x;
         }
@@ -213,41 +224,104 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_tridiag_kernel(const JacobiBl
         if (skip) { for (int i = tid; i < n1; i += nt) nv_[i] = 0.0; }       // no reflector: only the pending update runs
         __syncthreads();
         if (!skip) { for (int i = tid; i < n1; i += nt) T[(size_t)t * k + t + 1 + i] = nv_[i]; }
-        const int seg = (n1 + parts - 1) / parts;
-        const int c_lo = min(n1, part * seg), c_hi = min(n1, c_lo + seg);
-        // entry (c, i) of the trailing matrix, c in this thread's piece: pending update, then its
-        // term of p = T v (rows read as columns, coalesced over the output index i)
-        for (int i = li; i < n1; i += tpp) {
-            const double vi = pv_[1 + i], wi = pw_[1 + i];
-            double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-            double* col = T + (size_t)(t + 1) * k + (t + 1 + i);
-            int c = c_lo;
-            for (; c + 8 <= c_hi; c += 8) {
-                double x[8];
+        double pv = 0.0;
+        if (half) {
+            // entry (c, i), i <= c, of the trailing matrix: pending update, then its terms of p = T v
+            double colacc[STRIPS];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = col[(size_t)(c + u) * k];
+            for (int q = 0; q < STRIPS; ++q) colacc[q] = 0.0;
+            // (the next row of a wave is fetched while the current one is worked on)
+            auto fetch = [&](int c, double* x) {
+                const double* row = T + (size_t)(t + 1 + c) * k + (t + 1);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    x[u] -= pv_[1 + c + u] * wi + pw_[1 + c + u] * vi;
-                    col[(size_t)(c + u) * k] = x[u];
-                    acc[u] += x[u] * nv_[c + u];
+                for (int q = 0; q < STRIPS; ++q) {
+                    const int i = 64 * q + lane;
+                    x[q] = (c < n1 && i <= c) ? row[i] : 0.0;
+                }
+            };
+            double xa[STRIPS], xb[STRIPS];
+            fetch(wave, xa);
+            auto work = [&](int c, const double* x) {
+                const double vc = pv_[1 + c], wc = pw_[1 + c], nc = nv_[c];
+                double* row = T + (size_t)(t + 1 + c) * k + (t + 1);
+                double rowacc = 0.0;
+#pragma unroll
+                for (int q = 0; q < STRIPS; ++q) {
+                    const int i = 64 * q + lane;
+                    if (i <= c) {
+                        const double xi = x[q] - (vc * pw_[1 + i] + wc * pv_[1 + i]);
+                        row[i] = xi;
+                        colacc[q] += xi * nc;
+                        if (i < c) rowacc += xi * nv_[i];
+                    }
+                }
+                rowacc = eig_wave_sum(rowacc);
+                if (lane == 0) s_prow[c] = rowacc;
+            };
+            for (int c = wave; c < n1; c += 2 * nw) {
+                fetch(c + nw, xb);
+                work(c, xa);
+                if (c + nw < n1) {
+                    fetch(c + 2 * nw, xa);
+                    work(c + nw, xb);
                 }
             }
-            for (; c < c_hi; ++c) {
-                const double x = col[(size_t)c * k] - (pv_[1 + c] * wi + pw_[1 + c] * vi);
-                col[(size_t)c * k] = x;
-                acc[0] += x * nv_[c];
+            // column sums of the waves: the first half of the waves store theirs, the second half add to them
+            if (wave < nw / 2) {
+#pragma unroll
+                for (int q = 0; q < STRIPS; ++q)
+                    if (64 * q + lane < n1) s_part[wave * EIG_MAXK + 64 * q + lane] = colacc[q];
             }
-            s_part[part * EIG_MAXK + i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
-        }
-        __syncthreads();
-        double pv = 0.0;
-        for (int i = tid; i < n1; i += nt) {
-            double a = 0.0;
-            for (int q = 0; q < parts; ++q) a += s_part[q * EIG_MAXK + i];
-            a *= beta;
-            nw_[i] = a;
-            pv += a * nv_[i];
+            __syncthreads();
+            if (wave >= nw / 2) {
+#pragma unroll
+                for (int q = 0; q < STRIPS; ++q)
+                    if (64 * q + lane < n1) s_part[(wave - nw / 2) * EIG_MAXK + 64 * q + lane] += colacc[q];
+            }
+            __syncthreads();
+            for (int i = tid; i < n1; i += nt) {
+                double a = s_prow[i];
+                for (int q = 0; q < nw / 2; ++q) a += s_part[q * EIG_MAXK + i];
+                a *= beta;
+                nw_[i] = a;
+                pv += a * nv_[i];
+            }
+        } else {
+            const int seg = (n1 + parts - 1) / parts;
+            const int c_lo = min(n1, part * seg), c_hi = min(n1, c_lo + seg);
+            // entry (c, i) of the trailing matrix, c in this thread's piece: pending update, then its
+            // term of p = T v (rows read as columns, coalesced over the output index i)
+            for (int i = li; i < n1; i += tpp) {
+                const double vi = pv_[1 + i], wi = pw_[1 + i];
+                double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+                double* col = T + (size_t)(t + 1) * k + (t + 1 + i);
+                int c = c_lo;
+                for (; c + 8 <= c_hi; c += 8) {
+                    double x[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) x[u] = col[(size_t)(c + u) * k];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        x[u] -= pv_[1 + c + u] * wi + pw_[1 + c + u] * vi;
+                        col[(size_t)(c + u) * k] = x[u];
+                        acc[u] += x[u] * nv_[c + u];
+                    }
+                }
+                for (; c < c_hi; ++c) {
+                    const double x = col[(size_t)c * k] - (pv_[1 + c] * wi + pw_[1 + c] * vi);
+                    col[(size_t)c * k] = x;
+                    acc[0] += x * nv_[c];
+                }
+                s_part[part * EIG_MAXK + i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+            }
+            __syncthreads();
+            for (int i = tid; i < n1; i += nt) {
+                double a = 0.0;
+                for (int q = 0; q < parts; ++q) a += s_part[q * EIG_MAXK + i];
+                a *= beta;
+                nw_[i] = a;
+                pv += a * nv_[i];
+            }
         }
         const double kk2 = 0.5 * beta * block_sum(pv);
         for (int i = tid; i < n1; i += nt) nw_[i] -= kk2 * nv_[i];           // w = p - (beta/2)(p.v) v
