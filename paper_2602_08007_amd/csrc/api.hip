@@ -338,7 +338,8 @@ void build_orth_nt(OrthNtPass& pass, const std::vector<RefreshBlock>& blocks, bo
     const int nb = (int)blocks.size();
     build_nt_stage(pass.gram, NtVariant{NT_128x128, 0, 0}, g, nb, ar, 512, false, 0, /*lower_only=*/true);
     NtVariant v2{};
-    v2.shape = NT_128x128_K32; v2.b_pieces = 2;
+    const char* e = getenv("TSR_TUNE_ORTH_WIDE");          // 0: 128 x 128 tiles instead of the wide-tile kernel
+    v2.shape = (e && e[0] == '0') ? (int)NT_128x128_K32 : (int)NT_256x128_K32; v2.b_pieces = 2;
     build_nt_stage(pass.ap, v2, a1, nb, ar, 1);
 }
 
