@@ -1,8 +1,12 @@
-// bf16 NT GEMM for the per-step path on gfx950: C = alpha A B^T + beta C with A (M x K) and
-// B (N x K) both k-contiguous.  256 threads, 64-deep k-tiles, double-buffered LDS (one
-// barrier per k-tile), register prefetch of the next k-tile, v_mfma_f32_32x32x16_bf16 with
-// fp32 accumulation.  For the read-modify-write epilogue (beta != 0) the C tile is fetched
-// before the k-loop so that its HBM latency hides behind the whole loop.
+// bf16 NT GEMMs for the per-step path and the refresh on gfx950: C = alpha A B^T + beta C with A (M x K)
+// and B (N x K) both k-contiguous, v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  Four kernels:
+//   nt_gemm_kernel             128 x 128 (and smaller) tiles, 256 threads, two register stages + two LDS
+//                              buffers; stores, bf16 stores or a read-modify-write epilogue; B in pieces
+//   nt_wide_kernel             256 x 256 / 256 x 128 tiles, one workgroup per compute unit, hand-scheduled
+//   nt_gemm_persistent_kernel  a workgroup walks a list of tiles, optionally with Adam in the epilogue
+//   nt_rmw_ws_kernel           the weight update at rank 512: separate waves for MFMAs, operands and C
+// and the projection kernel (a whole P^T panel in accumulators), the bf16 shadows of the bases and the
+// operand preparation of the refresh products.
 #include "nt_gemm.h"
 
 namespace tsr {
