@@ -924,14 +924,17 @@ def _bf16_plan_run(tsr, steps, restart_at=None):
     return out
 
 
-def test_step_under_graph_capture_replays_bitwise(tsr):
+@pytest.mark.parametrize("r", [64, 512])       # 512: the wide-tile kernels and the wave-specialised weight update
+def test_step_under_graph_capture_replays_bitwise(tsr, r):
     # the batched step is kernel launches on the caller's stream and nothing else (no allocation, no
     # copy, no host synchronisation), so it can be captured into a HIP graph; three replays, with
     # eager work and synchronisations between them, must leave exactly what three eager steps leave
     # (the step count and the hyper-parameters are baked into the captured launches)
-    shapes = [(320, 448), (448, 320), (256, 256), (130, 264)]
-    r = 64
-    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, si.stream_key(911))
+    if r == 64:
+        shapes = [(320, 448), (448, 320), (256, 256), (130, 264)]
+    else:
+        shapes = [(640, 1085), (1541, 520), (512, 512)]
+    blocks, host = make_blocks(shapes, r, 1, torch.bfloat16, si.stream_key(911, r), pad_g=True)
     plan = tsr.Plan(blocks, precision=tsr.TSR_PREC_BF16)
     assert plan.tsr_plan_kernel_path() == 1
     for t in (1, 2):                                            # warm: shadows of the bases built, kernels configured
